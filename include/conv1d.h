@@ -1,0 +1,138 @@
+/*
+ * conv1d.h - C ABI of the MI355X (gfx950) 1D dilated convolution layer.
+ *
+ * The layer is the one defined in Section 2 (Eq. 2) of "Efficient and Generic
+ * 1D Dilated Convolution Layer for Deep Learning": stride 1, one group, no bias
+ * (Section 3, first paragraph: bias is left to the framework), zero padding at
+ * the edges.  Eq. 2 is read the way Algorithms 1 and 2 index it (input column
+ * q + s*d contributes to output column q through tap s, i.e. cross-correlation).
+ *
+ * Geometry shared by every entry point
+ *   N        batch size
+ *   C        input channels
+ *   K        filters (output channels)
+ *   W        input width, NOT including padding
+ *   S        filter width (taps)
+ *   dilation d >= 1, distance between taps along the width
+ *   padding  P >= 0 zeros assumed on each side of the width axis; they are
+ *            implicit and never materialised
+ *   Q        output width = W + 2*P - (S-1)*d   (conv1d_out_width)
+ *
+ * Tensor layouts (all row-major, contiguous, innermost index last)
+ *   x  [N][C][W]   layer input                 dtype
+ *   w  [K][C][S]   filter weights              dtype
+ *   y  [N][K][Q]   layer output                float
+ *   dy [N][K][Q]   gradient w.r.t. the output  dtype
+ *   dx [N][C][W]   gradient w.r.t. the input   float
+ *   dw [K][C][S]   gradient w.r.t. the weights float
+ * `dtype` is CONV1D_FP32 (IEEE binary32) or CONV1D_BF16 (bfloat16, 2 bytes);
+ * products are accumulated in FP32 and outputs are always FP32, never rounded
+ * back to bfloat16.  C, K and W may be odd for either dtype.
+ *
+ * Pointers, ownership, execution
+ *   Every tensor pointer is a DEVICE pointer owned by the caller and must stay
+ *   valid until the work queued on `stream` has finished.  `stream` is a
+ *   hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *   enqueue kernels: they do not allocate, free or synchronise, and they
+ *   OVERWRITE their output (beta = 0 in the notation of Eq. 3).  Inputs and
+ *   outputs must not alias.  float tensors must be 4-byte aligned, bfloat16
+ *   tensors 2-byte aligned; 16-byte alignment (any torch allocation) enables
+ *   the fast kernels.  Calls are thread-safe and re-entrant across streams as
+ *   long as their outputs and workspaces are distinct.
+ *
+ * Errors
+ *   Every int-returning entry point returns CONV1D_OK (0) or a negative
+ *   conv1d_status_t; nothing is thrown and errno is untouched.  On an error
+ *   no kernel has been launched.
+ */
+#ifndef CONV1D_MI355X_H
+#define CONV1D_MI355X_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { CONV1D_FP32 = 0, CONV1D_BF16 = 1 } conv1d_dtype_t;
+
+typedef enum {
+    CONV1D_OK = 0,
+    CONV1D_EINVAL = -1,       /* null pointer, non-positive size, d < 1, P < 0, Q <= 0, bad dtype, misaligned pointer */
+    CONV1D_EUNSUPPORTED = -2, /* a forced kernel variant cannot run this geometry, or sizes overflow 32-bit tile indices */
+    CONV1D_EWORKSPACE = -3,   /* workspace missing or smaller than conv1d_bwd_weight_workspace_bytes() */
+    CONV1D_EHIP = -4          /* the HIP runtime refused a launch (see hipGetLastError) */
+} conv1d_status_t;
+
+/* Kernel families.  AUTO lets the library choose from the geometry; the others
+ * force one family (experiments and tests) and fail with CONV1D_EUNSUPPORTED
+ * when that family cannot run the geometry. */
+typedef enum {
+    CONV1D_VARIANT_AUTO = 0,
+    CONV1D_VARIANT_GENERIC = 1, /* plain FMA, any geometry */
+    CONV1D_VARIANT_SMALLC = 2,  /* MFMA, C and K <= 16, taps held in registers */
+    CONV1D_VARIANT_IGEMM = 3    /* MFMA implicit GEMM over (tap, channel-chunk) */
+} conv1d_variant_t;
+
+typedef enum { CONV1D_PASS_FWD = 0, CONV1D_PASS_BWD_DATA = 1, CONV1D_PASS_BWD_WEIGHT = 2 } conv1d_pass_t;
+
+/* Output width Q = W + 2*padding - (S-1)*dilation (Section 2; Fig. 1 has
+ * W=17, S=3, d=3, P=3 -> Q=17).  Returns a value <= 0 when the geometry is
+ * invalid (any non-positive size, dilation < 1, padding < 0, or no output column). */
+int conv1d_out_width(int W, int S, int dilation, int padding);
+
+/* Forward pass (Eq. 2; Algorithms 1 and 2):
+ *   y[n][k][q] = sum_{c<C} sum_{s<S} x[n][c][q + s*d - P] * w[k][c][s],  x = 0 outside [0,W).
+ * x: device, dtype, N*C*W elements (read).  w: device, dtype, K*C*S elements (read).
+ * y: device, float, N*K*Q elements (overwritten). */
+int conv1d_fwd(const void* x, const void* w, float* y,
+               int N, int C, int K, int W, int S, int dilation, int padding,
+               int dtype, void* stream);
+
+/* Backward-data pass (Section 3.2, Algorithm 3: the adjoint of the forward map in x):
+ *   dx[n][c][i] = sum_{k<K} sum_{s<S} w[k][c][s] * dy[n][k][i + P - s*d],  dy = 0 outside [0,Q).
+ * dy: device, dtype, N*K*Q elements (read).  w: device, dtype, K*C*S (read).
+ * dx: device, float, N*C*W elements (overwritten). */
+int conv1d_bwd_data(const void* dy, const void* w, float* dx,
+                    int N, int C, int K, int W, int S, int dilation, int padding,
+                    int dtype, void* stream);
+
+/* Bytes of device scratch conv1d_bwd_weight needs for this geometry (partial
+ * sums of the first reduction stage).  Returns 0 for an invalid geometry.
+ * The size covers every kernel variant, so a forced variant never needs more. */
+size_t conv1d_bwd_weight_workspace_bytes(int N, int C, int K, int W, int S, int dilation, int padding,
+                                         int dtype);
+
+/* Backward-weight pass (Section 3.3, Algorithm 4: the adjoint of the forward map in w):
+ *   dw[k][c][s] = sum_{n<N} sum_{q<Q} x[n][c][q + s*d - P] * dy[n][k][q].
+ * The sum over (n, q) is split over workgroups; their partial sums go to
+ * `workspace` and a second kernel adds them in a fixed order, so results are
+ * bit-identical from run to run (no floating-point atomics).
+ * x: device, dtype, N*C*W (read).  dy: device, dtype, N*K*Q (read).
+ * dw: device, float, K*C*S (overwritten).
+ * workspace: device, 256-byte aligned, at least workspace_bytes >=
+ * conv1d_bwd_weight_workspace_bytes(...); contents on entry are ignored and
+ * on exit unspecified.  Two calls in flight must not share a workspace. */
+int conv1d_bwd_weight(const void* x, const void* dy, float* dw,
+                      void* workspace, size_t workspace_bytes,
+                      int N, int C, int K, int W, int S, int dilation, int padding,
+                      int dtype, void* stream);
+
+/* Force a kernel family for all later calls of this process (CONV1D_VARIANT_*).
+ * Returns CONV1D_EINVAL for an unknown value. Not meant for production use. */
+int conv1d_set_variant(int variant);
+
+/* Name of the kernel the current variant setting selects for a pass
+ * (conv1d_pass_t) and geometry, e.g. "smallc_mfma_bf16"; "invalid" for a bad
+ * geometry, "unsupported" when a forced variant cannot run it.  The string is
+ * static storage. */
+const char* conv1d_kernel_name(int pass, int N, int C, int K, int W, int S, int dilation, int padding,
+                               int dtype);
+
+/* Human-readable text for a conv1d_status_t (static storage). */
+const char* conv1d_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONV1D_MI355X_H */

@@ -1,0 +1,201 @@
+// C ABI of the conv1d library: argument validation, kernel-family dispatch, status strings.
+// Every entry point only enqueues kernels on the caller's stream.
+#include <atomic>
+
+#include "conv1d_internal.h"
+
+using namespace conv1d;
+
+namespace {
+
+std::atomic<int> g_variant{CONV1D_VARIANT_AUTO};
+
+struct Geom {
+    int N, C, K, W, S, d, P, Q;
+};
+
+bool make_geom(int N, int C, int K, int W, int S, int d, int P, Geom* g) {
+    if (N < 1 || C < 1 || K < 1 || W < 1 || S < 1 || d < 1 || P < 0) return false;
+    const long Q = static_cast<long>(W) + 2L * P - static_cast<long>(S - 1) * d;
+    if (Q < 1 || Q > 0x7fffffffL) return false;
+    // every tensor must be addressable with the 32-bit row arithmetic of the tiled kernels' hosts
+    // (element offsets themselves are 64-bit inside the kernels)
+    *g = Geom{N, C, K, W, S, d, P, static_cast<int>(Q)};
+    return true;
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+CorrProblem fwd_problem(const Geom& g, const void* x, const void* w, float* y, int bf16) {
+    CorrProblem p{};
+    p.in = x; p.wt = w; p.out = y;
+    p.N = g.N; p.R = g.C; p.M = g.K; p.Win = g.W; p.Wout = g.Q; p.S = g.S; p.d = g.d; p.P = g.P;
+    p.w_sm = static_cast<long>(g.C) * g.S; p.w_sr = g.S; p.w_s0 = 0; p.w_ss = 1;
+    p.bf16 = bf16;
+    return p;
+}
+
+// Section 3.2: the same contraction over dy with C and K swapped, taps reversed, P' = (S-1)d - P.
+CorrProblem bwd_data_problem(const Geom& g, const void* dy, const void* w, float* dx, int bf16) {
+    CorrProblem p{};
+    p.in = dy; p.wt = w; p.out = dx;
+    p.N = g.N; p.R = g.K; p.M = g.C; p.Win = g.Q; p.Wout = g.W; p.S = g.S; p.d = g.d;
+    p.P = (g.S - 1) * g.d - g.P;
+    p.w_sm = g.S; p.w_sr = static_cast<long>(g.C) * g.S; p.w_s0 = g.S - 1; p.w_ss = -1;
+    p.bf16 = bf16;
+    return p;
+}
+
+WgradProblem wgrad_problem(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t wsb, int bf16) {
+    WgradProblem p{};
+    p.x = x; p.dy = dy; p.dw = dw; p.ws = ws; p.ws_bytes = wsb;
+    p.N = g.N; p.C = g.C; p.K = g.K; p.W = g.W; p.Q = g.Q; p.S = g.S; p.d = g.d; p.P = g.P;
+    p.bf16 = bf16;
+    return p;
+}
+
+// Which family runs a correlation problem under the current variant setting (-1: none).
+int pick_corr(const CorrProblem& p) {
+    const int v = g_variant.load(std::memory_order_relaxed);
+    switch (v) {
+        case CONV1D_VARIANT_GENERIC: return CONV1D_VARIANT_GENERIC;
+        case CONV1D_VARIANT_SMALLC: return smallc_corr_supported(p) ? v : -1;
+        case CONV1D_VARIANT_IGEMM: return igemm_corr_supported(p) ? v : -1;
+        default: break;
+    }
+    if (smallc_corr_supported(p)) return CONV1D_VARIANT_SMALLC;
+    if (igemm_corr_supported(p)) return CONV1D_VARIANT_IGEMM;
+    return CONV1D_VARIANT_GENERIC;
+}
+
+int pick_wgrad(const WgradProblem& p) {
+    const int v = g_variant.load(std::memory_order_relaxed);
+    switch (v) {
+        case CONV1D_VARIANT_GENERIC: return CONV1D_VARIANT_GENERIC;
+        case CONV1D_VARIANT_SMALLC: return smallc_wgrad_supported(p) ? v : -1;
+        case CONV1D_VARIANT_IGEMM: return igemm_wgrad_supported(p) ? v : -1;
+        default: break;
+    }
+    if (smallc_wgrad_supported(p)) return CONV1D_VARIANT_SMALLC;
+    if (igemm_wgrad_supported(p)) return CONV1D_VARIANT_IGEMM;
+    return CONV1D_VARIANT_GENERIC;
+}
+
+int run_corr(const CorrProblem& p, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    switch (pick_corr(p)) {
+        case CONV1D_VARIANT_GENERIC: e = generic_corr_launch(p, st); break;
+        case CONV1D_VARIANT_SMALLC: e = smallc_corr_launch(p, st); break;
+        case CONV1D_VARIANT_IGEMM: e = igemm_corr_launch(p, st); break;
+        default: return CONV1D_EUNSUPPORTED;
+    }
+    if (e == hipErrorInvalidValue) return CONV1D_EUNSUPPORTED;
+    return e == hipSuccess ? CONV1D_OK : CONV1D_EHIP;
+}
+
+const char* family_name(int fam, int bf16, bool wgrad) {
+    switch (fam) {
+        case CONV1D_VARIANT_GENERIC: return bf16 ? (wgrad ? "generic_wgrad_bf16" : "generic_fma_bf16") : (wgrad ? "generic_wgrad_fp32" : "generic_fma_fp32");
+        case CONV1D_VARIANT_SMALLC: return bf16 ? (wgrad ? "smallc_wgrad_mfma_bf16" : "smallc_mfma_bf16") : (wgrad ? "smallc_wgrad_mfma_fp32" : "smallc_mfma_fp32");
+        case CONV1D_VARIANT_IGEMM: return bf16 ? (wgrad ? "igemm_wgrad_mfma_bf16" : "igemm_mfma_bf16") : (wgrad ? "igemm_wgrad_mfma_fp32" : "igemm_mfma_fp32");
+        default: return "unsupported";
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int conv1d_out_width(int W, int S, int dilation, int padding) {
+    Geom g;
+    if (!make_geom(1, 1, 1, W, S, dilation, padding, &g)) {
+        const long Q = static_cast<long>(W) + 2L * padding - static_cast<long>(S - 1) * dilation;
+        return Q < 0 ? static_cast<int>(Q < -0x7fffffffL ? -0x7fffffffL : Q) : 0;
+    }
+    return g.Q;
+}
+
+int conv1d_fwd(const void* x, const void* w, float* y, int N, int C, int K, int W, int S, int dilation,
+               int padding, int dtype, void* stream) {
+    Geom g;
+    if (!x || !w || !y || (dtype != CONV1D_FP32 && dtype != CONV1D_BF16)) return CONV1D_EINVAL;
+    if (!make_geom(N, C, K, W, S, dilation, padding, &g)) return CONV1D_EINVAL;
+    const size_t ea = dtype == CONV1D_BF16 ? 2 : 4;
+    if (!aligned(x, ea) || !aligned(w, ea) || !aligned(y, 4)) return CONV1D_EINVAL;
+    return run_corr(fwd_problem(g, x, w, y, dtype == CONV1D_BF16), stream);
+}
+
+int conv1d_bwd_data(const void* dy, const void* w, float* dx, int N, int C, int K, int W, int S, int dilation,
+                    int padding, int dtype, void* stream) {
+    Geom g;
+    if (!dy || !w || !dx || (dtype != CONV1D_FP32 && dtype != CONV1D_BF16)) return CONV1D_EINVAL;
+    if (!make_geom(N, C, K, W, S, dilation, padding, &g)) return CONV1D_EINVAL;
+    const size_t ea = dtype == CONV1D_BF16 ? 2 : 4;
+    if (!aligned(dy, ea) || !aligned(w, ea) || !aligned(dx, 4)) return CONV1D_EINVAL;
+    return run_corr(bwd_data_problem(g, dy, w, dx, dtype == CONV1D_BF16), stream);
+}
+
+size_t conv1d_bwd_weight_workspace_bytes(int N, int C, int K, int W, int S, int dilation, int padding, int dtype) {
+    Geom g;
+    if ((dtype != CONV1D_FP32 && dtype != CONV1D_BF16) || !make_geom(N, C, K, W, S, dilation, padding, &g)) return 0;
+    WgradProblem p = wgrad_problem(g, nullptr, nullptr, nullptr, nullptr, 0, dtype == CONV1D_BF16);
+    size_t need = generic_wgrad_workspace(p);
+    if (smallc_wgrad_supported(p)) { size_t b = smallc_wgrad_workspace(p); if (b > need) need = b; }
+    if (igemm_wgrad_supported(p)) { size_t b = igemm_wgrad_workspace(p); if (b > need) need = b; }
+    return (need + 255) & ~static_cast<size_t>(255);
+}
+
+int conv1d_bwd_weight(const void* x, const void* dy, float* dw, void* workspace, size_t workspace_bytes, int N,
+                      int C, int K, int W, int S, int dilation, int padding, int dtype, void* stream) {
+    Geom g;
+    if (!x || !dy || !dw || (dtype != CONV1D_FP32 && dtype != CONV1D_BF16)) return CONV1D_EINVAL;
+    if (!make_geom(N, C, K, W, S, dilation, padding, &g)) return CONV1D_EINVAL;
+    const size_t ea = dtype == CONV1D_BF16 ? 2 : 4;
+    if (!aligned(x, ea) || !aligned(dy, ea) || !aligned(dw, 4)) return CONV1D_EINVAL;
+    const size_t need = conv1d_bwd_weight_workspace_bytes(N, C, K, W, S, dilation, padding, dtype);
+    if (!workspace || workspace_bytes < need) return CONV1D_EWORKSPACE;
+    if (!aligned(workspace, 256)) return CONV1D_EINVAL;
+    WgradProblem p = wgrad_problem(g, x, dy, dw, workspace, workspace_bytes, dtype == CONV1D_BF16);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    switch (pick_wgrad(p)) {
+        case CONV1D_VARIANT_GENERIC: e = generic_wgrad_launch(p, st); break;
+        case CONV1D_VARIANT_SMALLC: e = smallc_wgrad_launch(p, st); break;
+        case CONV1D_VARIANT_IGEMM: e = igemm_wgrad_launch(p, st); break;
+        default: return CONV1D_EUNSUPPORTED;
+    }
+    if (e == hipErrorInvalidValue) return CONV1D_EUNSUPPORTED;
+    return e == hipSuccess ? CONV1D_OK : CONV1D_EHIP;
+}
+
+int conv1d_set_variant(int variant) {
+    if (variant < CONV1D_VARIANT_AUTO || variant > CONV1D_VARIANT_IGEMM) return CONV1D_EINVAL;
+    g_variant.store(variant, std::memory_order_relaxed);
+    return CONV1D_OK;
+}
+
+const char* conv1d_kernel_name(int pass, int N, int C, int K, int W, int S, int dilation, int padding, int dtype) {
+    Geom g;
+    if ((dtype != CONV1D_FP32 && dtype != CONV1D_BF16) || !make_geom(N, C, K, W, S, dilation, padding, &g)) return "invalid";
+    const int bf16 = dtype == CONV1D_BF16;
+    switch (pass) {
+        case CONV1D_PASS_FWD: return family_name(pick_corr(fwd_problem(g, nullptr, nullptr, nullptr, bf16)), bf16, false);
+        case CONV1D_PASS_BWD_DATA: return family_name(pick_corr(bwd_data_problem(g, nullptr, nullptr, nullptr, bf16)), bf16, false);
+        case CONV1D_PASS_BWD_WEIGHT: return family_name(pick_wgrad(wgrad_problem(g, nullptr, nullptr, nullptr, nullptr, 0, bf16)), bf16, true);
+        default: return "invalid";
+    }
+}
+
+const char* conv1d_status_string(int status) {
+    switch (status) {
+        case CONV1D_OK: return "ok";
+        case CONV1D_EINVAL: return "invalid argument (null or misaligned pointer, bad size, dilation, padding or dtype)";
+        case CONV1D_EUNSUPPORTED: return "geometry not supported by the selected kernel variant";
+        case CONV1D_EWORKSPACE: return "workspace missing or too small";
+        case CONV1D_EHIP: return "HIP runtime error on launch";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,76 @@
+// Internal declarations shared by the HIP translation units of the conv1d library.
+// Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/conv1d.h"
+
+namespace conv1d {
+
+// One "correlation problem": the forward pass and the backward-data pass are both
+//   out[n][m][o] = sum_{r<R} sum_{s<S} in[n][r][o + s*d - P] * wt(m, r, s),   in = 0 outside [0, Win)
+// The forward pass (Eq. 2) has in = x, R = C, M = K, P = padding and wt(m,r,s) = w[m][r][s].
+// The backward-data pass (Section 3.2) is the same contraction over dy with the roles of C and K
+// swapped, the taps reversed and P' = (S-1)*d - P:  wt(m,r,s) = w[r][m][S-1-s].
+// Weight element (m, r, s) lives at wt[m*w_sm + r*w_sr + w_s0 + s*w_ss] (in elements).
+struct CorrProblem {
+    const void* in;
+    const void* wt;
+    float* out;
+    int N, R, M, Win, Wout, S, d, P;  // P may be negative for bwd_data when padding > (S-1)*d
+    long w_sm, w_sr;
+    int w_s0, w_ss;
+    int bf16;  // 0: float inputs, 1: bfloat16 inputs
+};
+
+// The backward-weight problem (Section 3.3):
+//   dw[k][c][s] = sum_n sum_q x[n][c][q + s*d - P] * dy[n][k][q]
+struct WgradProblem {
+    const void* x;
+    const void* dy;
+    float* dw;
+    void* ws;
+    size_t ws_bytes;
+    int N, C, K, W, Q, S, d, P;
+    int bf16;
+};
+
+// generic (plain FMA) family: any geometry
+hipError_t generic_corr_launch(const CorrProblem& p, hipStream_t st);
+size_t generic_wgrad_workspace(const WgradProblem& p);
+hipError_t generic_wgrad_launch(const WgradProblem& p, hipStream_t st);
+
+// small-channel MFMA family: R, M <= 16 (C, K <= 16)
+bool smallc_corr_supported(const CorrProblem& p);
+hipError_t smallc_corr_launch(const CorrProblem& p, hipStream_t st);
+bool smallc_wgrad_supported(const WgradProblem& p);
+size_t smallc_wgrad_workspace(const WgradProblem& p);
+hipError_t smallc_wgrad_launch(const WgradProblem& p, hipStream_t st);
+
+// implicit-GEMM MFMA family
+bool igemm_corr_supported(const CorrProblem& p);
+hipError_t igemm_corr_launch(const CorrProblem& p, hipStream_t st);
+bool igemm_wgrad_supported(const WgradProblem& p);
+size_t igemm_wgrad_workspace(const WgradProblem& p);
+hipError_t igemm_wgrad_launch(const WgradProblem& p, hipStream_t st);
+
+// ---- device helpers -------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_float(unsigned short b) {
+    return __uint_as_float(static_cast<unsigned int>(b) << 16);
+}
+
+template <bool BF16>
+__device__ __forceinline__ float load_elem(const void* base, long idx) {
+    if constexpr (BF16) {
+        return bf16_to_float(static_cast<const unsigned short*>(base)[idx]);
+    } else {
+        return static_cast<const float*>(base)[idx];
+    }
+}
+
+inline int cdiv(long a, long b) { return static_cast<int>((a + b - 1) / b); }
+
+}  // namespace conv1d

@@ -1,0 +1,81 @@
+"""The C-ABI library loads, exports what the header declares, and rejects bad arguments
+before touching a GPU.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2104_08002_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return binding.load()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "conv1d.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(conv1d_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_out_width():
+    assert binding.conv1d_out_width(17, 3, 3, 3) == 17          # Fig. 1 geometry
+    assert binding.conv1d_out_width(256, 5, 2, 0) == 248
+    assert binding.conv1d_out_width(60000, 51, 8, 200) == 60000
+    assert binding.conv1d_out_width(5, 4, 3, 0) <= 0
+    assert binding.conv1d_out_width(0, 1, 1, 0) <= 0
+    assert binding.conv1d_out_width(10, 3, 0, 0) <= 0
+    assert binding.conv1d_out_width(10, 3, 1, -1) <= 0
+
+
+def test_status_strings(lib):
+    seen = {binding.conv1d_status_string(s) for s in (0, -1, -2, -3, -4)}
+    assert len(seen) == 5 and binding.conv1d_status_string(0) == "ok"
+    assert "unknown" in binding.conv1d_status_string(-99)
+
+
+def test_argument_validation_without_gpu(lib):
+    fake = ctypes.c_void_p(0x1000)          # never dereferenced: every call below fails validation
+    g = (2, 4, 4, 256, 5, 2, 0)
+    assert lib.conv1d_fwd(None, fake, fake, *g, 0, None) == -1
+    assert lib.conv1d_fwd(fake, None, fake, *g, 0, None) == -1
+    assert lib.conv1d_fwd(fake, fake, None, *g, 0, None) == -1
+    assert lib.conv1d_fwd(fake, fake, fake, *g, 7, None) == -1                      # dtype
+    assert lib.conv1d_fwd(fake, fake, fake, 0, 4, 4, 256, 5, 2, 0, 0, None) == -1   # N
+    assert lib.conv1d_fwd(fake, fake, fake, 2, 4, 4, 256, 5, 0, 0, 0, None) == -1   # dilation
+    assert lib.conv1d_fwd(fake, fake, fake, 2, 4, 4, 256, 5, 2, -1, 0, None) == -1  # padding
+    assert lib.conv1d_fwd(fake, fake, fake, 2, 4, 4, 8, 5, 2, 0, 0, None) == -1     # Q <= 0
+    assert lib.conv1d_fwd(ctypes.c_void_p(0x1002), fake, fake, *g, 0, None) == -1   # misaligned float
+    assert lib.conv1d_fwd(ctypes.c_void_p(0x1001), fake, fake, *g, 1, None) == -1   # misaligned bf16
+    assert lib.conv1d_bwd_data(None, fake, fake, *g, 0, None) == -1
+    assert lib.conv1d_bwd_data(fake, fake, fake, 2, 4, 4, 8, 5, 2, 0, 1, None) == -1
+    assert lib.conv1d_bwd_weight(fake, fake, fake, None, 0, *g, 0, None) == -3
+    assert lib.conv1d_bwd_weight(fake, fake, fake, fake, 16, *g, 0, None) == -3
+    assert lib.conv1d_bwd_weight(None, fake, fake, fake, 1 << 20, *g, 0, None) == -1
+    assert lib.conv1d_bwd_weight(fake, fake, fake, ctypes.c_void_p(0x1010), 1 << 20, *g, 0, None) == -1  # ws alignment
+    assert lib.conv1d_set_variant(99) == -1 and lib.conv1d_set_variant(0) == 0
+
+
+def test_workspace_query_and_kernel_names():
+    assert binding.conv1d_bwd_weight_workspace_bytes(2, 4, 4, 8, 5, 2, 0, 0) == 0   # invalid geometry
+    for dt in (0, 1):
+        b = binding.conv1d_bwd_weight_workspace_bytes(16, 15, 15, 60000, 51, 8, 200, dt)
+        assert b >= 15 * 15 * 51 * 4 and b % 256 == 0
+    assert binding.conv1d_kernel_name(0, 2, 4, 4, 8, 5, 2, 0, 0) == "invalid"
+    binding.conv1d_set_variant(binding.VARIANT_GENERIC)
+    try:
+        assert binding.conv1d_kernel_name(binding.PASS_FWD, 2, 4, 4, 256, 5, 2, 0, 0) == "generic_fma_fp32"
+        assert binding.conv1d_kernel_name(binding.PASS_BWD_WEIGHT, 2, 4, 4, 256, 5, 2, 0, 1) == "generic_wgrad_bf16"
+    finally:
+        binding.conv1d_set_variant(binding.VARIANT_AUTO)

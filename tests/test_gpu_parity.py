@@ -1,0 +1,198 @@
+"""Parity of the HIP path against the FP64 oracle, through the C ABI, on a real MI355X.
+
+Bar (per output element e, A[e] = sum of |products| feeding it):
+    |gpu[e] - oracle[e]| / A[e] <= 1e-5 for fp32 inputs, <= 1e-2 for bf16 inputs,
+and gpu[e] == 0 exactly where A[e] == 0.
+"""
+import numpy as np
+import pytest
+
+from paper_2104_08002_amd import inputs
+from parity_util import TOL, check_full, check_sampled, gpu_passes, to_device
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = {"auto": 0, "generic": 1, "smallc": 2, "igemm": 3}
+PASS_ID = {"fwd": 0, "bwd_data": 1, "bwd_weight": 2}
+
+
+@pytest.fixture(scope="module")
+def binding():
+    import torch
+
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2104_08002_amd import binding as b
+
+    b.load()
+    yield b
+    b.conv1d_set_variant(b.VARIANT_AUTO)
+
+
+def _supported_passes(binding, wl):
+    code = 1 if wl.dtype == "bf16" else 0
+    return tuple(p for p, i in PASS_ID.items()
+                 if binding.conv1d_kernel_name(i, *wl.geometry(), code) != "unsupported")
+
+
+def _run_full(binding, oracle, wl, variant):
+    binding.conv1d_set_variant(VARIANTS[variant])
+    try:
+        passes = _supported_passes(binding, wl)
+        if not passes:
+            pytest.skip(f"variant {variant} does not run this geometry")
+        data = inputs.make_inputs(wl)
+        got = gpu_passes(wl, to_device(wl, data), passes)
+    finally:
+        binding.conv1d_set_variant(0)
+    errs = check_full(oracle, wl, data, got, passes)
+    print(wl.name, variant, errs, flush=True)
+    for p, e in errs.items():
+        assert e <= TOL[wl.dtype], (wl.name, variant, p, e)
+    return passes
+
+
+def _mk(name, N, C, K, W, S, d, P, dtype, base=inputs.TINY, **kw):
+    return inputs.scaled(base, name=name, N=N, C=C, K=K, W=W, S=S, d=d, P=P, dtype=dtype, **kw)
+
+
+# ---- the tiny configuration under every kernel family -------------------------------------------
+@pytest.mark.parametrize("variant", list(VARIANTS))
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_tiny_every_variant(binding, oracle, variant, dtype):
+    wl = inputs.scaled(inputs.TINY, dtype=dtype, name=f"tiny_{dtype}")
+    _run_full(binding, oracle, wl, variant)
+
+
+# ---- small geometries: several tiles, ragged tails, odd channel counts, every dilation ----------
+SMALL = [
+    # name                N  C   K   W     S   d   P
+    ("one_of_each",       1, 1,  1,  1,    1,  1,  0),
+    ("single_column",     2, 3,  2,  9,    3,  4,  0),     # Q = 1
+    ("pad_gt_span",       2, 3,  4,  40,   3,  2,  9),     # P > (S-1)d: bwd_data sees a negative shift
+    ("valid_ragged",      3, 5,  7,  1000, 5,  3,  0),
+    ("same_d1",           2, 15, 15, 1333, 51, 1,  25),
+    ("same_d2",           2, 15, 15, 1500, 51, 2,  50),
+    ("same_d4",           2, 16, 16, 2049, 51, 4,  100),
+    ("genomics_small",    3, 15, 15, 5000, 51, 8,  200),
+    ("same_d16",          2, 15, 15, 3001, 51, 16, 400),
+    ("d3_odd",            2, 15, 13, 2500, 25, 3,  36),
+    ("d5_asym",           2, 9,  16, 1777, 31, 5,  7),
+    ("narrow_S9",         4, 10, 8,  777,  9,  8,  32),
+    ("S1_gemm",           2, 15, 15, 4100, 1,  1,  0),
+    ("even_S",            2, 8,  4,  900,  6,  8,  20),
+    ("c17_k33",           2, 17, 33, 1200, 9,  2,  8),
+    ("c32_k32_d4",        2, 32, 32, 2100, 17, 4,  32),
+    ("c64_k64_d1",        2, 64, 64, 1100, 9,  1,  4),
+    ("c64_k64_d16",       1, 64, 64, 2500, 33, 16, 256),
+    ("c48_k80",           2, 48, 80, 700,  5,  8,  16),
+    ("c256_k256",         1, 256, 256, 600, 9, 4,  16),
+    ("halo_gt_width",     2, 15, 15, 300,  51, 8,  200),   # halo (S-1)d = 400 exceeds W
+    ("long_halo_short_W", 4, 4,  4,  64,   33, 16, 256),
+]
+
+
+@pytest.mark.parametrize("variant", list(VARIANTS))
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_small_geometries(binding, oracle, case, dtype, variant):
+    name, N, C, K, W, S, d, P = case
+    dists = dict(x_dist="sparse_exp", w_dist="normal_fan", dy_dist="normal") if "genomics" in name else {}
+    wl = _mk(f"{name}_{dtype}", N, C, K, W, S, d, P, dtype, seed=inputs.BASE_SEED + 1000 + len(name), **dists)
+    _run_full(binding, oracle, wl, variant)
+
+
+# ---- genomics at full size, the configuration the benchmark times: whole-output comparison ------
+@pytest.mark.parametrize("wl", [inputs.GENOMICS_FP32, inputs.GENOMICS_BF16], ids=lambda w: w.name)
+def test_genomics_full_size(binding, oracle, wl):
+    _run_full(binding, oracle, wl, "auto")
+
+
+# ---- filter-width x dilation sweep at full size: sampled outputs --------------------------------
+def _run_sampled(binding, oracle, wl):
+    data = inputs.make_inputs(wl)
+    got = gpu_passes(wl, to_device(wl, data))
+    errs = check_sampled(oracle, wl, data, got, np.random.default_rng(wl.seed))
+    print(wl.name, errs, flush=True)
+    for p, e in errs.items():
+        assert e <= TOL[wl.dtype], (wl.name, p, e)
+    for k, v in got.items():
+        assert np.isfinite(v).all(), (wl.name, k)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("S", inputs.SWEEP_S)
+@pytest.mark.parametrize("d", inputs.SWEEP_D)
+def test_sweep_full_size_sampled(binding, oracle, S, d, dtype):
+    _run_sampled(binding, oracle, inputs.sweep_point(S, d, dtype))
+
+
+def test_wide_full_size_sampled(binding, oracle):
+    _run_sampled(binding, oracle, inputs.WIDE_BF16)
+
+
+# ---- the sweep and wide shapes at a width the oracle finishes whole ------------------------------
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("S,d", [(5, 1), (9, 16), (17, 2), (33, 4), (51, 8), (51, 16)])
+def test_sweep_reduced_width_full_compare(binding, oracle, S, d, dtype):
+    wl = inputs.scaled(inputs.sweep_point(S, d, dtype), N=2, W=3000 + 7)
+    _run_full(binding, oracle, wl, "auto")
+
+
+def test_wide_reduced_full_compare(binding, oracle):
+    wl = inputs.scaled(inputs.WIDE_BF16, N=2, W=1000)
+    _run_full(binding, oracle, wl, "auto")
+
+
+# ---- backward-weight is bit-reproducible (fixed-order second stage, no float atomics) -----------
+@pytest.mark.parametrize("wl", [inputs.scaled(inputs.GENOMICS_BF16, N=4, W=20000, name="det_bf16"),
+                                inputs.scaled(inputs.GENOMICS_FP32, N=4, W=20000, name="det_fp32"),
+                                inputs.scaled(inputs.sweep_point(17, 4, "bf16"), N=2, W=5000)],
+                         ids=lambda w: w.name)
+def test_bwd_weight_is_deterministic(binding, wl):
+    import torch
+
+    dev = to_device(wl, inputs.make_inputs(wl))
+    runs = []
+    for _ in range(3):
+        runs.append(binding.conv1d_bwd_weight(dev["x"], dev["dy"], wl.S, wl.d, wl.P).clone())
+        torch.cuda.synchronize()
+    assert torch.equal(runs[0], runs[1]) and torch.equal(runs[0], runs[2])
+
+
+# ---- outputs are overwritten, not accumulated into (beta = 0) ------------------------------------
+def test_outputs_are_overwritten(binding, oracle):
+    import torch
+
+    wl = inputs.scaled(inputs.GENOMICS_FP32, N=2, W=3000, name="overwrite")
+    data = inputs.make_inputs(wl)
+    dev = to_device(wl, data)
+    y = torch.full((wl.N, wl.K, wl.Q), float("nan"), device="cuda")
+    dx = torch.full((wl.N, wl.C, wl.W), float("nan"), device="cuda")
+    dw = torch.full((wl.K, wl.C, wl.S), float("nan"), device="cuda")
+    ws = torch.full((binding.conv1d_bwd_weight_workspace_bytes(*wl.geometry(), 0) // 4,), float("nan"), device="cuda")
+    binding.conv1d_fwd(dev["x"], dev["w"], wl.d, wl.P, out=y)
+    binding.conv1d_bwd_data(dev["dy"], dev["w"], wl.W, wl.d, wl.P, out=dx)
+    binding.conv1d_bwd_weight(dev["x"], dev["dy"], wl.S, wl.d, wl.P, out=dw, workspace=ws.view(torch.uint8))
+    torch.cuda.synchronize()
+    got = {"fwd": y.cpu().numpy(), "bwd_data": dx.cpu().numpy(), "bwd_weight": dw.cpu().numpy()}
+    for p, e in check_full(oracle, wl, data, got).items():
+        assert e <= TOL["fp32"], (p, e)
+
+
+# ---- a non-default stream --------------------------------------------------------------------------
+def test_runs_on_callers_stream(binding, oracle):
+    import torch
+
+    wl = inputs.scaled(inputs.GENOMICS_BF16, N=2, W=4000, name="stream")
+    data = inputs.make_inputs(wl)
+    dev = to_device(wl, data)
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(st):
+        y = binding.conv1d_fwd(dev["x"], dev["w"], wl.d, wl.P)
+        dx = binding.conv1d_bwd_data(dev["dy"], dev["w"], wl.W, wl.d, wl.P)
+        dw = binding.conv1d_bwd_weight(dev["x"], dev["dy"], wl.S, wl.d, wl.P)
+    st.synchronize()
+    got = {"fwd": y.cpu().numpy(), "bwd_data": dx.cpu().numpy(), "bwd_weight": dw.cpu().numpy()}
+    for p, e in check_full(oracle, wl, data, got).items():
+        assert e <= TOL["bf16"], (p, e)
