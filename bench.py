@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of the 1D dilated convolution hot path on one MI355X.
+
+A "step" is one forward + one backward-data + one backward-weight pass of the layer on the
+genomics-shaped workload (N=16, C=K=15, W=60000, S=51, d=8, same padding), inputs resident in
+HBM.  Prints ONE JSON line:  metric/value = TFLOP/s over the whole step (3 passes x 2*N*C*K*S*Q
+nominal FLOPs), plus per-pass figures, a roofline object for the slowest kernel (timed with
+HIP events on the launch stream) and the FP64 oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"bf16": 2500.0, "fp32": 157.3}      # dense MFMA TFLOP/s, MI355X
+HBM_PEAK_GBS = 8000.0
+PASSES = ("fwd", "bwd_data", "bwd_weight")
+
+
+def algorithmic_bytes(wl, p):
+    """Bytes one launch must move: read each input once, write each fp32 output once."""
+    e = 2 if wl.dtype == "bf16" else 4
+    x, dy, w = wl.N * wl.C * wl.W, wl.N * wl.K * wl.Q, wl.K * wl.C * wl.S
+    if p == "fwd":
+        return x * e + w * e + dy * 4
+    if p == "bwd_data":
+        return dy * e + w * e + x * 4
+    return x * e + dy * e + w * 4
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="genomics_bf16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--variant", type=int, default=0, help="force a kernel family (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(the path shards over the batch axis; see DESIGN.md)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2104_08002_amd import binding, inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    binding.load()
+    binding.conv1d_set_variant(args.variant)
+    wl = inputs.WORKLOADS[args.workload]
+    data = inputs.make_inputs(wl)
+    dev = {}
+    for k in ("x", "w", "dy"):
+        if wl.dtype == "bf16":
+            dev[k] = torch.from_numpy(data[k + "_bits"].view(np.int16)).cuda().view(torch.bfloat16)
+        else:
+            dev[k] = torch.from_numpy(data[k]).cuda()
+    code = 1 if wl.dtype == "bf16" else 0
+    y = torch.empty((wl.N, wl.K, wl.Q), dtype=torch.float32, device="cuda")
+    dx = torch.empty((wl.N, wl.C, wl.W), dtype=torch.float32, device="cuda")
+    dw = torch.empty((wl.K, wl.C, wl.S), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(256, binding.conv1d_bwd_weight_workspace_bytes(*wl.geometry(), code)), dtype=torch.uint8,
+                     device="cuda")
+
+    launch = {
+        "fwd": lambda: binding.conv1d_fwd(dev["x"], dev["w"], wl.d, wl.P, out=y),
+        "bwd_data": lambda: binding.conv1d_bwd_data(dev["dy"], dev["w"], wl.W, wl.d, wl.P, out=dx),
+        "bwd_weight": lambda: binding.conv1d_bwd_weight(dev["x"], dev["dy"], wl.S, wl.d, wl.P, out=dw, workspace=ws),
+    }
+
+    def step():
+        for p in PASSES:
+            launch[p]()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = 3 * wl.flops / (ms_per_step * 1e-3) / 1e12
+
+    # per-pass device time: HIP events on the stream the kernels are launched on (torch's current stream)
+    per_pass = {}
+    for p in PASSES:
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        for a, b in evs:
+            a.record()
+            launch[p]()
+            b.record()
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in evs)
+        avg = sum(ms) / len(ms)
+        tf = wl.flops / (avg * 1e-3) / 1e12
+        gbs = algorithmic_bytes(wl, p) / (avg * 1e-3) / 1e9
+        per_pass[p] = {
+            "kernel": binding.conv1d_kernel_name(PASSES.index(p), *wl.geometry(), code),
+            "avg_us": round(avg * 1e3, 2), "median_us": round(ms[len(ms) // 2] * 1e3, 2),
+            "tflops": round(tf, 2), "frac_mfma_peak": round(tf / PEAK[wl.dtype], 4),
+            "algorithmic_GBps": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+        }
+    dom = max(PASSES, key=lambda p: per_pass[p]["avg_us"])
+    # which roof bounds the dominant kernel: time at MFMA peak vs time at HBM peak for its algorithmic work
+    t_mfma = wl.flops / (PEAK[wl.dtype] * 1e12)
+    t_hbm = algorithmic_bytes(wl, dom) / (HBM_PEAK_GBS * 1e9)
+    if t_hbm > t_mfma:
+        roof = {"bound": "hbm", "achieved": per_pass[dom]["algorithmic_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": per_pass[dom]["frac_hbm_peak"]}
+    else:
+        roof = {"bound": "mfma", "achieved": per_pass[dom]["tflops"], "peak": PEAK[wl.dtype], "unit": "TFLOP/s",
+                "frac": per_pass[dom]["frac_mfma_peak"]}
+    roof.update({"kernel": per_pass[dom]["kernel"], "pass": dom, "avg_us": per_pass[dom]["avg_us"], "traffic": None})
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        oracle.build()
+        x64, w64, dy64 = (data[k].astype(np.float64) for k in ("x", "w", "dy"))
+        tt = {}
+        t = time.perf_counter(); oracle.fwd(x64, w64, wl.d, wl.P); tt["fwd"] = time.perf_counter() - t
+        t = time.perf_counter(); oracle.bwd_data(dy64, w64, wl.W, wl.d, wl.P); tt["bwd_data"] = time.perf_counter() - t
+        t = time.perf_counter(); oracle.bwd_weight(x64, dy64, wl.S, wl.d, wl.P); tt["bwd_weight"] = time.perf_counter() - t
+        tot = sum(tt.values())
+        cpu = {"value": round(3 * wl.flops / tot / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+               "sample": f"the whole {wl.name} workload once (N={wl.N}), fp64 direct summation, one run per pass: "
+                         + ", ".join(f"{k} {v:.2f}s" for k, v in tt.items())}
+
+    out = {
+        "metric": "TFLOP/s per step (fwd + bwd_data + bwd_weight), 1 MI355X", "value": round(value, 3), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "N": wl.N, "C": wl.C, "K": wl.K, "W": wl.W, "S": wl.S, "dilation": wl.d,
+                   "padding": wl.P, "Q": wl.Q, "gflop_per_pass": round(wl.flops / 1e9, 3), "outputs": "fp32"},
+        "frac_mfma_peak": round(value / PEAK[wl.dtype], 4),
+        "per_pass": per_pass, "roofline": roof, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
