@@ -50,6 +50,15 @@ bool smallc_wgrad_supported(const WgradProblem& p);
 size_t smallc_wgrad_workspace(const WgradProblem& p);
 hipError_t smallc_wgrad_launch(const WgradProblem& p, hipStream_t st);
 
+// bf16 members of the small-channel family (own translation unit)
+bool smallc_bf16_corr_supported(const CorrProblem& p);
+hipError_t smallc_bf16_corr_launch(const CorrProblem& p, hipStream_t st);
+bool smallc_bf16_wgrad_supported(const WgradProblem& p);
+size_t smallc_bf16_wgrad_workspace(const WgradProblem& p);
+hipError_t smallc_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st);
+// fixed-order sum of per-workgroup partial tiles ws[(wg*S + s)*256 + k*16 + c] into dw[k][c][s]
+hipError_t smallc_wgrad_reduce_launch(const float* ws, float* dw, int K, int C, int S, int nwg, hipStream_t st);
+
 // implicit-GEMM MFMA family
 bool igemm_corr_supported(const CorrProblem& p);
 hipError_t igemm_corr_launch(const CorrProblem& p, hipStream_t st);

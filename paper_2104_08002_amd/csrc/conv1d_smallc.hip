@@ -1,4 +1,4 @@
-// Small-channel MFMA kernels (C, K <= 16), FP32 inputs.
+// Small-channel MFMA kernels (C, K <= 16): family dispatch and the FP32 members.
 //
 // The forward / backward-data contraction (Eq. 2; Section 3.2) for one sample is the product of a
 // 16 x (taps*channels) weight matrix with a (taps*channels) x width matrix whose rows are shifted
@@ -79,16 +79,36 @@ __global__ __launch_bounds__(WAVES * 64) void smallc_corr_f32_kernel(CorrProblem
         const int ob = wave * T * 16;
         const float* bptr = win + kb * LPS + ob + li;
         const float* aptr = wfrag + lane;
+        // operands of tap s+1 are fetched from LDS while the MFMAs of tap s run
+        float a_cur[RC], b_cur[RC][T];
+#pragma unroll
+        for (int cc = 0; cc < RC; ++cc) {
+            a_cur[cc] = aptr[cc * 64];
+#pragma unroll
+            for (int j = 0; j < T; ++j) b_cur[cc][j] = bptr[cc * 4 * LPS + j * 16];
+        }
         for (int s = 0; s < p.S; ++s) {
-            const float* bs = bptr + s * p.d;
+            const int sn = s + 1 < p.S ? s + 1 : s;
+            const float* bs = bptr + sn * p.d;
+            float a_nxt[RC], b_nxt[RC][T];
 #pragma unroll
             for (int cc = 0; cc < RC; ++cc) {
-                const float a = aptr[(s * RC + cc) * 64];
+                a_nxt[cc] = aptr[(sn * RC + cc) * 64];
 #pragma unroll
-                for (int j = 0; j < T; ++j) {
-                    const float b = bs[cc * 4 * LPS + j * 16];
-                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[j], 0, 0, 0);
-                }
+                for (int j = 0; j < T; ++j) b_nxt[cc][j] = bs[cc * 4 * LPS + j * 16];
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of the MFMA block
+#pragma unroll
+            for (int cc = 0; cc < RC; ++cc) {
+#pragma unroll
+                for (int j = 0; j < T; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[cc], b_cur[cc][j], acc[j], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int cc = 0; cc < RC; ++cc) {
+                a_cur[cc] = a_nxt[cc];
+#pragma unroll
+                for (int j = 0; j < T; ++j) b_cur[cc][j] = b_nxt[cc][j];
             }
         }
 #pragma unroll
@@ -162,14 +182,13 @@ __global__ __launch_bounds__(256) void smallc_wgrad_f32_kernel(WgradProblem p, i
     float* xt = lds + 16 * LQS;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15;
     const int kb = lane >> 4;
     const float* __restrict__ x = static_cast<const float*>(p.x);
     const float* __restrict__ dy = static_cast<const float*>(p.dy);
-    const int halo = (p.S - 1) * p.d;
-    const int LX = QC + halo;
-    const int nt = (p.S - wave + 3) / 4;  // taps of this wave
+    const int LX = QC + (4 * NT - 1) * p.d;  // every tap slot a wave may read, valid tap or not
+    const int nt = (p.S - wave + 3) / 4;     // real taps of this wave; slots beyond compute unused sums
 
     f32x4 acc[NT];
 #pragma unroll
@@ -203,15 +222,23 @@ __global__ __launch_bounds__(256) void smallc_wgrad_f32_kernel(WgradProblem p, i
         const float* ap = dyt + li * LQS + kb;
         const float* bp = xt + li * LXS + kb + wave * p.d;
         const int dstep = 4 * p.d;
-        for (int t = 0; t < QC; t += 4) {
-            const float a = ap[t];
+        // operands of k-step t+4 are fetched from LDS while the MFMAs of k-step t run
+        float a_cur = ap[0], b_cur[NT];
 #pragma unroll
-            for (int i = 0; i < NT; ++i) {
-                if (i < nt) {
-                    const float b = bp[t + i * dstep];
-                    acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[i], 0, 0, 0);
-                }
-            }
+        for (int i = 0; i < NT; ++i) b_cur[i] = bp[i * dstep];
+        for (int t = 0; t < QC; t += 4) {
+            const int tn = t + 4 < QC ? t + 4 : t;
+            const float a_nxt = ap[tn];
+            float b_nxt[NT];
+#pragma unroll
+            for (int i = 0; i < NT; ++i) b_nxt[i] = bp[tn + i * dstep];
+            __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of the MFMA block
+#pragma unroll
+            for (int i = 0; i < NT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur, b_cur[i], acc[i], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            a_cur = a_nxt;
+#pragma unroll
+            for (int i = 0; i < NT; ++i) b_cur[i] = b_nxt[i];
         }
     }
     float* ws = static_cast<float*>(p.ws) + static_cast<long>(blockIdx.x) * p.S * 256;
@@ -250,7 +277,7 @@ WgradF32Plan wgrad_f32_plan(const WgradProblem& p) {
     WgradF32Plan pl{};
     pl.ok = false;
     if (p.C > 16 || p.K > 16 || p.S > 4 * kWgradNT) return pl;
-    const long halo = static_cast<long>(p.S - 1) * p.d;
+    const long halo = static_cast<long>(4 * kWgradNT - 1) * p.d;
     int QC = 256;
     // row strides == 2 (mod 32) words: the 16 rows x 4 columns of an operand fragment hit distinct banks
     auto pad = [](long v) { return (v + 31) / 32 * 32 + 2; };
@@ -272,13 +299,19 @@ WgradF32Plan wgrad_f32_plan(const WgradProblem& p) {
 
 }  // namespace
 
+hipError_t smallc_wgrad_reduce_launch(const float* ws, float* dw, int K, int C, int S, int nwg, hipStream_t st) {
+    const int kcs = K * C * S;
+    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(cdiv(kcs, 256)), dim3(256), 0, st, ws, dw, K, C, S, nwg);
+    return hipGetLastError();
+}
+
 bool smallc_corr_supported(const CorrProblem& p) {
-    if (p.bf16) return false;
+    if (p.bf16) return smallc_bf16_corr_supported(p);
     return corr_f32_plan(p).ok;
 }
 
 hipError_t smallc_corr_launch(const CorrProblem& p, hipStream_t st) {
-    if (p.bf16) return hipErrorInvalidValue;
+    if (p.bf16) return smallc_bf16_corr_launch(p, st);
     const CorrF32Plan pl = corr_f32_plan(p);
     if (!pl.ok) return hipErrorInvalidValue;
     switch (pl.RC) {
@@ -290,19 +323,19 @@ hipError_t smallc_corr_launch(const CorrProblem& p, hipStream_t st) {
 }
 
 bool smallc_wgrad_supported(const WgradProblem& p) {
-    if (p.bf16) return false;
+    if (p.bf16) return smallc_bf16_wgrad_supported(p);
     return wgrad_f32_plan(p).ok;
 }
 
 size_t smallc_wgrad_workspace(const WgradProblem& p) {
-    if (p.bf16) return 0;
+    if (p.bf16) return smallc_bf16_wgrad_workspace(p);
     const WgradF32Plan pl = wgrad_f32_plan(p);
     if (!pl.ok) return 0;
     return static_cast<size_t>(pl.grid) * p.S * 256 * sizeof(float);
 }
 
 hipError_t smallc_wgrad_launch(const WgradProblem& p, hipStream_t st) {
-    if (p.bf16) return hipErrorInvalidValue;
+    if (p.bf16) return smallc_bf16_wgrad_launch(p, st);
     const WgradF32Plan pl = wgrad_f32_plan(p);
     if (!pl.ok) return hipErrorInvalidValue;
     auto kern = smallc_wgrad_f32_kernel<kWgradNT>;
@@ -312,10 +345,7 @@ hipError_t smallc_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     hipLaunchKernelGGL(kern, dim3(pl.grid), dim3(256), pl.lds_bytes, st, p, pl.chunks_per_row, pl.nchunks, pl.QC, pl.LQS, pl.LXS);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int kcs = p.K * p.C * p.S;
-    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(cdiv(kcs, 256)), dim3(256), 0, st, static_cast<const float*>(p.ws),
-                       p.dw, p.K, p.C, p.S, pl.grid);
-    return hipGetLastError();
+    return smallc_wgrad_reduce_launch(static_cast<const float*>(p.ws), p.dw, p.K, p.C, p.S, pl.grid, st);
 }
 
 }  // namespace conv1d

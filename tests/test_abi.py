@@ -79,3 +79,14 @@ def test_workspace_query_and_kernel_names():
         assert binding.conv1d_kernel_name(binding.PASS_BWD_WEIGHT, 2, 4, 4, 256, 5, 2, 0, 1) == "generic_wgrad_bf16"
     finally:
         binding.conv1d_set_variant(binding.VARIANT_AUTO)
+
+
+def test_headline_workloads_dispatch_to_mfma_kernels():
+    """The benchmarked genomics shapes must not silently run on the plain-FMA fallback."""
+    from paper_2104_08002_amd import inputs
+
+    binding.conv1d_set_variant(binding.VARIANT_AUTO)
+    for wl in (inputs.GENOMICS_FP32, inputs.GENOMICS_BF16):
+        code = 1 if wl.dtype == "bf16" else 0
+        names = [binding.conv1d_kernel_name(i, *wl.geometry(), code) for i in range(3)]
+        assert all("mfma" in n for n in names), names
