@@ -29,49 +29,105 @@ constexpr int kNumCU = 256;
 //   wfrag[S*RC][64]   weights in MFMA A-operand order: entry (step = s*RC + cc, lane = m + 16*kb)
 //                     is wt(m, 4*cc + kb, s)  (zero outside M x R)
 //   win[4*RC][LPS]    the input window, row r, column i <-> input position G0 + i
-template <int RC, int T, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void smallc_corr_f32_kernel(CorrProblem p, int tiles_per_row, int ntiles, int LPS) {
+// A workgroup walks tiles blockIdx.x, +gridDim.x, ...; the window of the next tile is fetched
+// from global memory into registers (16-byte slots, MAXS per thread) while the MFMAs of the
+// current tile run, and written to LDS after the barrier that ends the current tile.
+template <int RC, int T, int WAVES, int MAXS>
+__global__ __launch_bounds__(WAVES * 64) void smallc_corr_f32_kernel(CorrProblem p, int tiles_per_row, int ntiles, int LPS, int LP4,
+                                                                     int fast, int raw_in_lds) {
     extern __shared__ float lds[];
     constexpr int TQ = WAVES * T * 16;
+    constexpr int NTH = WAVES * 64;
     const int nsteps = p.S * RC;
     float* wfrag = lds;
     float* win = lds + nsteps * 64;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15;  // row of A / column of B and D
     const int kb = lane >> 4;  // k index of A/B; row block of D
     const float* __restrict__ in = static_cast<const float*>(p.in);
     const float* __restrict__ wt = static_cast<const float*>(p.wt);
+    const int nslots = 4 * RC * LP4;
 
-    for (int e = tid; e < nsteps * 64; e += WAVES * 64) {
+    auto load_slot = [&](int n, int G0, int e) -> f32x4 {
+        const int r = e / LP4;
+        const int g = G0 + 4 * (e - r * LP4);
+        f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (r < p.R) {
+            const float* row = in + (static_cast<long>(n) * p.R + r) * p.Win;
+            if (fast && g >= 0 && g + 4 <= p.Win) {
+                v = *reinterpret_cast<const f32x4*>(row + g);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (g + j >= 0 && g + j < p.Win) v[j] = row[g + j];
+            }
+        }
+        return v;
+    };
+    auto lds_slot = [&](int e) -> f32x4* {
+        const int r = e / LP4;
+        return reinterpret_cast<f32x4*>(win + r * LPS + 4 * (e - r * LP4));
+    };
+
+    f32x4 pre[MAXS];
+    int tile = blockIdx.x;
+    {
+        const int n = tile / tiles_per_row;
+        const int G0 = (tile - n * tiles_per_row) * TQ - p.P;
+#pragma unroll
+        for (int k = 0; k < MAXS; ++k) {
+            const int e = tid + k * NTH;
+            pre[k] = load_slot(n, G0, e < nslots ? e : nslots - 1);
+        }
+    }
+
+    // weights: coalesced copy of the raw tensor into LDS (aliasing the window), then reorder
+    const int nW = p.M * p.R * p.S;
+    if (raw_in_lds) {
+        if ((reinterpret_cast<uintptr_t>(wt) & 15) == 0) {
+            for (int e = tid; e < nW / 4; e += NTH) reinterpret_cast<f32x4*>(win)[e] = reinterpret_cast<const f32x4*>(wt)[e];
+            for (int e = (nW / 4) * 4 + tid; e < nW; e += NTH) win[e] = wt[e];
+        } else {
+            for (int e = tid; e < nW; e += NTH) win[e] = wt[e];
+        }
+        __syncthreads();
+    }
+    for (int e = tid; e < nsteps * 64; e += NTH) {
         const int step = e >> 6, l = e & 63;
         const int m = l & 15, r = 4 * (step % RC) + (l >> 4), s = step / RC;
         float v = 0.f;
-        if (m < p.M && r < p.R) v = wt[m * p.w_sm + r * p.w_sr + p.w_s0 + s * p.w_ss];
+        if (m < p.M && r < p.R) {
+            const long idx = m * p.w_sm + r * p.w_sr + p.w_s0 + s * p.w_ss;
+            v = raw_in_lds ? win[idx] : wt[idx];
+        }
         wfrag[e] = v;
     }
 
-    const int halo = (p.S - 1) * p.d;
-    const int LP = TQ + halo;
-    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    while (tile < ntiles) {
         const int n = tile / tiles_per_row;
         const int O0 = (tile - n * tiles_per_row) * TQ;
-        const int G0 = O0 - p.P;
-        __syncthreads();  // previous tile's readers are done (and wfrag is written on the first pass)
-        for (int r = 0; r < 4 * RC; ++r) {
-            float* row = win + r * LPS;
-            if (r < p.R) {
-                const float* src = in + (static_cast<long>(n) * p.R + r) * p.Win;
-                for (int i = tid; i < LP; i += WAVES * 64) {
-                    const int g = G0 + i;
-                    row[i] = (g >= 0 && g < p.Win) ? src[g] : 0.f;
-                }
-            } else {
-                for (int i = tid; i < LP; i += WAVES * 64) row[i] = 0.f;
+        __syncthreads();  // readers of the previous window (or of the raw weights) are done
+#pragma unroll
+        for (int k = 0; k < MAXS; ++k) {
+            const int e = tid + k * NTH;
+            if (e < nslots) *lds_slot(e) = pre[k];
+        }
+        for (int e = tid + MAXS * NTH; e < nslots; e += NTH) *lds_slot(e) = load_slot(n, O0 - p.P, e);
+        __syncthreads();
+
+        const int next = tile + gridDim.x;
+        if (next < ntiles) {
+            const int nn = next / tiles_per_row;
+            const int G0n = (next - nn * tiles_per_row) * TQ - p.P;
+#pragma unroll
+            for (int k = 0; k < MAXS; ++k) {
+                const int e = tid + k * NTH;
+                pre[k] = load_slot(nn, G0n, e < nslots ? e : nslots - 1);
             }
         }
-        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
 
         f32x4 acc[T];
 #pragma unroll
@@ -122,21 +178,22 @@ __global__ __launch_bounds__(WAVES * 64) void smallc_corr_f32_kernel(CorrProblem
                 }
             }
         }
+        tile = next;
     }
 }
 
 struct CorrF32Plan {
-    int RC, LPS, tiles_per_row, ntiles;
+    int RC, LPS, LP4, tiles_per_row, ntiles, fast, raw_in_lds;
     size_t lds_bytes;
     bool ok;
 };
 
-constexpr int kCorrT = 4, kCorrWaves = 8;
+constexpr int kCorrT = 4, kCorrWaves = 8, kCorrMaxS = 8;
 
 CorrF32Plan corr_f32_plan(const CorrProblem& p) {
     CorrF32Plan pl{};
     pl.ok = false;
-    if (p.R > 16 || p.M > 16) return pl;
+    if (p.bf16 || p.R > 16 || p.M > 16) return pl;
     constexpr int TQ = kCorrWaves * kCorrT * 16;
     pl.RC = (p.R + 3) / 4;
     const long halo = static_cast<long>(p.S - 1) * p.d;
@@ -146,37 +203,44 @@ CorrF32Plan corr_f32_plan(const CorrProblem& p) {
     const long bytes = (static_cast<long>(p.S) * pl.RC * 64 + 4L * pl.RC * LPS) * 4;
     if (bytes > kLdsBudget) return pl;
     pl.LPS = static_cast<int>(LPS);
+    pl.LP4 = static_cast<int>((LP + 3) / 4);
     pl.tiles_per_row = cdiv(p.Wout, TQ);
     const long nt = static_cast<long>(p.N) * pl.tiles_per_row;
     if (nt > 0x7fffffffL) return pl;
     pl.ntiles = static_cast<int>(nt);
     pl.lds_bytes = static_cast<size_t>(bytes);
+    // 16-byte window loads need every row start, the window origin and the base pointer aligned
+    pl.fast = (p.Win % 4 == 0) && (((p.P % 4) + 4) % 4 == 0) && (reinterpret_cast<uintptr_t>(p.in) % 16 == 0);
+    pl.raw_in_lds = static_cast<long>(p.M) * p.R * p.S <= 4L * pl.RC * LPS;
     pl.ok = true;
     return pl;
 }
 
 template <int RC>
 hipError_t corr_f32_launch_rc(const CorrProblem& p, const CorrF32Plan& pl, hipStream_t st) {
-    auto kern = smallc_corr_f32_kernel<RC, kCorrT, kCorrWaves>;
+    auto kern = smallc_corr_f32_kernel<RC, kCorrT, kCorrWaves, kCorrMaxS>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        static_cast<int>(pl.lds_bytes));
     if (e != hipSuccess) return e;
     const int grid = pl.ntiles < kNumCU ? pl.ntiles : kNumCU;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kCorrWaves * 64), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kCorrWaves * 64), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.LP4,
+                       pl.fast, pl.raw_in_lds);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------
 // FP32 backward-weight
 // ------------------------------------------------------------------------------------------------
-// Workgroup of 4 waves; wave v owns taps s = v, v+4, v+8, ... (at most NT of them) and keeps one
-// 16 x 16 accumulator tile per tap.  The workgroup walks chunks of QC output columns of one sample:
+// Workgroup of 4 waves; wave v owns taps s = v, v+4, v+8, ... (NT slots) and keeps one 16 x 16
+// accumulator tile per tap.  The workgroup walks chunks of QC output columns of one sample:
 //   dyt[16][LQS]  rows = filters, column j <-> q = Qs + j
 //   xt [16][LXS]  rows = channels, column i <-> input position Qs - P + i
 // One MFMA k-step covers 4 positions: A = dy[m][q0 + kb], B = x[c][q0 + kb + s*d - P].
+// The next chunk is fetched into registers (16-byte slots) while the current one is consumed.
 // Partial sums: ws[(wg * S + s) * 256 + m * 16 + c].
-template <int NT>
-__global__ __launch_bounds__(256) void smallc_wgrad_f32_kernel(WgradProblem p, int chunks_per_row, int nchunks, int QC, int LQS, int LXS) {
+template <int NT, int MAXS>
+__global__ __launch_bounds__(256) void smallc_wgrad_f32_kernel(WgradProblem p, int chunks_per_row, int nchunks, int QC, int LQS, int LXS,
+                                                               int LX4, int fast) {
     extern __shared__ float lds[];
     float* dyt = lds;
     float* xt = lds + 16 * LQS;
@@ -187,38 +251,79 @@ __global__ __launch_bounds__(256) void smallc_wgrad_f32_kernel(WgradProblem p, i
     const int kb = lane >> 4;
     const float* __restrict__ x = static_cast<const float*>(p.x);
     const float* __restrict__ dy = static_cast<const float*>(p.dy);
-    const int LX = QC + (4 * NT - 1) * p.d;  // every tap slot a wave may read, valid tap or not
-    const int nt = (p.S - wave + 3) / 4;     // real taps of this wave; slots beyond compute unused sums
+    const int nt = (p.S - wave + 3) / 4;  // real taps of this wave; slots beyond compute unused sums
+    const int Q4 = QC / 4;
+    const int ndy = 16 * Q4;
+    const int nslots = ndy + 16 * LX4;
+
+    // slot e: first the dy rows (Q4 slots each), then the x rows (LX4 slots each)
+    auto load_slot = [&](int n, int Qs, int e) -> f32x4 {
+        const bool is_x = e >= ndy;
+        const int e2 = is_x ? e - ndy : e;
+        const int per_row = is_x ? LX4 : Q4;
+        const int r = e2 / per_row;
+        const int rows = is_x ? p.C : p.K;
+        const int width = is_x ? p.W : p.Q;
+        const int g = (is_x ? Qs - p.P : Qs) + 4 * (e2 - r * per_row);
+        f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (r < rows) {
+            const float* row = (is_x ? x : dy) + (static_cast<long>(n) * rows + r) * width;
+            if (fast && g >= 0 && g + 4 <= width) {
+                v = *reinterpret_cast<const f32x4*>(row + g);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (g + j >= 0 && g + j < width) v[j] = row[g + j];
+            }
+        }
+        return v;
+    };
+    auto lds_slot = [&](int e) -> f32x4* {
+        const bool is_x = e >= ndy;
+        const int e2 = is_x ? e - ndy : e;
+        const int per_row = is_x ? LX4 : Q4;
+        const int r = e2 / per_row;
+        return reinterpret_cast<f32x4*>((is_x ? xt + r * LXS : dyt + r * LQS) + 4 * (e2 - r * per_row));
+    };
 
     f32x4 acc[NT];
 #pragma unroll
     for (int i = 0; i < NT; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
+    f32x4 pre[MAXS];
+    int chunk = blockIdx.x;
+    {
         const int n = chunk / chunks_per_row;
         const int Qs = (chunk - n * chunks_per_row) * QC;
-        const int G0 = Qs - p.P;
+#pragma unroll
+        for (int k = 0; k < MAXS; ++k) {
+            const int e = tid + k * 256;
+            pre[k] = load_slot(n, Qs, e < nslots ? e : nslots - 1);
+        }
+    }
+    while (chunk < nchunks) {
+        const int n = chunk / chunks_per_row;
+        const int Qs = (chunk - n * chunks_per_row) * QC;
         __syncthreads();
-        for (int r = 0; r < 16; ++r) {
-            float* drow = dyt + r * LQS;
-            float* xrow = xt + r * LXS;
-            if (r < p.K) {
-                const float* src = dy + (static_cast<long>(n) * p.K + r) * p.Q;
-                for (int i = tid; i < QC; i += 256) drow[i] = (Qs + i < p.Q) ? src[Qs + i] : 0.f;
-            } else {
-                for (int i = tid; i < QC; i += 256) drow[i] = 0.f;
-            }
-            if (r < p.C) {
-                const float* src = x + (static_cast<long>(n) * p.C + r) * p.W;
-                for (int i = tid; i < LX; i += 256) {
-                    const int g = G0 + i;
-                    xrow[i] = (g >= 0 && g < p.W) ? src[g] : 0.f;
-                }
-            } else {
-                for (int i = tid; i < LX; i += 256) xrow[i] = 0.f;
+#pragma unroll
+        for (int k = 0; k < MAXS; ++k) {
+            const int e = tid + k * 256;
+            if (e < nslots) *lds_slot(e) = pre[k];
+        }
+        for (int e = tid + MAXS * 256; e < nslots; e += 256) *lds_slot(e) = load_slot(n, Qs, e);
+        __syncthreads();
+        const int next = chunk + gridDim.x;
+        if (next < nchunks) {
+            const int nn = next / chunks_per_row;
+            const int Qn = (next - nn * chunks_per_row) * QC;
+#pragma unroll
+            for (int k = 0; k < MAXS; ++k) {
+                const int e = tid + k * 256;
+                pre[k] = load_slot(nn, Qn, e < nslots ? e : nslots - 1);
             }
         }
-        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+
         const float* ap = dyt + li * LQS + kb;
         const float* bp = xt + li * LXS + kb + wave * p.d;
         const int dstep = 4 * p.d;
@@ -240,6 +345,7 @@ __global__ __launch_bounds__(256) void smallc_wgrad_f32_kernel(WgradProblem p, i
 #pragma unroll
             for (int i = 0; i < NT; ++i) b_cur[i] = b_nxt[i];
         }
+        chunk = next;
     }
     float* ws = static_cast<float*>(p.ws) + static_cast<long>(blockIdx.x) * p.S * 256;
 #pragma unroll
@@ -252,47 +358,67 @@ __global__ __launch_bounds__(256) void smallc_wgrad_f32_kernel(WgradProblem p, i
     }
 }
 
-// dw[k][c][s] = sum over workgroups, in workgroup order, of ws[(wg*S + s)*256 + k*16 + c]
+// Second stage of the backward-weight pass: dw[k][c][s] = sum over workgroups g of
+// ws[(g*S + s)*256 + k*16 + c], always in the same order: 16 contiguous groups of workgroups are
+// summed left to right by 16 threads each, then the 16 group sums are added left to right.
 __global__ __launch_bounds__(256) void smallc_wgrad_reduce_kernel(const float* __restrict__ ws, float* __restrict__ dw, int K, int C, int S, int nwg) {
-    const int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= K * C * S) return;
-    const int s = e % S;
-    const int c = (e / S) % C;
-    const int k = e / (S * C);
-    const float* src = ws + s * 256 + k * 16 + c;
+    __shared__ float part[16][17];
+    const int el = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int e = blockIdx.x * 16 + el;  // index into one workgroup's S*256 partial tile
+    const int total = S * 256;
+    const int per = (nwg + 15) / 16;
+    const int g0 = grp * per, g1 = min(nwg, g0 + per);
     float t = 0.f;
-    for (int g = 0; g < nwg; ++g) t += src[static_cast<long>(g) * S * 256];
-    dw[e] = t;
+    if (e < total) {
+        const float* src = ws + e;
+#pragma unroll 8
+        for (int g = g0; g < g1; ++g) t += src[static_cast<long>(g) * total];
+    }
+    part[grp][el] = t;
+    __syncthreads();
+    if (grp == 0 && e < total) {
+        float sum = part[0][el];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) sum += part[i][el];
+        const int s = e >> 8, k = (e >> 4) & 15, c = e & 15;
+        if (k < K && c < C) dw[(k * C + c) * S + s] = sum;
+    }
 }
 
 struct WgradF32Plan {
-    int QC, LQS, LXS, chunks_per_row, nchunks, grid;
+    int QC, LQS, LXS, LX4, chunks_per_row, nchunks, grid, fast;
     size_t lds_bytes;
     bool ok;
 };
 
-constexpr int kWgradNT = 13;
+constexpr int kWgradNT = 13, kWgradMaxS = 16;
 
 WgradF32Plan wgrad_f32_plan(const WgradProblem& p) {
     WgradF32Plan pl{};
     pl.ok = false;
-    if (p.C > 16 || p.K > 16 || p.S > 4 * kWgradNT) return pl;
-    const long halo = static_cast<long>(4 * kWgradNT - 1) * p.d;
-    int QC = 256;
-    // row strides == 2 (mod 32) words: the 16 rows x 4 columns of an operand fragment hit distinct banks
-    auto pad = [](long v) { return (v + 31) / 32 * 32 + 2; };
-    long LQS = pad(QC), LXS = pad(QC + halo);
-    long bytes = 16 * (LQS + LXS) * 4;
+    if (p.bf16 || p.C > 16 || p.K > 16 || p.S > 4 * kWgradNT) return pl;
+    const long halo = static_cast<long>(4 * kWgradNT - 1) * p.d;  // every tap slot a wave may read
+    const int QC = 256;
+    // row strides == 2 (mod 32) words (and a multiple of 4 words would break that): 16-byte slot
+    // stores need 4-word alignment, so the stride is 4 (mod 32) words instead: 8 rows x 4 columns
+    // of an operand fragment then cover 32 distinct banks
+    auto pad = [](long v) { return (v + 31) / 32 * 32 + 4; };
+    const long LQS = pad(QC), LXS = pad(QC + halo);
+    const long bytes = 16 * (LQS + LXS) * 4;
     if (bytes > kLdsBudget) return pl;
     pl.QC = QC;
     pl.LQS = static_cast<int>(LQS);
     pl.LXS = static_cast<int>(LXS);
+    pl.LX4 = static_cast<int>((QC + halo + 3) / 4);
     pl.chunks_per_row = cdiv(p.Q, QC);
     const long nc = static_cast<long>(p.N) * pl.chunks_per_row;
     if (nc > 0x7fffffffL) return pl;
     pl.nchunks = static_cast<int>(nc);
-    pl.grid = pl.nchunks < 2 * kNumCU ? pl.nchunks : 2 * kNumCU;
+    const int per_cu = bytes <= kLdsBudget / 2 ? 2 : 1;
+    pl.grid = pl.nchunks < per_cu * kNumCU ? pl.nchunks : per_cu * kNumCU;
     pl.lds_bytes = static_cast<size_t>(bytes);
+    pl.fast = (p.W % 4 == 0) && (p.Q % 4 == 0) && (p.P % 4 == 0) && (reinterpret_cast<uintptr_t>(p.x) % 16 == 0) &&
+              (reinterpret_cast<uintptr_t>(p.dy) % 16 == 0);
     pl.ok = true;
     return pl;
 }
@@ -300,8 +426,7 @@ WgradF32Plan wgrad_f32_plan(const WgradProblem& p) {
 }  // namespace
 
 hipError_t smallc_wgrad_reduce_launch(const float* ws, float* dw, int K, int C, int S, int nwg, hipStream_t st) {
-    const int kcs = K * C * S;
-    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(cdiv(kcs, 256)), dim3(256), 0, st, ws, dw, K, C, S, nwg);
+    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(cdiv(S * 256, 16)), dim3(256), 0, st, ws, dw, K, C, S, nwg);
     return hipGetLastError();
 }
 
@@ -338,11 +463,12 @@ hipError_t smallc_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     if (p.bf16) return smallc_bf16_wgrad_launch(p, st);
     const WgradF32Plan pl = wgrad_f32_plan(p);
     if (!pl.ok) return hipErrorInvalidValue;
-    auto kern = smallc_wgrad_f32_kernel<kWgradNT>;
+    auto kern = smallc_wgrad_f32_kernel<kWgradNT, kWgradMaxS>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        static_cast<int>(pl.lds_bytes));
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(pl.grid), dim3(256), pl.lds_bytes, st, p, pl.chunks_per_row, pl.nchunks, pl.QC, pl.LQS, pl.LXS);
+    hipLaunchKernelGGL(kern, dim3(pl.grid), dim3(256), pl.lds_bytes, st, p, pl.chunks_per_row, pl.nchunks, pl.QC, pl.LQS, pl.LXS,
+                       pl.LX4, pl.fast);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     return smallc_wgrad_reduce_launch(static_cast<const float*>(p.ws), p.dw, p.K, p.C, p.S, pl.grid, st);

@@ -40,28 +40,103 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast
 // k-slot layout of one MFMA (lane = li + 16*kb, element j of the lane's 8):
 //   channel r = 8*(kb & 1) + j,  tap s = p + NP*(kb >> 1)
 // LDS: plane h = kb & 1 holds channels 8h..8h+7; slot (h*LPS + i) <-> input position G0 + i.
-template <int NP, int G, int T>
-__global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrProblem p, int tiles_per_row, int ntiles, int LPS, int fast) {
+template <int NP, int G, int T, int MAXT>
+__global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrProblem p, int tiles_per_row, int ntiles, int LPS, int fast,
+                                                                          int raw_in_lds) {
     extern __shared__ u32x4 lds4[];
     constexpr int TQ = kWaves * T * 16;
+    constexpr int NTH = kWaves * 64;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15;
     const int kb = lane >> 4;
     const unsigned short* __restrict__ in = static_cast<const unsigned short*>(p.in);
     const unsigned short* __restrict__ wt = static_cast<const unsigned short*>(p.wt);
     const int d = (G > 0) ? 16 / (G > 0 ? G : 1) : p.d;
+    const int LP = TQ + (2 * NP - 1) * d;
+    const int LP2 = (LP + 1) >> 1;
+    const int ntasks = 2 * LP2;
 
-    // weight slices in A-operand order, built once in LDS, then held in registers
-    for (int e = tid; e < NP * 64; e += kWaves * 64) {
+    // One staging task = 8 channels (half h) x 2 adjacent positions: 8 dwords in, two 16-byte
+    // [position][8 channels] slots out.  The dwords of the next tile are fetched while the MFMAs
+    // of the current tile run.
+    struct Task { unsigned v[8]; };
+    auto load_task = [&](int n, int G0, int task) -> Task {
+        const int h = task >= LP2 ? 1 : 0;
+        const int g = G0 + 2 * (task - h * LP2);
+        Task t;
+        if (fast && g >= 0 && g + 1 < p.Win) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int r = 8 * h + j;
+                t.v[j] = r < p.R ? *reinterpret_cast<const unsigned*>(in + (static_cast<long>(n) * p.R + r) * p.Win + g) : 0u;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int r = 8 * h + j;
+                unsigned lo = 0u, hi = 0u;
+                if (r < p.R) {
+                    const unsigned short* row = in + (static_cast<long>(n) * p.R + r) * p.Win;
+                    if (g >= 0 && g < p.Win) lo = row[g];
+                    if (g + 1 >= 0 && g + 1 < p.Win) hi = row[g + 1];
+                }
+                t.v[j] = lo | (hi << 16);
+            }
+        }
+        return t;
+    };
+    auto store_task = [&](int task, const Task& t) {
+        const int h = task >= LP2 ? 1 : 0;
+        const int pp = task - h * LP2;
+        u32x4 ev, od;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            ev[q] = __builtin_amdgcn_perm(t.v[2 * q + 1], t.v[2 * q], kPermLo);
+            od[q] = __builtin_amdgcn_perm(t.v[2 * q + 1], t.v[2 * q], kPermHi);
+        }
+        lds4[h * LPS + 2 * pp] = ev;
+        lds4[h * LPS + 2 * pp + 1] = od;
+    };
+
+    Task pre[MAXT];
+    int tile = blockIdx.x;
+    {
+        const int n = tile / tiles_per_row;
+        const int G0 = (tile - n * tiles_per_row) * TQ - p.P;
+#pragma unroll
+        for (int k = 0; k < MAXT; ++k) {
+            const int task = tid + k * NTH;
+            pre[k] = load_task(n, G0, task < ntasks ? task : ntasks - 1);
+        }
+    }
+
+    // Weight slices in A-operand order: the raw tensor is copied into LDS with wide loads, the
+    // slices are assembled from that copy, and each wave then keeps all NP slices in registers.
+    unsigned short* raw = reinterpret_cast<unsigned short*>(lds4 + NP * 64);
+    const int nW = p.M * p.R * p.S;
+    if (raw_in_lds) {
+        if ((reinterpret_cast<uintptr_t>(wt) & 15) == 0) {
+            for (int e = tid; e < nW / 8; e += NTH) reinterpret_cast<u32x4*>(raw)[e] = reinterpret_cast<const u32x4*>(wt)[e];
+            for (int e = (nW / 8) * 8 + tid; e < nW; e += NTH) raw[e] = wt[e];
+        } else {
+            for (int e = tid; e < nW; e += NTH) raw[e] = wt[e];
+        }
+        __syncthreads();
+    }
+    for (int e = tid; e < NP * 64; e += NTH) {
         const int pi = e >> 6, l = e & 63;
         const int m = l & 15, h = (l >> 4) & 1, s = pi + NP * (l >> 5);
         unsigned v[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int r = 8 * h + j;
-            v[j] = (m < p.M && r < p.R && s < p.S) ? wt[m * p.w_sm + r * p.w_sr + p.w_s0 + s * p.w_ss] : 0u;
+            v[j] = 0u;
+            if (m < p.M && r < p.R && s < p.S) {
+                const long idx = m * p.w_sm + r * p.w_sr + p.w_s0 + s * p.w_ss;
+                v[j] = raw_in_lds ? raw[idx] : wt[idx];
+            }
         }
         lds4[e] = u32x4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
     }
@@ -70,48 +145,28 @@ __global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrPr
 #pragma unroll
     for (int pi = 0; pi < NP; ++pi) wreg[pi] = as_bf16x8(lds4[pi * 64 + lane]);
 
-    const int LP = TQ + (2 * NP - 1) * d;
-    const int LP2 = (LP + 1) >> 1;
-    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    while (tile < ntiles) {
         const int n = tile / tiles_per_row;
         const int O0 = (tile - n * tiles_per_row) * TQ;
-        const int G0 = O0 - p.P;
-        __syncthreads();
-        // transpose the window into LDS: one task = 8 channels x 2 adjacent positions
-        for (int task = tid; task < 2 * LP2; task += kWaves * 64) {
-            const int h = task >= LP2 ? 1 : 0;
-            const int pp = task - h * LP2;
-            const int g = G0 + 2 * pp;
-            unsigned v[8];
-            if (fast && g >= 0 && g + 1 < p.Win) {
+        __syncthreads();  // readers of the previous window (or of the weight slices) are done
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int r = 8 * h + j;
-                    v[j] = r < p.R ? *reinterpret_cast<const unsigned*>(in + (static_cast<long>(n) * p.R + r) * p.Win + g) : 0u;
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int r = 8 * h + j;
-                    unsigned lo = 0u, hi = 0u;
-                    if (r < p.R) {
-                        const unsigned short* row = in + (static_cast<long>(n) * p.R + r) * p.Win;
-                        if (g >= 0 && g < p.Win) lo = row[g];
-                        if (g + 1 >= 0 && g + 1 < p.Win) hi = row[g + 1];
-                    }
-                    v[j] = lo | (hi << 16);
-                }
-            }
-            u32x4 ev, od;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                ev[q] = __builtin_amdgcn_perm(v[2 * q + 1], v[2 * q], kPermLo);
-                od[q] = __builtin_amdgcn_perm(v[2 * q + 1], v[2 * q], kPermHi);
-            }
-            lds4[h * LPS + 2 * pp] = ev;
-            lds4[h * LPS + 2 * pp + 1] = od;
+        for (int k = 0; k < MAXT; ++k) {
+            const int task = tid + k * NTH;
+            if (task < ntasks) store_task(task, pre[k]);
         }
+        for (int task = tid + MAXT * NTH; task < ntasks; task += NTH) store_task(task, load_task(n, O0 - p.P, task));
         __syncthreads();
+        const int next = tile + gridDim.x;
+        if (next < ntiles) {
+            const int nn = next / tiles_per_row;
+            const int G0n = (next - nn * tiles_per_row) * TQ - p.P;
+#pragma unroll
+            for (int k = 0; k < MAXT; ++k) {
+                const int task = tid + k * NTH;
+                pre[k] = load_task(nn, G0n, task < ntasks ? task : ntasks - 1);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
 
         f32x4 acc[T];
 #pragma unroll
@@ -139,19 +194,14 @@ __global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrPr
                 __builtin_amdgcn_sched_barrier(0);
             }
         } else {
-            bf16x8 fr[NP][T];
-#pragma unroll
-            for (int j = 0; j < T; ++j) fr[0][j] = as_bf16x8(bbase[16 * j]);
+            // dilations that do not divide 16: every (tile, slice) pair reads its own operand
 #pragma unroll
             for (int pi = 0; pi < NP; ++pi) {
-                if (pi + 1 < NP) {
 #pragma unroll
-                    for (int j = 0; j < T; ++j) fr[pi + 1][j] = as_bf16x8(bbase[16 * j + (pi + 1) * d]);
+                for (int j = 0; j < T; ++j) {
+                    const bf16x8 f = as_bf16x8(bbase[16 * j + pi * d]);
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[pi], f, acc[j], 0, 0, 0);
                 }
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int j = 0; j < T; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[pi], fr[pi][j], acc[j], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
             }
         }
 #pragma unroll
@@ -165,14 +215,16 @@ __global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrPr
                 }
             }
         }
+        tile = next;
     }
 }
 
 constexpr int kCorrT = 8;
+constexpr int kCorrMaxT = 4;
 constexpr int kNPBuckets[] = {3, 5, 9, 13, 17, 26};
 
 struct CorrPlan {
-    int NP, G, LPS, tiles_per_row, ntiles, fast;
+    int NP, G, LPS, tiles_per_row, ntiles, fast, raw_in_lds;
     size_t lds_bytes;
     bool ok;
 };
@@ -191,8 +243,12 @@ CorrPlan corr_plan(const CorrProblem& p) {
     constexpr int TQ = kWaves * kCorrT * 16;
     const long LP = TQ + static_cast<long>(2 * pl.NP - 1) * p.d;
     const long LPS = (LP + 2 + 7) / 8 * 8;
+    // the window aliases the weight-assembly area: [NP*64 slice slots][raw weight copy]
+    const long raw_slots = (static_cast<long>(p.M) * p.R * p.S * 2 + 15) / 16;
     long slots = 2 * LPS;
-    if (slots < pl.NP * 64) slots = pl.NP * 64;
+    pl.raw_in_lds = (pl.NP * 64 + raw_slots) * 16 <= kLdsBudget / 2;
+    const long wslots = pl.NP * 64 + (pl.raw_in_lds ? raw_slots : 0);
+    if (slots < wslots) slots = wslots;
     if (slots * 16 > kLdsBudget / 2) return pl;  // two workgroups per CU
     pl.LPS = static_cast<int>(LPS);
     pl.tiles_per_row = cdiv(p.Wout, TQ);
@@ -208,12 +264,13 @@ CorrPlan corr_plan(const CorrProblem& p) {
 
 template <int NP, int G>
 hipError_t corr_launch_t(const CorrProblem& p, const CorrPlan& pl, hipStream_t st) {
-    auto kern = smallc_corr_bf16_kernel<NP, G, kCorrT>;
+    auto kern = smallc_corr_bf16_kernel<NP, G, kCorrT, kCorrMaxT>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        static_cast<int>(pl.lds_bytes));
     if (e != hipSuccess) return e;
     const int grid = pl.ntiles < 2 * kNumCU ? pl.ntiles : 2 * kNumCU;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kWaves * 64), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.fast);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kWaves * 64), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.fast,
+                       pl.raw_in_lds);
     return hipGetLastError();
 }
 
@@ -232,16 +289,26 @@ hipError_t corr_launch_np(const CorrProblem& p, const CorrPlan& pl, hipStream_t 
 // ------------------------------------------------------------------------------------------------
 // backward-weight, d == 8
 // ------------------------------------------------------------------------------------------------
-// LDS rows of 16-byte slots (8 positions each):
-//   dyt[16][LQS]  row = filter,  slot i <-> q = Qs + 8i .. 8i+7
-//   xt [16][LXS]  row = channel, slot i <-> input positions Qs - P + 8i .. +7
-// k-step t covers q = Qs + 32t .. +31; lane (li, kb) holds positions 8*kb .. 8*kb+7 of it.
-// Tap s = v + 4i of wave v reads x slot 4*(t+i) + v + kb: operand index f = t + i.
-template <int NT>
-__global__ __launch_bounds__(256, 2) void smallc_wgrad_bf16_d8_kernel(WgradProblem p, int chunks_per_row, int nchunks, int QC, int LQS, int LXS, int fast) {
-    extern __shared__ u32x4 lds4[];
-    u32x4* dyt = lds4;
-    u32x4* xt = lds4 + 16 * LQS;
+// A workgroup (4 waves) owns a strip of one sample: `UPS` consecutive units of 416 output columns
+// (13 k-steps of 32).  Columns are handled as 16-byte slots of 8 bf16: dy slot i <-> q = 8i..8i+7,
+// x slot i <-> input positions 8i - P .. 8i - P + 7 (so tap s reads x slot = dy slot + s).
+// Wave v owns taps s = v + 4i (i < 13).  In k-step t its lane (li, kb) needs, for tap slot i, the
+// x operand X_f = x[li][slots 4f + v + kb], f = t + i: a sliding window of 13 operands kept in a
+// register ring, refilled with X_{t+13} in step t.  The refills of unit j therefore read exactly x
+// slots [52(j+1), 52(j+1) + 55): LDS holds one such "period" of x and one unit of dy at a time, and
+// the halo never has to be staged again.  The next period/unit is fetched from global memory into
+// registers while the MFMAs of the current unit run.
+//   xbuf [16][kXR]  row = channel, slot i <-> x slot 52(j+1) + i      (kXP = 60 slots staged)
+//   dybuf[16][kDR]  row = filter,  slot i <-> dy slot 52j + i
+constexpr int kNT = 13;            // taps per wave == operands in the ring == k-steps per unit
+constexpr int kUnitSlots = 4 * kNT;  // 52 slots = 416 columns
+constexpr int kXP = 60;            // x slots staged per period (52 + look-ahead of the highest tap slot)
+constexpr int kXR = 61, kDR = 53;  // LDS row strides in slots (odd: rows spread over the bank groups)
+constexpr int kWgMaxS = 7;         // 16 * (60 + 52) slots / 256 threads
+
+__global__ __launch_bounds__(256, 2) void smallc_wgrad_bf16_d8_kernel(WgradProblem p, int SPR, int UPS, int units_per_row, int fast) {
+    __shared__ u32x4 xbuf[16 * kXR];
+    __shared__ u32x4 dybuf[16 * kDR];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -249,118 +316,127 @@ __global__ __launch_bounds__(256, 2) void smallc_wgrad_bf16_d8_kernel(WgradProbl
     const int kb = lane >> 4;
     const unsigned short* __restrict__ x = static_cast<const unsigned short*>(p.x);
     const unsigned short* __restrict__ dy = static_cast<const unsigned short*>(p.dy);
-    const int nt = (p.S - wave + 3) / 4;
-    const int QS8 = QC / 8;       // dy slots per row
-    const int XS8 = QS8 + 56;     // x slots per row that the ring may touch
-    const int nsteps = QC / 32;   // multiple of NT
+    const int n = blockIdx.x / SPR;
+    const int j0 = (blockIdx.x - n * SPR) * UPS;
+    const int j1 = min(j0 + UPS, units_per_row);
+    const int Qb = min(j1 * kUnitSlots * 8, p.Q);  // this strip's dy columns end here
 
-    f32x4 acc[NT];
+    // 8 consecutive elements of one row starting at column g, zero outside [0, limit)
+    auto load8 = [&](const unsigned short* row, int g, int limit) -> u32x4 {
+        u32x4 v = u32x4{0u, 0u, 0u, 0u};
+        if (g + 8 > 0 && g < limit) {
+            if (fast && g >= 0 && g + 8 <= limit) {
+                v = *reinterpret_cast<const u32x4*>(row + g);
+            } else {
+                unsigned t[8];
 #pragma unroll
-    for (int i = 0; i < NT; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    for (int chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
-        const int n = chunk / chunks_per_row;
-        const int Qs = (chunk - n * chunks_per_row) * QC;
-        const int G0 = Qs - p.P;
-        __syncthreads();
-        for (int e = tid; e < 16 * (QS8 + XS8); e += 256) {
-            const bool is_x = e >= 16 * QS8;
-            const int e2 = is_x ? e - 16 * QS8 : e;
-            const int per_row = is_x ? XS8 : QS8;
-            const int r = e2 / per_row;
-            const int i = e2 - r * per_row;
-            const int rows = is_x ? p.C : p.K;
-            const int width = is_x ? p.W : p.Q;
-            const int g = (is_x ? G0 : Qs) + 8 * i;
-            u32x4 v = u32x4{0u, 0u, 0u, 0u};
-            if (r < rows && g + 8 > 0 && g < width) {
-                const unsigned short* row = (is_x ? x : dy) + (static_cast<long>(n) * rows + r) * width;
-                if (fast && g >= 0 && g + 8 <= width) {
-                    v = *reinterpret_cast<const u32x4*>(row + g);
-                } else {
-                    unsigned t[8];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) t[j] = (g + j >= 0 && g + j < width) ? row[g + j] : 0u;
-                    v = u32x4{t[0] | (t[1] << 16), t[2] | (t[3] << 16), t[4] | (t[5] << 16), t[6] | (t[7] << 16)};
-                }
+                for (int j = 0; j < 8; ++j) t[j] = (g + j >= 0 && g + j < limit) ? row[g + j] : 0u;
+                v = u32x4{t[0] | (t[1] << 16), t[2] | (t[3] << 16), t[4] | (t[5] << 16), t[6] | (t[7] << 16)};
             }
-            (is_x ? xt + r * LXS : dyt + r * LQS)[i] = v;
+        }
+        return v;
+    };
+    // staging slot e of "x period k": e in [0, 16*kXP)
+    auto load_x = [&](int k, int e) -> u32x4 {
+        const int r = e / kXP, i = e - r * kXP;
+        if (r >= p.C) return u32x4{0u, 0u, 0u, 0u};
+        return load8(x + (static_cast<long>(n) * p.C + r) * p.W, 8 * (kUnitSlots * k + i) - p.P, p.W);
+    };
+    auto load_dy = [&](int j, int e) -> u32x4 {
+        const int r = e / kUnitSlots, i = e - r * kUnitSlots;
+        if (r >= p.K) return u32x4{0u, 0u, 0u, 0u};
+        return load8(dy + (static_cast<long>(n) * p.K + r) * p.Q, 8 * (kUnitSlots * j + i), Qb);
+    };
+    constexpr int NX = 16 * kXP, NS = 16 * (kXP + kUnitSlots);
+    // combined slot space of one pipeline stage: x period j+1 first, then dy unit j
+    auto load_stage = [&](int j, int e) -> u32x4 { return e < NX ? load_x(j + 1, e) : load_dy(j, e - NX); };
+    auto store_stage = [&](int e, u32x4 v) {
+        if (e < NX) {
+            const int r = e / kXP;
+            xbuf[r * kXR + (e - r * kXP)] = v;
+        } else {
+            const int e2 = e - NX, r = e2 / kUnitSlots;
+            dybuf[r * kDR + (e2 - r * kUnitSlots)] = v;
+        }
+    };
+
+    f32x4 acc[kNT];
+#pragma unroll
+    for (int i = 0; i < kNT; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // prologue: x period j0 -> LDS -> operand ring
+    for (int e = tid; e < NX; e += 256) {
+        const int r = e / kXP;
+        xbuf[r * kXR + (e - r * kXP)] = load_x(j0, e);
+    }
+    u32x4 pre[kWgMaxS];
+#pragma unroll
+    for (int k = 0; k < kWgMaxS; ++k) pre[k] = load_stage(j0, tid + k * 256 < NS ? tid + k * 256 : NS - 1);
+    __syncthreads();
+    const u32x4* xp = xbuf + li * kXR + wave + kb;
+    const u32x4* ap = dybuf + li * kDR + kb;
+    bf16x8 ring[kNT];
+#pragma unroll
+    for (int i = 0; i < kNT; ++i) ring[i] = as_bf16x8(xp[4 * i]);
+
+    for (int j = j0; j < j1; ++j) {
+        __syncthreads();  // ring preload / previous unit's LDS reads are done
+#pragma unroll
+        for (int k = 0; k < kWgMaxS; ++k) {
+            const int e = tid + k * 256;
+            if (e < NS) store_stage(e, pre[k]);
         }
         __syncthreads();
-
-        const u32x4* ap = dyt + li * LQS + kb;
-        const u32x4* xp = xt + li * LXS + wave + kb;
-        bf16x8 ring[NT];
+        if (j + 1 < j1) {
 #pragma unroll
-        for (int i = 0; i < NT; ++i) ring[i] = as_bf16x8(xp[4 * i]);
+            for (int k = 0; k < kWgMaxS; ++k) pre[k] = load_stage(j + 1, tid + k * 256 < NS ? tid + k * 256 : NS - 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
         bf16x8 a = as_bf16x8(ap[0]);
-        for (int tb = 0; tb < nsteps; tb += NT) {
 #pragma unroll
-            for (int u = 0; u < NT; ++u) {
-                const int t = tb + u;
-                // slot u is dead once tap 0 has consumed it: refill it (and fetch the next dy operand)
-                // right away so the other taps' MFMAs cover the LDS latency
-                acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ring[u], acc[0], 0, 0, 0);
-                const bf16x8 a_nxt = as_bf16x8(ap[4 * (t + 1 < nsteps ? t + 1 : t)]);
-                ring[u] = as_bf16x8(xp[4 * (t + NT)]);
-                __builtin_amdgcn_sched_barrier(0);
+        for (int u = 0; u < kNT; ++u) {
+            // ring slot u is dead once tap slot 0 has consumed it: refill it (and fetch the next dy
+            // operand) right away so the other taps' MFMAs cover the LDS latency
+            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ring[u], acc[0], 0, 0, 0);
+            const bf16x8 a_nxt = as_bf16x8(ap[4 * (u + 1 < kNT ? u + 1 : u)]);
+            ring[u] = as_bf16x8(xp[4 * u]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int i = 1; i < NT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ring[(u + i) % NT], acc[i], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                a = a_nxt;
-            }
+            for (int i = 1; i < kNT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ring[(u + i) % kNT], acc[i], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            a = a_nxt;
         }
     }
+    const int nt = (p.S - wave + 3) / 4;  // real taps of this wave; the remaining slots hold unused sums
     float* ws = static_cast<float*>(p.ws) + static_cast<long>(blockIdx.x) * p.S * 256;
 #pragma unroll
-    for (int i = 0; i < NT; ++i) {
+    for (int i = 0; i < kNT; ++i) {
         if (i < nt) {
             const int s = wave + 4 * i;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) ws[s * 256 + (4 * kb + j) * 16 + li] = acc[i][j];
+            for (int jj = 0; jj < 4; ++jj) ws[s * 256 + (4 * kb + jj) * 16 + li] = acc[i][jj];
         }
     }
 }
 
-constexpr int kWgradNT = 13;
-
 struct WgradPlan {
-    int QC, LQS, LXS, chunks_per_row, nchunks, grid, fast;
-    size_t lds_bytes;
+    int SPR, UPS, units_per_row, grid, fast;
     bool ok;
 };
 
 WgradPlan wgrad_plan(const WgradProblem& p) {
     WgradPlan pl{};
     pl.ok = false;
-    if (!p.bf16 || p.C > 16 || p.K > 16 || p.d != 8 || p.S > 4 * kWgradNT) return pl;
-    const int unit = 32 * kWgradNT;  // 416 columns: one turn of the operand ring
-    // pick the chunk length (1..3 ring turns) that gives the shortest critical path over 2 WGs/CU
-    auto lds_for = [](int qc, int* lqs, int* lxs) {
-        const int QS8 = qc / 8, XS8 = QS8 + 56;
-        *lqs = (QS8 + 7) / 8 * 8 + 1;  // row stride == 16 bytes (mod 128): 8 rows of one column hit 8 bank groups
-        *lxs = (XS8 + 7) / 8 * 8 + 1;
-        return 16L * (*lqs + *lxs) * 16;
-    };
-    int best_m = 0;
-    long best_cost = -1;
-    for (int m = 1; m <= 3; ++m) {
-        int a, b;
-        if (lds_for(unit * m, &a, &b) > kLdsBudget / 2) break;  // two workgroups per CU
-        const long chunks = static_cast<long>(p.N) * cdiv(p.Q, unit * m);
-        const long rounds = (chunks + 2 * kNumCU - 1) / (2 * kNumCU);
-        const long cost = rounds * (unit * m + 450);  // columns computed + window re-staged per chunk
-        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_m = m; }
-    }
-    if (best_m == 0) return pl;
-    pl.QC = unit * best_m;
-    const long bytes = lds_for(pl.QC, &pl.LQS, &pl.LXS);
-    pl.chunks_per_row = cdiv(p.Q, pl.QC);
-    const long nc = static_cast<long>(p.N) * pl.chunks_per_row;
-    if (nc > 0x7fffffffL) return pl;
-    pl.nchunks = static_cast<int>(nc);
-    pl.grid = pl.nchunks < 2 * kNumCU ? pl.nchunks : 2 * kNumCU;
-    pl.lds_bytes = static_cast<size_t>(bytes);
+    if (!p.bf16 || p.C > 16 || p.K > 16 || p.d != 8 || p.S > 4 * kNT) return pl;
+    pl.units_per_row = cdiv(p.Q, kUnitSlots * 8);
+    // strips of UPS units so that about two workgroups per CU exist
+    const long total_units = static_cast<long>(p.N) * pl.units_per_row;
+    pl.UPS = static_cast<int>((total_units + 2 * kNumCU - 1) / (2 * kNumCU));
+    if (pl.UPS < 1) pl.UPS = 1;
+    pl.SPR = cdiv(pl.units_per_row, pl.UPS);
+    const long grid = static_cast<long>(p.N) * pl.SPR;
+    if (grid > 0x7fffffffL) return pl;
+    pl.grid = static_cast<int>(grid);
     pl.fast = (p.W % 8 == 0) && (p.Q % 8 == 0) && (p.P % 8 == 0) && (reinterpret_cast<uintptr_t>(p.x) % 16 == 0) &&
               (reinterpret_cast<uintptr_t>(p.dy) % 16 == 0);
     pl.ok = true;
@@ -395,13 +471,8 @@ size_t smallc_bf16_wgrad_workspace(const WgradProblem& p) {
 hipError_t smallc_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     const WgradPlan pl = wgrad_plan(p);
     if (!pl.ok) return hipErrorInvalidValue;
-    auto kern = smallc_wgrad_bf16_d8_kernel<kWgradNT>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(pl.lds_bytes));
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(pl.grid), dim3(256), pl.lds_bytes, st, p, pl.chunks_per_row, pl.nchunks, pl.QC, pl.LQS, pl.LXS,
-                       pl.fast);
-    e = hipGetLastError();
+    hipLaunchKernelGGL(smallc_wgrad_bf16_d8_kernel, dim3(pl.grid), dim3(256), 0, st, p, pl.SPR, pl.UPS, pl.units_per_row, pl.fast);
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return smallc_wgrad_reduce_launch(static_cast<const float*>(p.ws), p.dw, p.K, p.C, p.S, pl.grid, st);
 }
