@@ -42,6 +42,8 @@ def main() -> int:
     ap.add_argument("--workload", default="genomics_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--variant", type=int, default=0, help="force a kernel family (0 = auto)")
+    ap.add_argument("--passes", default=",".join(PASSES),
+                    help="comma-separated subset of passes to run (profiling runs; the headline needs all three)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -79,8 +81,10 @@ def main() -> int:
         "bwd_weight": lambda: binding.conv1d_bwd_weight(dev["x"], dev["dy"], wl.S, wl.d, wl.P, out=dw, workspace=ws),
     }
 
+    run_passes = tuple(p for p in PASSES if p in args.passes.split(","))
+
     def step():
-        for p in PASSES:
+        for p in run_passes:
             launch[p]()
 
     for _ in range(args.warmup):
@@ -92,11 +96,11 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    value = 3 * wl.flops / (ms_per_step * 1e-3) / 1e12
+    value = len(run_passes) * wl.flops / (ms_per_step * 1e-3) / 1e12
 
     # per-pass device time: HIP events on the stream the kernels are launched on (torch's current stream)
     per_pass = {}
-    for p in PASSES:
+    for p in run_passes:
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
         torch.cuda.synchronize()
         for a, b in evs:
@@ -114,7 +118,7 @@ def main() -> int:
             "tflops": round(tf, 2), "frac_mfma_peak": round(tf / PEAK[wl.dtype], 4),
             "algorithmic_GBps": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
         }
-    dom = max(PASSES, key=lambda p: per_pass[p]["avg_us"])
+    dom = max(run_passes, key=lambda p: per_pass[p]["avg_us"])
     # which roof bounds the dominant kernel: time at MFMA peak vs time at HBM peak for its algorithmic work
     t_mfma = wl.flops / (PEAK[wl.dtype] * 1e12)
     t_hbm = algorithmic_bytes(wl, dom) / (HBM_PEAK_GBS * 1e9)
@@ -148,7 +152,7 @@ def main() -> int:
         "config": {"workload": wl.name, "N": wl.N, "C": wl.C, "K": wl.K, "W": wl.W, "S": wl.S, "dilation": wl.d,
                    "padding": wl.P, "Q": wl.Q, "gflop_per_pass": round(wl.flops / 1e9, 3), "outputs": "fp32"},
         "frac_mfma_peak": round(value / PEAK[wl.dtype], 4),
-        "per_pass": per_pass, "roofline": roof, "cpu_baseline": cpu,
+        "passes": list(run_passes), "per_pass": per_pass, "roofline": roof, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
     return 0

@@ -36,7 +36,8 @@ def sources():
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
-    cmd = [hipcc(), *HIP_FLAGS, "-c", src, "-o", obj]
+    extra = ["-DCONV1D_DEV_FEW_KERNELS"] if os.environ.get("CONV1D_DEV_FEW_KERNELS") else []  # faster edit-compile loop
+    cmd = [hipcc(), *HIP_FLAGS, *extra, "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     msgs = "\n".join(l for l in (r.stdout + r.stderr).splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

@@ -32,9 +32,9 @@ constexpr int kNumCU = 256;
 // A workgroup walks tiles blockIdx.x, +gridDim.x, ...; the window of the next tile is fetched
 // from global memory into registers (16-byte slots, MAXS per thread) while the MFMAs of the
 // current tile run, and written to LDS after the barrier that ends the current tile.
-template <int RC, int T, int WAVES, int MAXS>
+template <int RC, int T, int WAVES, int MAXS, bool FAST>
 __global__ __launch_bounds__(WAVES * 64) void smallc_corr_f32_kernel(CorrProblem p, int tiles_per_row, int ntiles, int LPS, int LP4,
-                                                                     int fast, int raw_in_lds) {
+                                                                     int raw_in_lds) {
     extern __shared__ float lds[];
     constexpr int TQ = WAVES * T * 16;
     constexpr int NTH = WAVES * 64;
@@ -50,36 +50,46 @@ __global__ __launch_bounds__(WAVES * 64) void smallc_corr_f32_kernel(CorrProblem
     const float* __restrict__ wt = static_cast<const float*>(p.wt);
     const int nslots = 4 * RC * LP4;
 
-    auto load_slot = [&](int n, int G0, int e) -> f32x4 {
+    // Staging slot e = 4 adjacent positions of row e / LP4.  FAST (row starts, window origin and
+    // base pointer are multiples of 4 floats, so a slot is inside or outside its row as a whole):
+    // one 16-byte load from a clamped address, masked when it is written to LDS.  Otherwise
+    // element loads, done synchronously after the barrier.
+    auto fetch = [&](int n, int G0, int e) -> f32x4 {
         const int r = e / LP4;
         const int g = G0 + 4 * (e - r * LP4);
-        f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (r < p.R) {
-            const float* row = in + (static_cast<long>(n) * p.R + r) * p.Win;
-            if (fast && g >= 0 && g + 4 <= p.Win) {
-                v = *reinterpret_cast<const f32x4*>(row + g);
-            } else {
+        const float* row = in + static_cast<long>(n) * p.R * p.Win + static_cast<unsigned>(min(r, p.R - 1) * p.Win);
+        if constexpr (FAST) {
+            const int lim = p.Win - 4;  // >= 0 on this path (checked by the host)
+            return *reinterpret_cast<const f32x4*>(row + (g < 0 ? 0 : (g > lim ? lim : g)));
+        } else {
+            f32x4 v;
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (g + j >= 0 && g + j < p.Win) v[j] = row[g + j];
+            for (int j = 0; j < 4; ++j) {
+                const int gj = g + j;
+                const float t = row[gj < 0 ? 0 : (gj > p.Win - 1 ? p.Win - 1 : gj)];
+                v[j] = (gj >= 0 && gj < p.Win) ? t : 0.f;
             }
+            return v;
         }
-        return v;
     };
-    auto lds_slot = [&](int e) -> f32x4* {
+    auto commit = [&](int G0, int e, f32x4 v) {
         const int r = e / LP4;
-        return reinterpret_cast<f32x4*>(win + r * LPS + 4 * (e - r * LP4));
+        const int i = e - r * LP4;
+        const int g = G0 + 4 * i;
+        const bool ok = r < p.R && (!FAST || (g >= 0 && g + 4 <= p.Win));
+        if (!ok) v = f32x4{0.f, 0.f, 0.f, 0.f};
+        *reinterpret_cast<f32x4*>(win + r * LPS + 4 * i) = v;
     };
 
-    f32x4 pre[MAXS];
+    f32x4 pre[FAST ? MAXS : 1];
     int tile = blockIdx.x;
-    {
+    if constexpr (FAST) {
         const int n = tile / tiles_per_row;
         const int G0 = (tile - n * tiles_per_row) * TQ - p.P;
 #pragma unroll
         for (int k = 0; k < MAXS; ++k) {
             const int e = tid + k * NTH;
-            pre[k] = load_slot(n, G0, e < nslots ? e : nslots - 1);
+            pre[k] = fetch(n, G0, e < nslots ? e : nslots - 1);
         }
     }
 
@@ -109,22 +119,28 @@ __global__ __launch_bounds__(WAVES * 64) void smallc_corr_f32_kernel(CorrProblem
         const int n = tile / tiles_per_row;
         const int O0 = (tile - n * tiles_per_row) * TQ;
         __syncthreads();  // readers of the previous window (or of the raw weights) are done
-#pragma unroll
-        for (int k = 0; k < MAXS; ++k) {
-            const int e = tid + k * NTH;
-            if (e < nslots) *lds_slot(e) = pre[k];
-        }
-        for (int e = tid + MAXS * NTH; e < nslots; e += NTH) *lds_slot(e) = load_slot(n, O0 - p.P, e);
-        __syncthreads();
-
-        const int next = tile + gridDim.x;
-        if (next < ntiles) {
-            const int nn = next / tiles_per_row;
-            const int G0n = (next - nn * tiles_per_row) * TQ - p.P;
+        if constexpr (FAST) {
 #pragma unroll
             for (int k = 0; k < MAXS; ++k) {
                 const int e = tid + k * NTH;
-                pre[k] = load_slot(nn, G0n, e < nslots ? e : nslots - 1);
+                if (e < nslots) commit(O0 - p.P, e, pre[k]);
+            }
+            for (int e = tid + MAXS * NTH; e < nslots; e += NTH) commit(O0 - p.P, e, fetch(n, O0 - p.P, e));
+        } else {
+            for (int e = tid; e < nslots; e += NTH) commit(O0 - p.P, e, fetch(n, O0 - p.P, e));
+        }
+        __syncthreads();
+
+        const int next = tile + gridDim.x;
+        if constexpr (FAST) {
+            if (next < ntiles) {
+                const int nn = next / tiles_per_row;
+                const int G0n = (next - nn * tiles_per_row) * TQ - p.P;
+#pragma unroll
+                for (int k = 0; k < MAXS; ++k) {
+                    const int e = tid + k * NTH;
+                    pre[k] = fetch(nn, G0n, e < nslots ? e : nslots - 1);
+                }
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -194,6 +210,7 @@ CorrF32Plan corr_f32_plan(const CorrProblem& p) {
     CorrF32Plan pl{};
     pl.ok = false;
     if (p.bf16 || p.R > 16 || p.M > 16) return pl;
+    if (static_cast<long>(p.R) * p.Win >= (1L << 30)) return pl;  // 32-bit element offsets within one sample
     constexpr int TQ = kCorrWaves * kCorrT * 16;
     pl.RC = (p.R + 3) / 4;
     const long halo = static_cast<long>(p.S - 1) * p.d;
@@ -210,22 +227,27 @@ CorrF32Plan corr_f32_plan(const CorrProblem& p) {
     pl.ntiles = static_cast<int>(nt);
     pl.lds_bytes = static_cast<size_t>(bytes);
     // 16-byte window loads need every row start, the window origin and the base pointer aligned
-    pl.fast = (p.Win % 4 == 0) && (((p.P % 4) + 4) % 4 == 0) && (reinterpret_cast<uintptr_t>(p.in) % 16 == 0);
+    pl.fast = (p.Win % 4 == 0) && (((p.P % 4) + 4) % 4 == 0) && (reinterpret_cast<uintptr_t>(p.in) % 16 == 0) && p.Win >= 4;
     pl.raw_in_lds = static_cast<long>(p.M) * p.R * p.S <= 4L * pl.RC * LPS;
     pl.ok = true;
     return pl;
 }
 
-template <int RC>
-hipError_t corr_f32_launch_rc(const CorrProblem& p, const CorrF32Plan& pl, hipStream_t st) {
-    auto kern = smallc_corr_f32_kernel<RC, kCorrT, kCorrWaves, kCorrMaxS>;
+template <int RC, bool FAST>
+hipError_t corr_f32_launch_f(const CorrProblem& p, const CorrF32Plan& pl, hipStream_t st) {
+    auto kern = smallc_corr_f32_kernel<RC, kCorrT, kCorrWaves, kCorrMaxS, FAST>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        static_cast<int>(pl.lds_bytes));
     if (e != hipSuccess) return e;
     const int grid = pl.ntiles < kNumCU ? pl.ntiles : kNumCU;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kCorrWaves * 64), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.LP4,
-                       pl.fast, pl.raw_in_lds);
+                       pl.raw_in_lds);
     return hipGetLastError();
+}
+
+template <int RC>
+hipError_t corr_f32_launch_rc(const CorrProblem& p, const CorrF32Plan& pl, hipStream_t st) {
+    return pl.fast ? corr_f32_launch_f<RC, true>(p, pl, st) : corr_f32_launch_f<RC, false>(p, pl, st);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -238,9 +260,9 @@ hipError_t corr_f32_launch_rc(const CorrProblem& p, const CorrF32Plan& pl, hipSt
 // One MFMA k-step covers 4 positions: A = dy[m][q0 + kb], B = x[c][q0 + kb + s*d - P].
 // The next chunk is fetched into registers (16-byte slots) while the current one is consumed.
 // Partial sums: ws[(wg * S + s) * 256 + m * 16 + c].
-template <int NT, int MAXS>
+template <int NT, int MAXS, bool FAST>
 __global__ __launch_bounds__(256) void smallc_wgrad_f32_kernel(WgradProblem p, int chunks_per_row, int nchunks, int QC, int LQS, int LXS,
-                                                               int LX4, int fast) {
+                                                               int LX4) {
     extern __shared__ float lds[];
     float* dyt = lds;
     float* xt = lds + 16 * LQS;
@@ -256,70 +278,87 @@ __global__ __launch_bounds__(256) void smallc_wgrad_f32_kernel(WgradProblem p, i
     const int ndy = 16 * Q4;
     const int nslots = ndy + 16 * LX4;
 
-    // slot e: first the dy rows (Q4 slots each), then the x rows (LX4 slots each)
-    auto load_slot = [&](int n, int Qs, int e) -> f32x4 {
+    // Staging slot e: first the dy rows (Q4 slots each), then the x rows (LX4 slots each); 4 adjacent
+    // positions per slot.  FAST: one clamped 16-byte load, masked at the LDS write (widths, padding
+    // and pointers are multiples of 4 floats, so a slot never straddles a row end).
+    struct Where { const float* row; int g, limit, rows_ok; float* dst; };
+    auto where = [&](int n, int Qs, int e) -> Where {
+        Where w;
         const bool is_x = e >= ndy;
         const int e2 = is_x ? e - ndy : e;
         const int per_row = is_x ? LX4 : Q4;
-        const int r = e2 / per_row;
+        const int r = e2 / per_row, i = e2 - r * per_row;
         const int rows = is_x ? p.C : p.K;
-        const int width = is_x ? p.W : p.Q;
-        const int g = (is_x ? Qs - p.P : Qs) + 4 * (e2 - r * per_row);
-        f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (r < rows) {
-            const float* row = (is_x ? x : dy) + (static_cast<long>(n) * rows + r) * width;
-            if (fast && g >= 0 && g + 4 <= width) {
-                v = *reinterpret_cast<const f32x4*>(row + g);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (g + j >= 0 && g + j < width) v[j] = row[g + j];
-            }
-        }
-        return v;
+        w.limit = is_x ? p.W : p.Q;
+        w.row = (is_x ? x : dy) + static_cast<long>(n) * rows * w.limit + static_cast<unsigned>(min(r, rows - 1) * w.limit);
+        w.g = (is_x ? Qs - p.P : Qs) + 4 * i;
+        w.rows_ok = r < rows;
+        w.dst = (is_x ? xt + r * LXS : dyt + r * LQS) + 4 * i;
+        return w;
     };
-    auto lds_slot = [&](int e) -> f32x4* {
-        const bool is_x = e >= ndy;
-        const int e2 = is_x ? e - ndy : e;
-        const int per_row = is_x ? LX4 : Q4;
-        const int r = e2 / per_row;
-        return reinterpret_cast<f32x4*>((is_x ? xt + r * LXS : dyt + r * LQS) + 4 * (e2 - r * per_row));
+    auto fetch = [&](int n, int Qs, int e) -> f32x4 {
+        const Where w = where(n, Qs, e);
+        if constexpr (FAST) {
+            const int lim = w.limit - 4;
+            return *reinterpret_cast<const f32x4*>(w.row + (w.g < 0 ? 0 : (w.g > lim ? lim : w.g)));
+        } else {
+            f32x4 v;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int gj = w.g + j;
+                const float t = w.row[gj < 0 ? 0 : (gj > w.limit - 1 ? w.limit - 1 : gj)];
+                v[j] = (gj >= 0 && gj < w.limit) ? t : 0.f;
+            }
+            return v;
+        }
+    };
+    auto commit = [&](int n, int Qs, int e, f32x4 v) {
+        const Where w = where(n, Qs, e);
+        const bool ok = w.rows_ok && (!FAST || (w.g >= 0 && w.g + 4 <= w.limit));
+        if (!ok) v = f32x4{0.f, 0.f, 0.f, 0.f};
+        *reinterpret_cast<f32x4*>(w.dst) = v;
     };
 
     f32x4 acc[NT];
 #pragma unroll
     for (int i = 0; i < NT; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    f32x4 pre[MAXS];
+    f32x4 pre[FAST ? MAXS : 1];
     int chunk = blockIdx.x;
-    {
+    if constexpr (FAST) {
         const int n = chunk / chunks_per_row;
         const int Qs = (chunk - n * chunks_per_row) * QC;
 #pragma unroll
         for (int k = 0; k < MAXS; ++k) {
             const int e = tid + k * 256;
-            pre[k] = load_slot(n, Qs, e < nslots ? e : nslots - 1);
+            pre[k] = fetch(n, Qs, e < nslots ? e : nslots - 1);
         }
     }
     while (chunk < nchunks) {
         const int n = chunk / chunks_per_row;
         const int Qs = (chunk - n * chunks_per_row) * QC;
         __syncthreads();
-#pragma unroll
-        for (int k = 0; k < MAXS; ++k) {
-            const int e = tid + k * 256;
-            if (e < nslots) *lds_slot(e) = pre[k];
-        }
-        for (int e = tid + MAXS * 256; e < nslots; e += 256) *lds_slot(e) = load_slot(n, Qs, e);
-        __syncthreads();
-        const int next = chunk + gridDim.x;
-        if (next < nchunks) {
-            const int nn = next / chunks_per_row;
-            const int Qn = (next - nn * chunks_per_row) * QC;
+        if constexpr (FAST) {
 #pragma unroll
             for (int k = 0; k < MAXS; ++k) {
                 const int e = tid + k * 256;
-                pre[k] = load_slot(nn, Qn, e < nslots ? e : nslots - 1);
+                if (e < nslots) commit(n, Qs, e, pre[k]);
+            }
+            for (int e = tid + MAXS * 256; e < nslots; e += 256) commit(n, Qs, e, fetch(n, Qs, e));
+        } else {
+            for (int e = tid; e < nslots; e += 256) commit(n, Qs, e, fetch(n, Qs, e));
+        }
+        __syncthreads();
+        const int next = chunk + gridDim.x;
+        if constexpr (FAST) {
+            if (next < nchunks) {
+                const int nn = next / chunks_per_row;
+                const int Qn = (next - nn * chunks_per_row) * QC;
+#pragma unroll
+                for (int k = 0; k < MAXS; ++k) {
+                    const int e = tid + k * 256;
+                    pre[k] = fetch(nn, Qn, e < nslots ? e : nslots - 1);
+                }
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -397,6 +436,7 @@ WgradF32Plan wgrad_f32_plan(const WgradProblem& p) {
     WgradF32Plan pl{};
     pl.ok = false;
     if (p.bf16 || p.C > 16 || p.K > 16 || p.S > 4 * kWgradNT) return pl;
+    if (static_cast<long>(p.C) * p.W >= (1L << 30) || static_cast<long>(p.K) * p.Q >= (1L << 30)) return pl;
     const long halo = static_cast<long>(4 * kWgradNT - 1) * p.d;  // every tap slot a wave may read
     const int QC = 256;
     // row strides == 2 (mod 32) words (and a multiple of 4 words would break that): 16-byte slot
@@ -417,8 +457,8 @@ WgradF32Plan wgrad_f32_plan(const WgradProblem& p) {
     const int per_cu = bytes <= kLdsBudget / 2 ? 2 : 1;
     pl.grid = pl.nchunks < per_cu * kNumCU ? pl.nchunks : per_cu * kNumCU;
     pl.lds_bytes = static_cast<size_t>(bytes);
-    pl.fast = (p.W % 4 == 0) && (p.Q % 4 == 0) && (p.P % 4 == 0) && (reinterpret_cast<uintptr_t>(p.x) % 16 == 0) &&
-              (reinterpret_cast<uintptr_t>(p.dy) % 16 == 0);
+    pl.fast = (p.W % 4 == 0) && (p.Q % 4 == 0) && (p.P % 4 == 0) && p.W >= 4 && p.Q >= 4 &&
+              (reinterpret_cast<uintptr_t>(p.x) % 16 == 0) && (reinterpret_cast<uintptr_t>(p.dy) % 16 == 0);
     pl.ok = true;
     return pl;
 }
@@ -463,12 +503,12 @@ hipError_t smallc_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     if (p.bf16) return smallc_bf16_wgrad_launch(p, st);
     const WgradF32Plan pl = wgrad_f32_plan(p);
     if (!pl.ok) return hipErrorInvalidValue;
-    auto kern = smallc_wgrad_f32_kernel<kWgradNT, kWgradMaxS>;
+    auto kern = pl.fast ? smallc_wgrad_f32_kernel<kWgradNT, kWgradMaxS, true> : smallc_wgrad_f32_kernel<kWgradNT, kWgradMaxS, false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        static_cast<int>(pl.lds_bytes));
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(pl.grid), dim3(256), pl.lds_bytes, st, p, pl.chunks_per_row, pl.nchunks, pl.QC, pl.LQS, pl.LXS,
-                       pl.LX4, pl.fast);
+                       pl.LX4);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     return smallc_wgrad_reduce_launch(static_cast<const float*>(p.ws), p.dw, p.K, p.C, p.S, pl.grid, st);

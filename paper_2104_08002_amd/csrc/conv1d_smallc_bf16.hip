@@ -16,6 +16,8 @@
 // 16 x 16 accumulator per tap.  With d = 8 the B operand of (k-step t, tap s) equals that of
 // (t+1, s-4); wave v of a workgroup owns the taps s = v (mod 4) and keeps their 13 operands in a
 // register ring, loading one new operand per k-step.
+#include <type_traits>
+
 #include "conv1d_internal.h"
 
 namespace conv1d {
@@ -40,9 +42,12 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast
 // k-slot layout of one MFMA (lane = li + 16*kb, element j of the lane's 8):
 //   channel r = 8*(kb & 1) + j,  tap s = p + NP*(kb >> 1)
 // LDS: plane h = kb & 1 holds channels 8h..8h+7; slot (h*LPS + i) <-> input position G0 + i.
-template <int NP, int G, int T, int MAXT>
-__global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrProblem p, int tiles_per_row, int ntiles, int LPS, int fast,
-                                                                          int raw_in_lds) {
+constexpr int kOS = 132;  // row stride (floats) of a wave's output staging tile: 4 rows apart -> 16 banks apart
+
+template <int NP, int G, int T, int MAXT, bool FAST>
+__global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrProblem p, int tiles_per_row, int ntiles, int LPS,
+                                                                          int vec_out) {
+    static_assert(T == 8, "the output staging tile is 16 rows x 128 columns");
     extern __shared__ u32x4 lds4[];
     constexpr int TQ = kWaves * T * 16;
     constexpr int NTH = kWaves * 64;
@@ -57,144 +62,208 @@ __global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrPr
     const int LP = TQ + (2 * NP - 1) * d;
     const int LP2 = (LP + 1) >> 1;
     const int ntasks = 2 * LP2;
+    const int ob = wave * T * 16;
+    // LDS: [window: 2*LPS slots][output staging: kWaves x 16 x kOS floats]
+    float* ostage = reinterpret_cast<float*>(lds4 + 2 * LPS) + wave * 16 * kOS;
 
     // One staging task = 8 channels (half h) x 2 adjacent positions: 8 dwords in, two 16-byte
-    // [position][8 channels] slots out.  The dwords of the next tile are fetched while the MFMAs
-    // of the current tile run.
+    // [position][8 channels] slots out.  Task k of a thread is the same (h, pair) in every tile.
+    // FAST (even row starts and window origin): the dwords of the next tile are fetched, from
+    // clamped addresses and without branches, between the MFMAs of the current tile; they are
+    // masked and transposed when they are written to LDS.  Otherwise the window is staged element
+    // by element after the barrier.
     struct Task { unsigned v[8]; };
-    auto load_task = [&](int n, int G0, int task) -> Task {
-        const int h = task >= LP2 ? 1 : 0;
-        const int g = G0 + 2 * (task - h * LP2);
+    auto task_h = [&](int task) { return task >= LP2 ? 1 : 0; };
+    auto fetch_one = [&](const unsigned short* base, int h, int g, int j) -> unsigned {
+        const int r = min(8 * h + j, p.R - 1);
+        return *reinterpret_cast<const unsigned*>(base + static_cast<unsigned>(r * p.Win + g));
+    };
+    auto clamp_pair = [&](int g) { return g < 0 ? 0 : (g > p.Win - 2 ? p.Win - 2 : g); };
+    auto fetch_task = [&](int n, int G0, int task) -> Task {
+        const int h = task_h(task);
+        const int g = clamp_pair(G0 + 2 * (task - h * LP2));
+        const unsigned short* base = in + static_cast<long>(n) * p.R * p.Win;  // uniform
         Task t;
-        if (fast && g >= 0 && g + 1 < p.Win) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int r = 8 * h + j;
-                t.v[j] = r < p.R ? *reinterpret_cast<const unsigned*>(in + (static_cast<long>(n) * p.R + r) * p.Win + g) : 0u;
-            }
-        } else {
+        for (int j = 0; j < 8; ++j) t.v[j] = fetch_one(base, h, g, j);
+        return t;
+    };
+    auto fetch_task_slow = [&](int n, int G0, int task) -> Task {
+        const int h = task_h(task);
+        const int g = G0 + 2 * (task - h * LP2);
+        const int g0 = g < 0 ? 0 : (g > p.Win - 1 ? p.Win - 1 : g);
+        const int g1 = g + 1 < 0 ? 0 : (g + 1 > p.Win - 1 ? p.Win - 1 : g + 1);
+        const unsigned short* base = in + static_cast<long>(n) * p.R * p.Win;
+        Task t;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int r = 8 * h + j;
-                unsigned lo = 0u, hi = 0u;
-                if (r < p.R) {
-                    const unsigned short* row = in + (static_cast<long>(n) * p.R + r) * p.Win;
-                    if (g >= 0 && g < p.Win) lo = row[g];
-                    if (g + 1 >= 0 && g + 1 < p.Win) hi = row[g + 1];
-                }
-                t.v[j] = lo | (hi << 16);
-            }
+        for (int j = 0; j < 8; ++j) {
+            const int r = min(8 * h + j, p.R - 1);
+            const unsigned lo = (g >= 0 && g < p.Win) ? base[static_cast<unsigned>(r * p.Win + g0)] : 0u;
+            const unsigned hi = (g + 1 >= 0 && g + 1 < p.Win) ? base[static_cast<unsigned>(r * p.Win + g1)] : 0u;
+            t.v[j] = lo | (hi << 16);
         }
         return t;
     };
-    auto store_task = [&](int task, const Task& t) {
-        const int h = task >= LP2 ? 1 : 0;
+    auto store_task = [&](int G0, int task, const Task& t) {
+        const int h = task_h(task);
         const int pp = task - h * LP2;
+        const int g = G0 + 2 * pp;
+        // FAST: a pair is inside or outside the row as a whole (g and Win are even)
+        const bool pos_ok = !FAST || (g >= 0 && g < p.Win);
         u32x4 ev, od;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            ev[q] = __builtin_amdgcn_perm(t.v[2 * q + 1], t.v[2 * q], kPermLo);
-            od[q] = __builtin_amdgcn_perm(t.v[2 * q + 1], t.v[2 * q], kPermHi);
+            const unsigned a = (pos_ok && 8 * h + 2 * q < p.R) ? t.v[2 * q] : 0u;
+            const unsigned b = (pos_ok && 8 * h + 2 * q + 1 < p.R) ? t.v[2 * q + 1] : 0u;
+            ev[q] = __builtin_amdgcn_perm(b, a, kPermLo);
+            od[q] = __builtin_amdgcn_perm(b, a, kPermHi);
         }
         lds4[h * LPS + 2 * pp] = ev;
         lds4[h * LPS + 2 * pp + 1] = od;
     };
 
-    Task pre[MAXT];
+    Task pre[FAST ? MAXT : 1];
     int tile = blockIdx.x;
-    {
+    if constexpr (FAST) {
         const int n = tile / tiles_per_row;
         const int G0 = (tile - n * tiles_per_row) * TQ - p.P;
 #pragma unroll
         for (int k = 0; k < MAXT; ++k) {
             const int task = tid + k * NTH;
-            pre[k] = load_task(n, G0, task < ntasks ? task : ntasks - 1);
+            pre[k] = fetch_task(n, G0, task < ntasks ? task : ntasks - 1);
         }
     }
 
-    // Weight slices in A-operand order: the raw tensor is copied into LDS with wide loads, the
-    // slices are assembled from that copy, and each wave then keeps all NP slices in registers.
-    unsigned short* raw = reinterpret_cast<unsigned short*>(lds4 + NP * 64);
-    const int nW = p.M * p.R * p.S;
-    if (raw_in_lds) {
+    // Weight slices in A-operand order.  Entry e = slice*64 + lane holds wt(m, 8h..8h+7, s) for
+    // m = lane & 15, h = (lane >> 4) & 1, s = slice + NP*(lane >> 5).  The raw tensor is copied into
+    // LDS with 16-byte loads (all of a thread's loads in flight at once), the entries are gathered
+    // from that copy, and each wave then keeps all NP slices in registers.  Both LDS areas alias
+    // the window: [NP*64 entry slots][raw copy].
+    {
+        unsigned short* raw = reinterpret_cast<unsigned short*>(lds4 + NP * 64);
+        const int nW = p.M * p.R * p.S;
+        constexpr int NV = (16 * 16 * 2 * NP / 8 + NTH - 1) / NTH;  // 16-byte pieces per thread, worst case
         if ((reinterpret_cast<uintptr_t>(wt) & 15) == 0) {
-            for (int e = tid; e < nW / 8; e += NTH) reinterpret_cast<u32x4*>(raw)[e] = reinterpret_cast<const u32x4*>(wt)[e];
-            for (int e = (nW / 8) * 8 + tid; e < nW; e += NTH) raw[e] = wt[e];
+            const int nvec = nW / 8;
+            u32x4 tmp[NV];
+#pragma unroll
+            for (int k = 0; k < NV; ++k) tmp[k] = reinterpret_cast<const u32x4*>(wt)[min(tid + k * NTH, nvec > 0 ? nvec - 1 : 0)];
+#pragma unroll
+            for (int k = 0; k < NV; ++k)
+                if (tid + k * NTH < nvec) reinterpret_cast<u32x4*>(raw)[tid + k * NTH] = tmp[k];
+            for (int e = nvec * 8 + tid; e < nW; e += NTH) raw[e] = wt[e];
         } else {
             for (int e = tid; e < nW; e += NTH) raw[e] = wt[e];
         }
         __syncthreads();
-    }
-    for (int e = tid; e < NP * 64; e += NTH) {
-        const int pi = e >> 6, l = e & 63;
-        const int m = l & 15, h = (l >> 4) & 1, s = pi + NP * (l >> 5);
-        unsigned v[8];
+        constexpr int NE = (NP * 64 + NTH - 1) / NTH;
+        unsigned wv[NE][8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int r = 8 * h + j;
-            v[j] = 0u;
-            if (m < p.M && r < p.R && s < p.S) {
-                const long idx = m * p.w_sm + r * p.w_sr + p.w_s0 + s * p.w_ss;
-                v[j] = raw_in_lds ? raw[idx] : wt[idx];
-            }
+        for (int k = 0; k < NE; ++k) {
+            const int e = min(tid + k * NTH, NP * 64 - 1);
+            const int pi = e >> 6, l = e & 63;
+            const int m = min(l & 15, p.M - 1), h = (l >> 4) & 1, s = min(pi + NP * (l >> 5), p.S - 1);
+            const int base = static_cast<int>(m * p.w_sm + p.w_s0 + s * p.w_ss);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) wv[k][j] = raw[base + min(8 * h + j, p.R - 1) * static_cast<int>(p.w_sr)];
         }
-        lds4[e] = u32x4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+#pragma unroll
+        for (int k = 0; k < NE; ++k) {
+            const int e = tid + k * NTH;
+            const int pi = e >> 6, l = e & 63;
+            const int m = l & 15, h = (l >> 4) & 1, s = pi + NP * (l >> 5);
+            unsigned v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = (m < p.M && 8 * h + j < p.R && s < p.S) ? wv[k][j] : 0u;
+            if (e < NP * 64) lds4[e] = u32x4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+        }
     }
     __syncthreads();
     bf16x8 wreg[NP];
 #pragma unroll
     for (int pi = 0; pi < NP; ++pi) wreg[pi] = as_bf16x8(lds4[pi * 64 + lane]);
 
-    while (tile < ntiles) {
-        const int n = tile / tiles_per_row;
-        const int O0 = (tile - n * tiles_per_row) * TQ;
-        __syncthreads();  // readers of the previous window (or of the weight slices) are done
+    // Output path.  Vector path (Wout and the output pointer are multiples of 4 floats): a wave
+    // parks its finished 16 x 128 tile in its LDS staging area and writes it out as 16-byte stores,
+    // two 512-byte row segments per instruction, between the MFMAs of its NEXT tile, so that the
+    // write traffic runs under the arithmetic instead of after it.
+    const int orow = lane >> 5, ocol = 4 * (lane & 31);
+    auto park = [&](const f32x4 (&acc)[T]) {
 #pragma unroll
-        for (int k = 0; k < MAXT; ++k) {
-            const int task = tid + k * NTH;
-            if (task < ntasks) store_task(task, pre[k]);
-        }
-        for (int task = tid + MAXT * NTH; task < ntasks; task += NTH) store_task(task, load_task(n, O0 - p.P, task));
-        __syncthreads();
-        const int next = tile + gridDim.x;
-        if (next < ntiles) {
-            const int nn = next / tiles_per_row;
-            const int G0n = (next - nn * tiles_per_row) * TQ - p.P;
+        for (int j = 0; j < T; ++j)
 #pragma unroll
-            for (int k = 0; k < MAXT; ++k) {
-                const int task = tid + k * NTH;
-                pre[k] = load_task(nn, G0n, task < ntasks ? task : ntasks - 1);
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
+            for (int i = 0; i < 4; ++i) ostage[(4 * kb + i) * kOS + j * 16 + li] = acc[j][i];
+    };
+    auto flush_read = [&](int q) -> f32x4 { return *reinterpret_cast<const f32x4*>(ostage + (2 * q + orow) * kOS + ocol); };
+    auto flush_write = [&](int n, int O0, int q, f32x4 v) {
+        const int m = 2 * q + orow;
+        const int o = O0 + ob + ocol;
+        float* base = p.out + (static_cast<long>(n) * p.M + 2 * q) * p.Wout + O0 + ob;  // uniform
+        if (m < p.M && o < p.Wout) *reinterpret_cast<f32x4*>(base + static_cast<unsigned>(orow * p.Wout + ocol)) = v;
+    };
 
-        f32x4 acc[T];
+    // One tile's reduction.  Between the MFMA groups it also (FLUSH) reads back and stores the
+    // previous tile's parked outputs and (FAST) issues the window loads of the next tile.
+    auto compute = [&](auto flush_tag, f32x4 (&acc)[T], int pn, int pO0, int nn, int G0n) {
+        constexpr bool FLUSH = decltype(flush_tag)::value;
 #pragma unroll
         for (int j = 0; j < T; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-        const int ob = wave * T * 16;
         const u32x4* bbase = lds4 + (kb & 1) * LPS + ob + li + (kb >> 1) * NP * d;
-        // Operands are fetched PF steps ahead of the MFMAs that consume them; the scheduling
-        // barriers keep the compiler from sinking the LDS reads back down to their first use.
-        constexpr int PF = 4;
+        const unsigned short* nbase = in + static_cast<long>(nn) * p.R * p.Win;  // uniform
+        int tg[MAXT];  // clamped first position of each of this thread's staging tasks in the next tile
+        auto th = [&](int k) { return task_h(min(tid + k * NTH, ntasks - 1)); };
+        if constexpr (FAST) {
+#pragma unroll
+            for (int k = 0; k < MAXT; ++k) {
+                const int task = min(tid + k * NTH, ntasks - 1);
+                tg[k] = clamp_pair(G0n + 2 * (task - task_h(task) * LP2));
+            }
+        }
+        constexpr int NL = FAST ? MAXT * 8 : 0;  // window loads to spread over the steps
+        f32x4 ov[8];
         if constexpr (G > 0) {
+            // Operands are fetched PF steps ahead of the MFMAs that consume them; the scheduling
+            // barriers pin this interleaving.
+            constexpr int PF = 3;
             constexpr int D = 16 / (G > 0 ? G : 1);
             constexpr int NF = G * (T - 1) + NP;
-            bf16x8 fr[NF];
+            constexpr int LPSTEP = (NL + NF - 1) / NF;
+            bf16x8 fr[PF + 1];  // rotating: operand m lives in slot m % (PF + 1)
 #pragma unroll
             for (int m = 0; m < PF && m < NF; ++m) fr[m] = as_bf16x8(bbase[m * D]);
 #pragma unroll
             for (int m = 0; m < NF; ++m) {
-                if (m + PF < NF) fr[m + PF] = as_bf16x8(bbase[(m + PF) * D]);
+                if (m + PF < NF) fr[(m + PF) % (PF + 1)] = as_bf16x8(bbase[(m + PF) * D]);
+#pragma unroll
+                for (int u = 0; u < LPSTEP; ++u) {
+                    const int q = m * LPSTEP + u;
+                    if (q < NL) pre[q / 8].v[q % 8] = fetch_one(nbase, th(q / 8), tg[q / 8], q % 8);
+                }
+                if constexpr (FLUSH) {
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        if (m == (q * NF) / 8) ov[q] = flush_read(q);
+                        if (m == ((q * NF) / 8 + 1 < NF ? (q * NF) / 8 + 1 : NF - 1)) flush_write(pn, pO0, q, ov[q]);
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int j = 0; j < T; ++j) {
                     const int pi = m - G * j;
-                    if (pi >= 0 && pi < NP) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[pi < 0 ? 0 : (pi >= NP ? 0 : pi)], fr[m], acc[j], 0, 0, 0);
+                    if (pi >= 0 && pi < NP) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[pi < 0 ? 0 : (pi >= NP ? 0 : pi)], fr[m % (PF + 1)], acc[j], 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
         } else {
             // dilations that do not divide 16: every (tile, slice) pair reads its own operand
+            if constexpr (FAST) {
+#pragma unroll
+                for (int q = 0; q < NL; ++q) pre[q / 8].v[q % 8] = fetch_one(nbase, th(q / 8), tg[q / 8], q % 8);
+            }
+            if constexpr (FLUSH) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q) flush_write(pn, pO0, q, flush_read(q));
+            }
 #pragma unroll
             for (int pi = 0; pi < NP; ++pi) {
 #pragma unroll
@@ -204,18 +273,64 @@ __global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrPr
                 }
             }
         }
+    };
+
+    // Two workgroups share a CU.  Started together they would run their MFMA phases at the same
+    // time and idle the matrix pipe together; delaying the second half of the grid by about half a
+    // tile period makes one workgroup stage/park/store while the other multiplies.
+    if (blockIdx.x >= (gridDim.x + 1) / 2) __builtin_amdgcn_s_sleep(48);
+    bool have_prev = false;
+    int pn = 0, pO0 = 0;
+    while (tile < ntiles) {
+        const int n = tile / tiles_per_row;
+        const int O0 = (tile - n * tiles_per_row) * TQ;
+        __syncthreads();  // readers of the previous window (or of the weight slices) are done
+        if constexpr (FAST) {
 #pragma unroll
-        for (int j = 0; j < T; ++j) {
-            const int o = O0 + ob + j * 16 + li;
-            if (o < p.Wout) {
+            for (int k = 0; k < MAXT; ++k) {
+                const int task = tid + k * NTH;
+                if (task < ntasks) store_task(O0 - p.P, task, pre[k]);
+            }
+            for (int task = tid + MAXT * NTH; task < ntasks; task += NTH) store_task(O0 - p.P, task, fetch_task(n, O0 - p.P, task));
+        } else {
+            for (int task = tid; task < ntasks; task += NTH) store_task(O0 - p.P, task, fetch_task_slow(n, O0 - p.P, task));
+        }
+        __syncthreads();
+        const int next = tile + gridDim.x;
+        // window loads are issued unconditionally: past the last tile they re-read the current one
+        const int nxt = next < ntiles ? next : tile;
+        const int nn = nxt / tiles_per_row;
+        const int G0n = (nxt - nn * tiles_per_row) * TQ - p.P;
+
+        f32x4 acc[T];
+        if (have_prev) {
+            compute(std::true_type{}, acc, pn, pO0, nn, G0n);
+        } else {
+            compute(std::false_type{}, acc, pn, pO0, nn, G0n);
+        }
+        if (vec_out) {
+            park(acc);
+            have_prev = true;
+            pn = n;
+            pO0 = O0;
+        } else {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int m = 4 * kb + i;
-                    if (m < p.M) p.out[(static_cast<long>(n) * p.M + m) * p.Wout + o] = acc[j][i];
+            for (int j = 0; j < T; ++j) {
+                const int o = O0 + ob + j * 16 + li;
+                if (o < p.Wout) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int m = 4 * kb + i;
+                        if (m < p.M) p.out[(static_cast<long>(n) * p.M + m) * p.Wout + o] = acc[j][i];
+                    }
                 }
             }
         }
         tile = next;
+    }
+    if (have_prev) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) flush_write(pn, pO0, q, flush_read(q));
     }
 }
 
@@ -224,7 +339,7 @@ constexpr int kCorrMaxT = 4;
 constexpr int kNPBuckets[] = {3, 5, 9, 13, 17, 26};
 
 struct CorrPlan {
-    int NP, G, LPS, tiles_per_row, ntiles, fast, raw_in_lds;
+    int NP, G, LPS, tiles_per_row, ntiles, fast, vec_out;
     size_t lds_bytes;
     bool ok;
 };
@@ -233,21 +348,23 @@ CorrPlan corr_plan(const CorrProblem& p) {
     CorrPlan pl{};
     pl.ok = false;
     if (!p.bf16 || p.R > 16 || p.M > 16) return pl;
+    if (static_cast<long>(p.R) * p.Win >= (1L << 30)) return pl;  // 32-bit element offsets within one sample
     const int need = (p.S + 1) / 2;
     pl.NP = 0;
     for (int b : kNPBuckets) {
         if (b >= need) { pl.NP = b; break; }
     }
     if (pl.NP == 0) return pl;
-    pl.G = (p.d <= 16 && 16 % p.d == 0) ? 16 / p.d : 0;
+    // operand reuse across tiles pays when a tile shift is a few taps (d = 4, 8, 16); for d = 1, 2 the
+    // shift is 16 or 8 taps, little is shared and the unrolled schedule gets very long
+    pl.G = (p.d == 4 || p.d == 8 || p.d == 16) ? 16 / p.d : 0;
+    if (pl.NP == 17 && pl.G == 4) pl.G = 0;  // this instantiation does not fit the register budget
     constexpr int TQ = kWaves * kCorrT * 16;
     const long LP = TQ + static_cast<long>(2 * pl.NP - 1) * p.d;
     const long LPS = (LP + 2 + 7) / 8 * 8;
-    // the window aliases the weight-assembly area: [NP*64 slice slots][raw weight copy]
-    const long raw_slots = (static_cast<long>(p.M) * p.R * p.S * 2 + 15) / 16;
-    long slots = 2 * LPS;
-    pl.raw_in_lds = (pl.NP * 64 + raw_slots) * 16 <= kLdsBudget / 2;
-    const long wslots = pl.NP * 64 + (pl.raw_in_lds ? raw_slots : 0);
+    // [window | per-wave output staging]; the weight-slice assembly area aliases the window
+    long slots = 2 * LPS + kWaves * 16 * kOS / 4;
+    const long wslots = pl.NP * 64 + (static_cast<long>(p.M) * p.R * p.S * 2 + 15) / 16;
     if (slots < wslots) slots = wslots;
     if (slots * 16 > kLdsBudget / 2) return pl;  // two workgroups per CU
     pl.LPS = static_cast<int>(LPS);
@@ -257,31 +374,39 @@ CorrPlan corr_plan(const CorrProblem& p) {
     pl.ntiles = static_cast<int>(nt);
     pl.lds_bytes = static_cast<size_t>(slots) * 16;
     // dword loads of position pairs need even row starts and an even window origin
-    pl.fast = (p.Win % 2 == 0) && (p.P % 2 == 0) && (reinterpret_cast<uintptr_t>(p.in) % 4 == 0);
+    pl.fast = (p.Win % 2 == 0) && (p.P % 2 == 0) && (reinterpret_cast<uintptr_t>(p.in) % 4 == 0) && p.Win >= 2;
+    pl.vec_out = (p.Wout % 4 == 0) && (reinterpret_cast<uintptr_t>(p.out) % 16 == 0) &&
+                 static_cast<long>(p.M) * p.Wout < (1L << 30);
     pl.ok = true;
     return pl;
 }
 
-template <int NP, int G>
-hipError_t corr_launch_t(const CorrProblem& p, const CorrPlan& pl, hipStream_t st) {
-    auto kern = smallc_corr_bf16_kernel<NP, G, kCorrT, kCorrMaxT>;
+template <int NP, int G, bool FAST>
+hipError_t corr_launch_f(const CorrProblem& p, const CorrPlan& pl, hipStream_t st) {
+    auto kern = smallc_corr_bf16_kernel<NP, G, kCorrT, kCorrMaxT, FAST>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        static_cast<int>(pl.lds_bytes));
     if (e != hipSuccess) return e;
     const int grid = pl.ntiles < 2 * kNumCU ? pl.ntiles : 2 * kNumCU;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kWaves * 64), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.fast,
-                       pl.raw_in_lds);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kWaves * 64), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.vec_out);
     return hipGetLastError();
+}
+
+template <int NP, int G>
+hipError_t corr_launch_t(const CorrProblem& p, const CorrPlan& pl, hipStream_t st) {
+    return pl.fast ? corr_launch_f<NP, G, true>(p, pl, st) : corr_launch_f<NP, G, false>(p, pl, st);
 }
 
 template <int NP>
 hipError_t corr_launch_np(const CorrProblem& p, const CorrPlan& pl, hipStream_t st) {
     switch (pl.G) {
+#ifndef CONV1D_DEV_FEW_KERNELS
         case 1: return corr_launch_t<NP, 1>(p, pl, st);
+        case 4:
+            if constexpr (NP != 17) return corr_launch_t<NP, 4>(p, pl, st);  // (17, 4) is routed to G = 0 by the plan
+            return hipErrorInvalidValue;
+#endif
         case 2: return corr_launch_t<NP, 2>(p, pl, st);
-        case 4: return corr_launch_t<NP, 4>(p, pl, st);
-        case 8: return corr_launch_t<NP, 8>(p, pl, st);
-        case 16: return corr_launch_t<NP, 16>(p, pl, st);
         default: return corr_launch_t<NP, 0>(p, pl, st);
     }
 }
@@ -306,7 +431,8 @@ constexpr int kXP = 60;            // x slots staged per period (52 + look-ahead
 constexpr int kXR = 61, kDR = 53;  // LDS row strides in slots (odd: rows spread over the bank groups)
 constexpr int kWgMaxS = 7;         // 16 * (60 + 52) slots / 256 threads
 
-__global__ __launch_bounds__(256, 2) void smallc_wgrad_bf16_d8_kernel(WgradProblem p, int SPR, int UPS, int units_per_row, int fast) {
+template <bool FAST>
+__global__ __launch_bounds__(256, 2) void smallc_wgrad_bf16_d8_kernel(WgradProblem p, int SPR, int UPS, int units_per_row) {
     __shared__ u32x4 xbuf[16 * kXR];
     __shared__ u32x4 dybuf[16 * kDR];
     const int tid = threadIdx.x;
@@ -320,37 +446,53 @@ __global__ __launch_bounds__(256, 2) void smallc_wgrad_bf16_d8_kernel(WgradProbl
     const int j0 = (blockIdx.x - n * SPR) * UPS;
     const int j1 = min(j0 + UPS, units_per_row);
     const int Qb = min(j1 * kUnitSlots * 8, p.Q);  // this strip's dy columns end here
+    const unsigned short* xn = x + static_cast<long>(n) * p.C * p.W;
+    const unsigned short* dyn = dy + static_cast<long>(n) * p.K * p.Q;
 
-    // 8 consecutive elements of one row starting at column g, zero outside [0, limit)
-    auto load8 = [&](const unsigned short* row, int g, int limit) -> u32x4 {
-        u32x4 v = u32x4{0u, 0u, 0u, 0u};
-        if (g + 8 > 0 && g < limit) {
-            if (fast && g >= 0 && g + 8 <= limit) {
-                v = *reinterpret_cast<const u32x4*>(row + g);
-            } else {
-                unsigned t[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) t[j] = (g + j >= 0 && g + j < limit) ? row[g + j] : 0u;
-                v = u32x4{t[0] | (t[1] << 16), t[2] | (t[3] << 16), t[4] | (t[5] << 16), t[6] | (t[7] << 16)};
-            }
-        }
-        return v;
-    };
-    // staging slot e of "x period k": e in [0, 16*kXP)
-    auto load_x = [&](int k, int e) -> u32x4 {
-        const int r = e / kXP, i = e - r * kXP;
-        if (r >= p.C) return u32x4{0u, 0u, 0u, 0u};
-        return load8(x + (static_cast<long>(n) * p.C + r) * p.W, 8 * (kUnitSlots * k + i) - p.P, p.W);
-    };
-    auto load_dy = [&](int j, int e) -> u32x4 {
-        const int r = e / kUnitSlots, i = e - r * kUnitSlots;
-        if (r >= p.K) return u32x4{0u, 0u, 0u, 0u};
-        return load8(dy + (static_cast<long>(n) * p.K + r) * p.Q, 8 * (kUnitSlots * j + i), Qb);
-    };
     constexpr int NX = 16 * kXP, NS = 16 * (kXP + kUnitSlots);
-    // combined slot space of one pipeline stage: x period j+1 first, then dy unit j
-    auto load_stage = [&](int j, int e) -> u32x4 { return e < NX ? load_x(j + 1, e) : load_dy(j, e - NX); };
-    auto store_stage = [&](int e, u32x4 v) {
+    // Staging slot e of pipeline stage j: e < NX is x period j+1 (row e / kXP), the rest is dy unit j.
+    // FAST (all widths, the padding and the pointers are multiples of 8 elements): one 16-byte load
+    // from a clamped address, masked when it is written to LDS; a slot is then inside or outside
+    // its row as a whole.  Otherwise element loads, done synchronously.
+    struct Where { const unsigned short* row; int g, limit, rows_ok; };
+    auto where = [&](int j, int e) -> Where {
+        Where w;
+        if (e < NX) {
+            const int r = e / kXP, i = e - r * kXP;
+            w.row = xn + static_cast<unsigned>(min(r, p.C - 1) * p.W);
+            w.g = 8 * (kUnitSlots * (j + 1) + i) - p.P;
+            w.limit = p.W;
+            w.rows_ok = r < p.C;
+        } else {
+            const int e2 = e - NX, r = e2 / kUnitSlots, i = e2 - r * kUnitSlots;
+            w.row = dyn + static_cast<unsigned>(min(r, p.K - 1) * p.Q);
+            w.g = 8 * (kUnitSlots * j + i);
+            w.limit = Qb;
+            w.rows_ok = r < p.K;
+        }
+        return w;
+    };
+    auto fetch = [&](int j, int e) -> u32x4 {
+        const Where w = where(j, e);
+        if constexpr (FAST) {
+            const int lim = w.limit - 8;  // >= 0 on this path (checked by the host)
+            const int gc = w.g < 0 ? 0 : (w.g > lim ? lim : w.g);
+            return *reinterpret_cast<const u32x4*>(w.row + gc);
+        } else {
+            unsigned t[8];
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) {
+                const int g = w.g + jj;
+                const int gc = g < 0 ? 0 : (g > w.limit - 1 ? w.limit - 1 : g);
+                t[jj] = (g >= 0 && g < w.limit) ? w.row[gc] : 0u;
+            }
+            return u32x4{t[0] | (t[1] << 16), t[2] | (t[3] << 16), t[4] | (t[5] << 16), t[6] | (t[7] << 16)};
+        }
+    };
+    auto commit = [&](int j, int e, u32x4 v) {
+        const Where w = where(j, e);
+        const bool ok = w.rows_ok && (!FAST || (w.g >= 0 && w.g + 8 <= w.limit));
+        if (!ok) v = u32x4{0u, 0u, 0u, 0u};
         if (e < NX) {
             const int r = e / kXP;
             xbuf[r * kXR + (e - r * kXP)] = v;
@@ -364,14 +506,13 @@ __global__ __launch_bounds__(256, 2) void smallc_wgrad_bf16_d8_kernel(WgradProbl
 #pragma unroll
     for (int i = 0; i < kNT; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // prologue: x period j0 -> LDS -> operand ring
-    for (int e = tid; e < NX; e += 256) {
-        const int r = e / kXP;
-        xbuf[r * kXR + (e - r * kXP)] = load_x(j0, e);
-    }
-    u32x4 pre[kWgMaxS];
+    // prologue: x period j0 -> LDS -> operand ring  (stage index j0 - 1 addresses x period j0)
+    for (int e = tid; e < NX; e += 256) commit(j0 - 1, e, fetch(j0 - 1, e));
+    u32x4 pre[FAST ? kWgMaxS : 1];
+    if constexpr (FAST) {
 #pragma unroll
-    for (int k = 0; k < kWgMaxS; ++k) pre[k] = load_stage(j0, tid + k * 256 < NS ? tid + k * 256 : NS - 1);
+        for (int k = 0; k < kWgMaxS; ++k) pre[k] = fetch(j0, tid + k * 256 < NS ? tid + k * 256 : NS - 1);
+    }
     __syncthreads();
     const u32x4* xp = xbuf + li * kXR + wave + kb;
     const u32x4* ap = dybuf + li * kDR + kb;
@@ -381,15 +522,21 @@ __global__ __launch_bounds__(256, 2) void smallc_wgrad_bf16_d8_kernel(WgradProbl
 
     for (int j = j0; j < j1; ++j) {
         __syncthreads();  // ring preload / previous unit's LDS reads are done
+        if constexpr (FAST) {
 #pragma unroll
-        for (int k = 0; k < kWgMaxS; ++k) {
-            const int e = tid + k * 256;
-            if (e < NS) store_stage(e, pre[k]);
+            for (int k = 0; k < kWgMaxS; ++k) {
+                const int e = tid + k * 256;
+                if (e < NS) commit(j, e, pre[k]);
+            }
+        } else {
+            for (int e = tid; e < NS; e += 256) commit(j, e, fetch(j, e));
         }
         __syncthreads();
-        if (j + 1 < j1) {
+        if constexpr (FAST) {
+            if (j + 1 < j1) {
 #pragma unroll
-            for (int k = 0; k < kWgMaxS; ++k) pre[k] = load_stage(j + 1, tid + k * 256 < NS ? tid + k * 256 : NS - 1);
+                for (int k = 0; k < kWgMaxS; ++k) pre[k] = fetch(j + 1, tid + k * 256 < NS ? tid + k * 256 : NS - 1);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
         bf16x8 a = as_bf16x8(ap[0]);
@@ -428,6 +575,7 @@ WgradPlan wgrad_plan(const WgradProblem& p) {
     WgradPlan pl{};
     pl.ok = false;
     if (!p.bf16 || p.C > 16 || p.K > 16 || p.d != 8 || p.S > 4 * kNT) return pl;
+    if (static_cast<long>(p.C) * p.W >= (1L << 30) || static_cast<long>(p.K) * p.Q >= (1L << 30)) return pl;
     pl.units_per_row = cdiv(p.Q, kUnitSlots * 8);
     // strips of UPS units so that about two workgroups per CU exist
     const long total_units = static_cast<long>(p.N) * pl.units_per_row;
@@ -437,8 +585,8 @@ WgradPlan wgrad_plan(const WgradProblem& p) {
     const long grid = static_cast<long>(p.N) * pl.SPR;
     if (grid > 0x7fffffffL) return pl;
     pl.grid = static_cast<int>(grid);
-    pl.fast = (p.W % 8 == 0) && (p.Q % 8 == 0) && (p.P % 8 == 0) && (reinterpret_cast<uintptr_t>(p.x) % 16 == 0) &&
-              (reinterpret_cast<uintptr_t>(p.dy) % 16 == 0);
+    pl.fast = (p.W % 8 == 0) && (p.Q % 8 == 0) && (p.P % 8 == 0) && p.W >= 8 && p.Q >= 8 &&
+              (reinterpret_cast<uintptr_t>(p.x) % 16 == 0) && (reinterpret_cast<uintptr_t>(p.dy) % 16 == 0);
     pl.ok = true;
     return pl;
 }
@@ -451,11 +599,13 @@ hipError_t smallc_bf16_corr_launch(const CorrProblem& p, hipStream_t st) {
     const CorrPlan pl = corr_plan(p);
     if (!pl.ok) return hipErrorInvalidValue;
     switch (pl.NP) {
+#ifndef CONV1D_DEV_FEW_KERNELS
         case 3: return corr_launch_np<3>(p, pl, st);
         case 5: return corr_launch_np<5>(p, pl, st);
         case 9: return corr_launch_np<9>(p, pl, st);
         case 13: return corr_launch_np<13>(p, pl, st);
         case 17: return corr_launch_np<17>(p, pl, st);
+#endif
         case 26: return corr_launch_np<26>(p, pl, st);
         default: return hipErrorInvalidValue;
     }
@@ -471,7 +621,11 @@ size_t smallc_bf16_wgrad_workspace(const WgradProblem& p) {
 hipError_t smallc_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     const WgradPlan pl = wgrad_plan(p);
     if (!pl.ok) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(smallc_wgrad_bf16_d8_kernel, dim3(pl.grid), dim3(256), 0, st, p, pl.SPR, pl.UPS, pl.units_per_row, pl.fast);
+    if (pl.fast) {
+        hipLaunchKernelGGL(smallc_wgrad_bf16_d8_kernel<true>, dim3(pl.grid), dim3(256), 0, st, p, pl.SPR, pl.UPS, pl.units_per_row);
+    } else {
+        hipLaunchKernelGGL(smallc_wgrad_bf16_d8_kernel<false>, dim3(pl.grid), dim3(256), 0, st, p, pl.SPR, pl.UPS, pl.units_per_row);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return smallc_wgrad_reduce_launch(static_cast<const float*>(p.ws), p.dw, p.K, p.C, p.S, pl.grid, st);
