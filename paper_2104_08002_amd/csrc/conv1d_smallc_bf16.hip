@@ -124,21 +124,23 @@ __global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrPr
 
     Task pre[FAST ? MAXT : 1];
     int tile = blockIdx.x;
-    if constexpr (FAST) {
-        const int n = tile / tiles_per_row;
-        const int G0 = (tile - n * tiles_per_row) * TQ - p.P;
-#pragma unroll
-        for (int k = 0; k < MAXT; ++k) {
-            const int task = tid + k * NTH;
-            pre[k] = fetch_task(n, G0, task < ntasks ? task : ntasks - 1);
-        }
-    }
 
     // Weight slices in A-operand order.  Entry e = slice*64 + lane holds wt(m, 8h..8h+7, s) for
     // m = lane & 15, h = (lane >> 4) & 1, s = slice + NP*(lane >> 5).  The raw tensor is copied into
     // LDS with 16-byte loads (all of a thread's loads in flight at once), the entries are gathered
     // from that copy, and each wave then keeps all NP slices in registers.  Both LDS areas alias
     // the window: [NP*64 entry slots][raw copy].
+    auto prefetch_first = [&]() {
+        if constexpr (FAST) {
+            const int n = tile / tiles_per_row;
+            const int G0 = (tile - n * tiles_per_row) * TQ - p.P;
+#pragma unroll
+            for (int k = 0; k < MAXT; ++k) {
+                const int task = tid + k * NTH;
+                pre[k] = fetch_task(n, G0, task < ntasks ? task : ntasks - 1);
+            }
+        }
+    };
     {
         unsigned short* raw = reinterpret_cast<unsigned short*>(lds4 + NP * 64);
         const int nW = p.M * p.R * p.S;
@@ -148,12 +150,15 @@ __global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrPr
             u32x4 tmp[NV];
 #pragma unroll
             for (int k = 0; k < NV; ++k) tmp[k] = reinterpret_cast<const u32x4*>(wt)[min(tid + k * NTH, nvec > 0 ? nvec - 1 : 0)];
+            prefetch_first();  // queued behind the weight loads, so the weights are not held up by them
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int k = 0; k < NV; ++k)
                 if (tid + k * NTH < nvec) reinterpret_cast<u32x4*>(raw)[tid + k * NTH] = tmp[k];
             for (int e = nvec * 8 + tid; e < nW; e += NTH) raw[e] = wt[e];
         } else {
             for (int e = tid; e < nW; e += NTH) raw[e] = wt[e];
+            prefetch_first();
         }
         __syncthreads();
         constexpr int NE = (NP * 64 + NTH - 1) / NTH;
