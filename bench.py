@@ -34,6 +34,17 @@ def algorithmic_bytes(wl, p):
     return x * e + dy * e + w * 4
 
 
+def stored_traffic(workload, pass_name):
+    """HBM bytes per launch of one pass, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a
+    plain copy of known size; read from profiles/hbm_traffic.json when that summary exists, else None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f)[workload][pass_name]["bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -42,6 +53,8 @@ def main() -> int:
     ap.add_argument("--workload", default="genomics_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--variant", type=int, default=0, help="force a kernel family (0 = auto)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 256 MiB device-to-device copy 5 times (reference for HBM byte counters)")
     ap.add_argument("--passes", default=",".join(PASSES),
                     help="comma-separated subset of passes to run (profiling runs; the headline needs all three)")
     args = ap.parse_args()
@@ -58,6 +71,14 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    if args.calibrate_copy:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": 256 << 20, "launches": 5}))
+        return 0
     binding.load()
     binding.conv1d_set_variant(args.variant)
     wl = inputs.WORKLOADS[args.workload]
@@ -128,7 +149,8 @@ def main() -> int:
     else:
         roof = {"bound": "mfma", "achieved": per_pass[dom]["tflops"], "peak": PEAK[wl.dtype], "unit": "TFLOP/s",
                 "frac": per_pass[dom]["frac_mfma_peak"]}
-    roof.update({"kernel": per_pass[dom]["kernel"], "pass": dom, "avg_us": per_pass[dom]["avg_us"], "traffic": None})
+    roof.update({"kernel": per_pass[dom]["kernel"], "pass": dom, "avg_us": per_pass[dom]["avg_us"],
+                 "traffic": stored_traffic(wl.name, dom)})
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -42,18 +42,31 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast
 // k-slot layout of one MFMA (lane = li + 16*kb, element j of the lane's 8):
 //   channel r = 8*(kb & 1) + j,  tap s = p + NP*(kb >> 1)
 // LDS: plane h = kb & 1 holds channels 8h..8h+7; slot (h*LPS + i) <-> input position G0 + i.
-constexpr int kOS = 132;  // row stride (floats) of a wave's output staging tile: 4 rows apart -> 16 banks apart
+constexpr int kOS = 132;                    // row stride (floats) of an output staging tile: 4 rows apart -> 16 banks apart
+constexpr int kOstSlots = 4 * 16 * kOS / 4;  // 16-byte slots of one staging buffer (4 consumer waves x 16 rows)
 
+// Workgroup = 8 waves with two roles, one workgroup per CU, persistent over a contiguous strip of tiles
+// (512 output columns of one sample each):
+//   waves 0-3 ("consumers") keep the weight slices in registers and do nothing but LDS operand reads,
+//             MFMAs and parking their finished 16 x 128 output tile in LDS;
+//   waves 4-7 ("producers") fetch the window of tile t+2 from global memory into registers, transpose
+//             the window of tile t+1 into the free LDS window buffer, and write the parked outputs of
+//             tile t-1 to global memory as 16-byte stores (two 512-byte row segments per instruction).
+// One workgroup barrier per tile hands the buffers over.  The matrix pipe of every SIMD is fed by a wave
+// whose instruction stream is almost pure MFMA, and the memory traffic of both directions runs under it.
+// LDS (16-byte slots): window buffer b at b*2*LPS (two planes of LPS slots), staging buffer b at
+// 4*LPS + b*kOstSlots; the weight-slice assembly area aliases the staging buffers before the first tile.
 template <int NP, int G, int T, int MAXT, bool FAST>
-__global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrProblem p, int tiles_per_row, int ntiles, int LPS,
-                                                                          int vec_out) {
+__global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p, int tiles_per_row, int ntiles, int LPS, int vec_out) {
     static_assert(T == 8, "the output staging tile is 16 rows x 128 columns");
     extern __shared__ u32x4 lds4[];
-    constexpr int TQ = kWaves * T * 16;
-    constexpr int NTH = kWaves * 64;
+    constexpr int TQ = 4 * T * 16;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool consumer = wave < 4;
+    const int cw = wave & 3;   // consumer wave index / the consumer wave this producer wave serves
+    const int rtid = tid & 255;  // thread index within the role group
     const int li = lane & 15;
     const int kb = lane >> 4;
     const unsigned short* __restrict__ in = static_cast<const unsigned short*>(p.in);
@@ -62,30 +75,35 @@ __global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrPr
     const int LP = TQ + (2 * NP - 1) * d;
     const int LP2 = (LP + 1) >> 1;
     const int ntasks = 2 * LP2;
-    const int ob = wave * T * 16;
-    // LDS: [window: 2*LPS slots][output staging: kWaves x 16 x kOS floats]
-    float* ostage = reinterpret_cast<float*>(lds4 + 2 * LPS) + wave * 16 * kOS;
+    const int ob = cw * T * 16;
+    auto win = [&](int b) { return lds4 + b * 2 * LPS; };
+    auto ost = [&](int b) { return reinterpret_cast<float*>(lds4 + 4 * LPS + b * kOstSlots) + cw * 16 * kOS; };
 
+    // Contiguous strip of tiles per workgroup.  Workgroups are dealt round-robin to the 8 XCDs, so the
+    // logical index puts neighbouring strips (which share halos) on the same XCD and its L2.
+    int lid = blockIdx.x;
+    if ((gridDim.x & 7) == 0) lid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int t_begin = static_cast<int>(static_cast<long>(lid) * ntiles / gridDim.x);
+    const int t_end = static_cast<int>(static_cast<long>(lid + 1) * ntiles / gridDim.x);
+
+    // ---- producer side: window staging -----------------------------------------------------------
     // One staging task = 8 channels (half h) x 2 adjacent positions: 8 dwords in, two 16-byte
-    // [position][8 channels] slots out.  Task k of a thread is the same (h, pair) in every tile.
-    // FAST (even row starts and window origin): the dwords of the next tile are fetched, from
-    // clamped addresses and without branches, between the MFMAs of the current tile; they are
-    // masked and transposed when they are written to LDS.  Otherwise the window is staged element
-    // by element after the barrier.
+    // [position][8 channels] slots out.  FAST (even row starts and window origin): branch-free dword
+    // loads from clamped addresses, masked when written to LDS, fetched one tile ahead.  Otherwise
+    // element loads, done when the window is written.
     struct Task { unsigned v[8]; };
     auto task_h = [&](int task) { return task >= LP2 ? 1 : 0; };
-    auto fetch_one = [&](const unsigned short* base, int h, int g, int j) -> unsigned {
-        const int r = min(8 * h + j, p.R - 1);
-        return *reinterpret_cast<const unsigned*>(base + static_cast<unsigned>(r * p.Win + g));
-    };
-    auto clamp_pair = [&](int g) { return g < 0 ? 0 : (g > p.Win - 2 ? p.Win - 2 : g); };
     auto fetch_task = [&](int n, int G0, int task) -> Task {
         const int h = task_h(task);
-        const int g = clamp_pair(G0 + 2 * (task - h * LP2));
+        int g = G0 + 2 * (task - h * LP2);
+        g = g < 0 ? 0 : (g > p.Win - 2 ? p.Win - 2 : g);
         const unsigned short* base = in + static_cast<long>(n) * p.R * p.Win;  // uniform
         Task t;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) t.v[j] = fetch_one(base, h, g, j);
+        for (int j = 0; j < 8; ++j) {
+            const int r = min(8 * h + j, p.R - 1);
+            t.v[j] = *reinterpret_cast<const unsigned*>(base + static_cast<unsigned>(r * p.Win + g));
+        }
         return t;
     };
     auto fetch_task_slow = [&](int n, int G0, int task) -> Task {
@@ -104,7 +122,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrPr
         }
         return t;
     };
-    auto store_task = [&](int G0, int task, const Task& t) {
+    auto store_task = [&](u32x4* wb, int G0, int task, const Task& t) {
         const int h = task_h(task);
         const int pp = task - h * LP2;
         const int g = G0 + 2 * pp;
@@ -118,54 +136,91 @@ __global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrPr
             ev[q] = __builtin_amdgcn_perm(b, a, kPermLo);
             od[q] = __builtin_amdgcn_perm(b, a, kPermHi);
         }
-        lds4[h * LPS + 2 * pp] = ev;
-        lds4[h * LPS + 2 * pp + 1] = od;
+        wb[h * LPS + 2 * pp] = ev;
+        wb[h * LPS + 2 * pp + 1] = od;
     };
-
+    auto tile_n = [&](int t) { return t / tiles_per_row; };
+    auto tile_O0 = [&](int t) { return (t - (t / tiles_per_row) * tiles_per_row) * TQ; };
     Task pre[FAST ? MAXT : 1];
-    int tile = blockIdx.x;
-
-    // Weight slices in A-operand order.  Entry e = slice*64 + lane holds wt(m, 8h..8h+7, s) for
-    // m = lane & 15, h = (lane >> 4) & 1, s = slice + NP*(lane >> 5).  The raw tensor is copied into
-    // LDS with 16-byte loads (all of a thread's loads in flight at once), the entries are gathered
-    // from that copy, and each wave then keeps all NP slices in registers.  Both LDS areas alias
-    // the window: [NP*64 entry slots][raw copy].
-    auto prefetch_first = [&]() {
+    auto prefetch = [&](int t) {  // producers: window of tile t -> registers
         if constexpr (FAST) {
-            const int n = tile / tiles_per_row;
-            const int G0 = (tile - n * tiles_per_row) * TQ - p.P;
+            const int n = tile_n(t), G0 = tile_O0(t) - p.P;
 #pragma unroll
             for (int k = 0; k < MAXT; ++k) {
-                const int task = tid + k * NTH;
+                const int task = rtid + k * 256;
                 pre[k] = fetch_task(n, G0, task < ntasks ? task : ntasks - 1);
             }
         }
     };
+    auto commit = [&](int t, u32x4* wb) {  // producers: registers (or memory) -> LDS window of tile t
+        const int n = tile_n(t), G0 = tile_O0(t) - p.P;
+        if constexpr (FAST) {
+#pragma unroll
+            for (int k = 0; k < MAXT; ++k) {
+                const int task = rtid + k * 256;
+                if (task < ntasks) store_task(wb, G0, task, pre[k]);
+            }
+            for (int task = rtid + MAXT * 256; task < ntasks; task += 256) store_task(wb, G0, task, fetch_task(n, G0, task));
+        } else {
+            for (int task = rtid; task < ntasks; task += 256) store_task(wb, G0, task, fetch_task_slow(n, G0, task));
+        }
+    };
+    // producers: parked outputs of tile t (staging buffer b) -> global memory
+    auto flush = [&](int t, int b) {
+        const int n = tile_n(t), O0 = tile_O0(t);
+        const float* src = ost(b);
+        if (vec_out) {
+            const int orow = lane >> 5, ocol = 4 * (lane & 31);
+            const int o = O0 + ob + ocol;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const f32x4 v = *reinterpret_cast<const f32x4*>(src + (2 * q + orow) * kOS + ocol);
+                float* base = p.out + (static_cast<long>(n) * p.M + 2 * q) * p.Wout + O0 + ob;  // uniform
+                if (2 * q + orow < p.M && o < p.Wout) *reinterpret_cast<f32x4*>(base + static_cast<unsigned>(orow * p.Wout + ocol)) = v;
+            }
+        } else {
+            for (int idx = lane; idx < 16 * T * 16; idx += 64) {
+                const int m = idx / (T * 16), col = idx - m * (T * 16);
+                const int o = O0 + ob + col;
+                if (m < p.M && o < p.Wout) p.out[(static_cast<long>(n) * p.M + m) * p.Wout + o] = src[m * kOS + col];
+            }
+        }
+    };
+
+    // ---- prologue: weight slices (all waves copy, consumers assemble) and the first window ---------
+    // Entry e = slice*64 + lane holds wt(m, 8h..8h+7, s) for m = lane & 15, h = (lane >> 4) & 1,
+    // s = slice + NP*(lane >> 5).  The raw tensor is copied into LDS with 16-byte loads (all of a
+    // thread's loads in flight at once), the entries are gathered from that copy, and each consumer wave
+    // then keeps all NP slices in registers.  Both areas alias the output staging buffers.
+    u32x4* entries = lds4 + 4 * LPS;
+    unsigned short* raw = reinterpret_cast<unsigned short*>(entries + NP * 64);
     {
-        unsigned short* raw = reinterpret_cast<unsigned short*>(lds4 + NP * 64);
         const int nW = p.M * p.R * p.S;
-        constexpr int NV = (16 * 16 * 2 * NP / 8 + NTH - 1) / NTH;  // 16-byte pieces per thread, worst case
+        constexpr int NV = (16 * 16 * 2 * NP / 8 + 511) / 512;  // 16-byte pieces per thread, worst case
         if ((reinterpret_cast<uintptr_t>(wt) & 15) == 0) {
             const int nvec = nW / 8;
             u32x4 tmp[NV];
 #pragma unroll
-            for (int k = 0; k < NV; ++k) tmp[k] = reinterpret_cast<const u32x4*>(wt)[min(tid + k * NTH, nvec > 0 ? nvec - 1 : 0)];
-            prefetch_first();  // queued behind the weight loads, so the weights are not held up by them
+            for (int k = 0; k < NV; ++k) tmp[k] = reinterpret_cast<const u32x4*>(wt)[min(tid + k * 512, nvec > 0 ? nvec - 1 : 0)];
+            if (!consumer && t_begin < t_end) prefetch(t_begin);  // queued behind the weight loads
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int k = 0; k < NV; ++k)
-                if (tid + k * NTH < nvec) reinterpret_cast<u32x4*>(raw)[tid + k * NTH] = tmp[k];
-            for (int e = nvec * 8 + tid; e < nW; e += NTH) raw[e] = wt[e];
+                if (tid + k * 512 < nvec) reinterpret_cast<u32x4*>(raw)[tid + k * 512] = tmp[k];
+            for (int e = nvec * 8 + tid; e < nW; e += 512) raw[e] = wt[e];
         } else {
-            for (int e = tid; e < nW; e += NTH) raw[e] = wt[e];
-            prefetch_first();
+            for (int e = tid; e < nW; e += 512) raw[e] = wt[e];
+            if (!consumer && t_begin < t_end) prefetch(t_begin);
         }
-        __syncthreads();
-        constexpr int NE = (NP * 64 + NTH - 1) / NTH;
+    }
+    __syncthreads();
+    bf16x8 wreg[NP];
+    if (consumer) {
+        constexpr int NE = (NP * 64 + 255) / 256;
         unsigned wv[NE][8];
 #pragma unroll
         for (int k = 0; k < NE; ++k) {
-            const int e = min(tid + k * NTH, NP * 64 - 1);
+            const int e = min(rtid + k * 256, NP * 64 - 1);
             const int pi = e >> 6, l = e & 63;
             const int m = min(l & 15, p.M - 1), h = (l >> 4) & 1, s = min(pi + NP * (l >> 5), p.S - 1);
             const int base = static_cast<int>(m * p.w_sm + p.w_s0 + s * p.w_ss);
@@ -174,65 +229,42 @@ __global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrPr
         }
 #pragma unroll
         for (int k = 0; k < NE; ++k) {
-            const int e = tid + k * NTH;
+            const int e = rtid + k * 256;
             const int pi = e >> 6, l = e & 63;
             const int m = l & 15, h = (l >> 4) & 1, s = pi + NP * (l >> 5);
             unsigned v[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) v[j] = (m < p.M && 8 * h + j < p.R && s < p.S) ? wv[k][j] : 0u;
-            if (e < NP * 64) lds4[e] = u32x4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+            if (e < NP * 64) entries[e] = u32x4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
         }
+    } else if (t_begin < t_end) {
+        commit(t_begin, win(0));
+        if (t_begin + 1 < t_end) prefetch(t_begin + 1);
     }
     __syncthreads();
-    bf16x8 wreg[NP];
+    if (consumer) {
 #pragma unroll
-    for (int pi = 0; pi < NP; ++pi) wreg[pi] = as_bf16x8(lds4[pi * 64 + lane]);
+        for (int pi = 0; pi < NP; ++pi) wreg[pi] = as_bf16x8(entries[pi * 64 + lane]);
+    }
+    __syncthreads();  // the slice entries alias the staging buffers: every wave has its copy before anyone parks
 
-    // Output path.  Vector path (Wout and the output pointer are multiples of 4 floats): a wave
-    // parks its finished 16 x 128 tile in its LDS staging area and writes it out as 16-byte stores,
-    // two 512-byte row segments per instruction, between the MFMAs of its NEXT tile, so that the
-    // write traffic runs under the arithmetic instead of after it.
-    const int orow = lane >> 5, ocol = 4 * (lane & 31);
-    auto park = [&](const f32x4 (&acc)[T]) {
-#pragma unroll
-        for (int j = 0; j < T; ++j)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) ostage[(4 * kb + i) * kOS + j * 16 + li] = acc[j][i];
-    };
-    auto flush_read = [&](int q) -> f32x4 { return *reinterpret_cast<const f32x4*>(ostage + (2 * q + orow) * kOS + ocol); };
-    auto flush_write = [&](int n, int O0, int q, f32x4 v) {
-        const int m = 2 * q + orow;
-        const int o = O0 + ob + ocol;
-        float* base = p.out + (static_cast<long>(n) * p.M + 2 * q) * p.Wout + O0 + ob;  // uniform
-        if (m < p.M && o < p.Wout) *reinterpret_cast<f32x4*>(base + static_cast<unsigned>(orow * p.Wout + ocol)) = v;
-    };
-
-    // One tile's reduction.  Between the MFMA groups it also (FLUSH) reads back and stores the
-    // previous tile's parked outputs and (FAST) issues the window loads of the next tile.
-    auto compute = [&](auto flush_tag, f32x4 (&acc)[T], int pn, int pO0, int nn, int G0n) {
-        constexpr bool FLUSH = decltype(flush_tag)::value;
+    // ---- consumer side: one tile's reduction, parked in LDS ------------------------------------------
+    auto compute = [&](const u32x4* wb, float* dst) {
+        f32x4 acc[T];
 #pragma unroll
         for (int j = 0; j < T; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-        const u32x4* bbase = lds4 + (kb & 1) * LPS + ob + li + (kb >> 1) * NP * d;
-        const unsigned short* nbase = in + static_cast<long>(nn) * p.R * p.Win;  // uniform
-        int tg[MAXT];  // clamped first position of each of this thread's staging tasks in the next tile
-        auto th = [&](int k) { return task_h(min(tid + k * NTH, ntasks - 1)); };
-        if constexpr (FAST) {
+        const u32x4* bbase = wb + (kb & 1) * LPS + ob + li + (kb >> 1) * NP * d;
+        auto park = [&](int j) {
 #pragma unroll
-            for (int k = 0; k < MAXT; ++k) {
-                const int task = min(tid + k * NTH, ntasks - 1);
-                tg[k] = clamp_pair(G0n + 2 * (task - task_h(task) * LP2));
-            }
-        }
-        constexpr int NL = FAST ? MAXT * 8 : 0;  // window loads to spread over the steps
-        f32x4 ov[8];
+            for (int i = 0; i < 4; ++i) dst[(4 * kb + i) * kOS + j * 16 + li] = acc[j][i];
+        };
         if constexpr (G > 0) {
-            // Operands are fetched PF steps ahead of the MFMAs that consume them; the scheduling
-            // barriers pin this interleaving.
+            // Operand m serves (tile j, slice m - G*j) for every j.  Operands are fetched PF steps ahead
+            // of their MFMAs; tile j is complete after step G*j + NP - 1 and is parked two steps later.
+            // The scheduling barriers pin this interleaving.
             constexpr int PF = 3;
             constexpr int D = 16 / (G > 0 ? G : 1);
             constexpr int NF = G * (T - 1) + NP;
-            constexpr int LPSTEP = (NL + NF - 1) / NF;
             bf16x8 fr[PF + 1];  // rotating: operand m lives in slot m % (PF + 1)
 #pragma unroll
             for (int m = 0; m < PF && m < NF; ++m) fr[m] = as_bf16x8(bbase[m * D]);
@@ -240,17 +272,8 @@ __global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrPr
             for (int m = 0; m < NF; ++m) {
                 if (m + PF < NF) fr[(m + PF) % (PF + 1)] = as_bf16x8(bbase[(m + PF) * D]);
 #pragma unroll
-                for (int u = 0; u < LPSTEP; ++u) {
-                    const int q = m * LPSTEP + u;
-                    if (q < NL) pre[q / 8].v[q % 8] = fetch_one(nbase, th(q / 8), tg[q / 8], q % 8);
-                }
-                if constexpr (FLUSH) {
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) {
-                        if (m == (q * NF) / 8) ov[q] = flush_read(q);
-                        if (m == ((q * NF) / 8 + 1 < NF ? (q * NF) / 8 + 1 : NF - 1)) flush_write(pn, pO0, q, ov[q]);
-                    }
-                }
+                for (int j = 0; j < T; ++j)
+                    if (G * j + NP - 1 == m - 2) park(j);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int j = 0; j < T; ++j) {
@@ -259,16 +282,11 @@ __global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrPr
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
+#pragma unroll
+            for (int j = 0; j < T; ++j)
+                if (G * j + NP - 1 > NF - 3) park(j);
         } else {
-            // dilations that do not divide 16: every (tile, slice) pair reads its own operand
-            if constexpr (FAST) {
-#pragma unroll
-                for (int q = 0; q < NL; ++q) pre[q / 8].v[q % 8] = fetch_one(nbase, th(q / 8), tg[q / 8], q % 8);
-            }
-            if constexpr (FLUSH) {
-#pragma unroll
-                for (int q = 0; q < 8; ++q) flush_write(pn, pO0, q, flush_read(q));
-            }
+            // dilations without operand sharing between tiles: every (tile, slice) pair reads its own operand
 #pragma unroll
             for (int pi = 0; pi < NP; ++pi) {
 #pragma unroll
@@ -277,66 +295,26 @@ __global__ __launch_bounds__(kWaves * 64, 2) void smallc_corr_bf16_kernel(CorrPr
                     acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[pi], f, acc[j], 0, 0, 0);
                 }
             }
+#pragma unroll
+            for (int j = 0; j < T; ++j) park(j);
         }
     };
 
-    // Two workgroups share a CU.  Started together they would run their MFMA phases at the same
-    // time and idle the matrix pipe together; delaying the second half of the grid by about half a
-    // tile period makes one workgroup stage/park/store while the other multiplies.
-    if (blockIdx.x >= (gridDim.x + 1) / 2) __builtin_amdgcn_s_sleep(48);
-    bool have_prev = false;
-    int pn = 0, pO0 = 0;
-    while (tile < ntiles) {
-        const int n = tile / tiles_per_row;
-        const int O0 = (tile - n * tiles_per_row) * TQ;
-        __syncthreads();  // readers of the previous window (or of the weight slices) are done
-        if constexpr (FAST) {
-#pragma unroll
-            for (int k = 0; k < MAXT; ++k) {
-                const int task = tid + k * NTH;
-                if (task < ntasks) store_task(O0 - p.P, task, pre[k]);
-            }
-            for (int task = tid + MAXT * NTH; task < ntasks; task += NTH) store_task(O0 - p.P, task, fetch_task(n, O0 - p.P, task));
+    // ---- steady state -----------------------------------------------------------------------------
+    int k = 0;
+    for (int t = t_begin; t < t_end; ++t, ++k) {
+        if (consumer) {
+            compute(win(k & 1), ost(k & 1));
         } else {
-            for (int task = tid; task < ntasks; task += NTH) store_task(O0 - p.P, task, fetch_task_slow(n, O0 - p.P, task));
+            if (t + 1 < t_end) {
+                commit(t + 1, win((k + 1) & 1));
+                if (t + 2 < t_end) prefetch(t + 2);
+            }
+            if (k > 0) flush(t - 1, (k - 1) & 1);
         }
         __syncthreads();
-        const int next = tile + gridDim.x;
-        // window loads are issued unconditionally: past the last tile they re-read the current one
-        const int nxt = next < ntiles ? next : tile;
-        const int nn = nxt / tiles_per_row;
-        const int G0n = (nxt - nn * tiles_per_row) * TQ - p.P;
-
-        f32x4 acc[T];
-        if (have_prev) {
-            compute(std::true_type{}, acc, pn, pO0, nn, G0n);
-        } else {
-            compute(std::false_type{}, acc, pn, pO0, nn, G0n);
-        }
-        if (vec_out) {
-            park(acc);
-            have_prev = true;
-            pn = n;
-            pO0 = O0;
-        } else {
-#pragma unroll
-            for (int j = 0; j < T; ++j) {
-                const int o = O0 + ob + j * 16 + li;
-                if (o < p.Wout) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int m = 4 * kb + i;
-                        if (m < p.M) p.out[(static_cast<long>(n) * p.M + m) * p.Wout + o] = acc[j][i];
-                    }
-                }
-            }
-        }
-        tile = next;
     }
-    if (have_prev) {
-#pragma unroll
-        for (int q = 0; q < 8; ++q) flush_write(pn, pO0, q, flush_read(q));
-    }
+    if (!consumer && k > 0) flush(t_end - 1, (k - 1) & 1);
 }
 
 constexpr int kCorrT = 8;
@@ -364,14 +342,12 @@ CorrPlan corr_plan(const CorrProblem& p) {
     // shift is 16 or 8 taps, little is shared and the unrolled schedule gets very long
     pl.G = (p.d == 4 || p.d == 8 || p.d == 16) ? 16 / p.d : 0;
     if (pl.NP == 17 && pl.G == 4) pl.G = 0;  // this instantiation does not fit the register budget
-    constexpr int TQ = kWaves * kCorrT * 16;
+    constexpr int TQ = 4 * kCorrT * 16;
     const long LP = TQ + static_cast<long>(2 * pl.NP - 1) * p.d;
     const long LPS = (LP + 2 + 7) / 8 * 8;
-    // [window | per-wave output staging]; the weight-slice assembly area aliases the window
-    long slots = 2 * LPS + kWaves * 16 * kOS / 4;
-    const long wslots = pl.NP * 64 + (static_cast<long>(p.M) * p.R * p.S * 2 + 15) / 16;
-    if (slots < wslots) slots = wslots;
-    if (slots * 16 > kLdsBudget / 2) return pl;  // two workgroups per CU
+    // [2 window buffers | 2 output staging buffers]; the weight-slice assembly area aliases the staging buffers
+    const long slots = 4 * LPS + 2 * kOstSlots;
+    if (slots * 16 > kLdsBudget) return pl;  // one workgroup per CU
     pl.LPS = static_cast<int>(LPS);
     pl.tiles_per_row = cdiv(p.Wout, TQ);
     const long nt = static_cast<long>(p.N) * pl.tiles_per_row;
@@ -392,8 +368,8 @@ hipError_t corr_launch_f(const CorrProblem& p, const CorrPlan& pl, hipStream_t s
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        static_cast<int>(pl.lds_bytes));
     if (e != hipSuccess) return e;
-    const int grid = pl.ntiles < 2 * kNumCU ? pl.ntiles : 2 * kNumCU;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kWaves * 64), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.vec_out);
+    const int grid = pl.ntiles < kNumCU ? pl.ntiles : kNumCU;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.vec_out);
     return hipGetLastError();
 }
 
