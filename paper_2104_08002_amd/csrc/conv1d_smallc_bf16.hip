@@ -67,6 +67,8 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
     const bool consumer = wave < 4;
     const int cw = wave & 3;   // consumer wave index / the consumer wave this producer wave serves
     const int rtid = tid & 255;  // thread index within the role group
+    // producers have little to do but sit on the critical path of the barrier: let them issue first
+    if (!consumer) __builtin_amdgcn_s_setprio(3);
     const int li = lane & 15;
     const int kb = lane >> 4;
     const unsigned short* __restrict__ in = static_cast<const unsigned short*>(p.in);
@@ -410,15 +412,24 @@ constexpr int kNT = 13;            // taps per wave == operands in the ring == k
 constexpr int kUnitSlots = 4 * kNT;  // 52 slots = 416 columns
 constexpr int kXP = 60;            // x slots staged per period (52 + look-ahead of the highest tap slot)
 constexpr int kXR = 61, kDR = 53;  // LDS row strides in slots (odd: rows spread over the bank groups)
-constexpr int kWgMaxS = 7;         // 16 * (60 + 52) slots / 256 threads
+constexpr int kWgMaxS = 7;         // 16 * (60 + 52) slots / 256 producer threads
 
+// Workgroup = 8 waves, one workgroup per CU: waves 0-3 ("consumers", one per tap class) do the operand
+// reads and MFMAs; waves 4-7 ("producers") fetch stage s+2 from global memory into registers and write
+// stage s+1 into the free half of the double-buffered LDS while the consumers work on stage s.  Stage s of
+// a strip is {x period j0+s+1, dy unit j0+s}; one workgroup barrier per unit hands the buffers over.
 template <bool FAST>
-__global__ __launch_bounds__(256, 2) void smallc_wgrad_bf16_d8_kernel(WgradProblem p, int SPR, int UPS, int units_per_row) {
-    __shared__ u32x4 xbuf[16 * kXR];
-    __shared__ u32x4 dybuf[16 * kDR];
+__global__ __launch_bounds__(512, 2) void smallc_wgrad_bf16_d8_kernel(WgradProblem p, int SPR, int UPS, int units_per_row) {
+    __shared__ u32x4 xbuf[2][16 * kXR];
+    __shared__ u32x4 dybuf[2][16 * kDR];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool consumer = wave < 4;
+    const int cw = wave & 3;  // tap class of a consumer wave
+    const int rtid = tid & 255;
+    // producers have little to do but sit on the critical path of the barrier: let them issue first
+    if (!consumer) __builtin_amdgcn_s_setprio(3);
     const int li = lane & 15;
     const int kb = lane >> 4;
     const unsigned short* __restrict__ x = static_cast<const unsigned short*>(p.x);
@@ -431,118 +442,162 @@ __global__ __launch_bounds__(256, 2) void smallc_wgrad_bf16_d8_kernel(WgradProbl
     const unsigned short* dyn = dy + static_cast<long>(n) * p.K * p.Q;
 
     constexpr int NX = 16 * kXP, NS = 16 * (kXP + kUnitSlots);
-    // Staging slot e of pipeline stage j: e < NX is x period j+1 (row e / kXP), the rest is dy unit j.
+    // Staging slot e of stage j: e < NX is x period j+1 (row e / kXP), the rest is dy unit j.  Everything
+    // about a slot except its column is fixed for a thread, so it is worked out once (producer waves share
+    // their SIMD's issue slots with an MFMA wave: every VALU instruction they do not execute matters).
     // FAST (all widths, the padding and the pointers are multiples of 8 elements): one 16-byte load
     // from a clamped address, masked when it is written to LDS; a slot is then inside or outside
-    // its row as a whole.  Otherwise element loads, done synchronously.
-    struct Where { const unsigned short* row; int g, limit, rows_ok; };
-    auto where = [&](int j, int e) -> Where {
-        Where w;
+    // its row as a whole.  Otherwise element loads, done when the stage is written.
+    struct Slot {
+        unsigned off;  // element offset of the (clamped) source row from the sample's x or dy base
+        int g0;        // column of the slot in stage 0 of this strip (advances by 416 per stage)
+        int lds;       // index into xbuf[b] / dybuf[b]; bit 30: x (else dy), bit 29: row beyond C or K
+    };
+    constexpr int kIsX = 1 << 30, kRowBad = 1 << 29, kLdsMask = kRowBad - 1;
+    auto make_slot = [&](int e) -> Slot {
+        Slot w;
         if (e < NX) {
             const int r = e / kXP, i = e - r * kXP;
-            w.row = xn + static_cast<unsigned>(min(r, p.C - 1) * p.W);
-            w.g = 8 * (kUnitSlots * (j + 1) + i) - p.P;
-            w.limit = p.W;
-            w.rows_ok = r < p.C;
+            w.off = static_cast<unsigned>(min(r, p.C - 1) * p.W);
+            w.g0 = 8 * (kUnitSlots * (j0 + 1) + i) - p.P;
+            w.lds = (r * kXR + i) | kIsX | (r < p.C ? 0 : kRowBad);
         } else {
             const int e2 = e - NX, r = e2 / kUnitSlots, i = e2 - r * kUnitSlots;
-            w.row = dyn + static_cast<unsigned>(min(r, p.K - 1) * p.Q);
-            w.g = 8 * (kUnitSlots * j + i);
-            w.limit = Qb;
-            w.rows_ok = r < p.K;
+            w.off = static_cast<unsigned>(min(r, p.K - 1) * p.Q);
+            w.g0 = 8 * (kUnitSlots * j0 + i);
+            w.lds = (r * kDR + i) | (r < p.K ? 0 : kRowBad);
         }
         return w;
     };
-    auto fetch = [&](int j, int e) -> u32x4 {
-        const Where w = where(j, e);
+    auto fetch = [&](const Slot& w, int stage) -> u32x4 {  // stage counts from 0 at unit j0
+        const int g = w.g0 + stage * (kUnitSlots * 8);
+        const bool is_x = w.lds & kIsX;
+        const int limit = is_x ? p.W : Qb;
+        const unsigned short* row = (is_x ? xn : dyn) + w.off;
         if constexpr (FAST) {
-            const int lim = w.limit - 8;  // >= 0 on this path (checked by the host)
-            const int gc = w.g < 0 ? 0 : (w.g > lim ? lim : w.g);
-            return *reinterpret_cast<const u32x4*>(w.row + gc);
+            const int lim = limit - 8;  // >= 0 on this path (checked by the host)
+            return *reinterpret_cast<const u32x4*>(row + (g < 0 ? 0 : (g > lim ? lim : g)));
         } else {
             unsigned t[8];
 #pragma unroll
             for (int jj = 0; jj < 8; ++jj) {
-                const int g = w.g + jj;
-                const int gc = g < 0 ? 0 : (g > w.limit - 1 ? w.limit - 1 : g);
-                t[jj] = (g >= 0 && g < w.limit) ? w.row[gc] : 0u;
+                const int gj = g + jj;
+                const int gc = gj < 0 ? 0 : (gj > limit - 1 ? limit - 1 : gj);
+                t[jj] = (gj >= 0 && gj < limit) ? row[gc] : 0u;
             }
             return u32x4{t[0] | (t[1] << 16), t[2] | (t[3] << 16), t[4] | (t[5] << 16), t[6] | (t[7] << 16)};
         }
     };
-    auto commit = [&](int j, int e, u32x4 v) {
-        const Where w = where(j, e);
-        const bool ok = w.rows_ok && (!FAST || (w.g >= 0 && w.g + 8 <= w.limit));
+    auto commit = [&](const Slot& w, int b, int stage, u32x4 v) {
+        const int g = w.g0 + stage * (kUnitSlots * 8);
+        const bool is_x = w.lds & kIsX;
+        const int limit = is_x ? p.W : Qb;
+        const bool ok = !(w.lds & kRowBad) && (!FAST || (g >= 0 && g + 8 <= limit));
         if (!ok) v = u32x4{0u, 0u, 0u, 0u};
-        if (e < NX) {
-            const int r = e / kXP;
-            xbuf[r * kXR + (e - r * kXP)] = v;
-        } else {
-            const int e2 = e - NX, r = e2 / kUnitSlots;
-            dybuf[r * kDR + (e2 - r * kUnitSlots)] = v;
+        (is_x ? xbuf[b] : dybuf[b])[w.lds & kLdsMask] = v;
+    };
+    Slot slot[kWgMaxS];
+#pragma unroll
+    for (int k = 0; k < kWgMaxS; ++k) slot[k] = make_slot(min(rtid + k * 256, NS - 1));
+    // producers keep two stages in flight (registers preA / preB, used alternately)
+    u32x4 preA[FAST ? kWgMaxS : 1], preB[FAST ? kWgMaxS : 1];
+    auto prefetch_stage = [&](u32x4 (&pre)[FAST ? kWgMaxS : 1], int j) {
+        if constexpr (FAST) {
+#pragma unroll
+            for (int k = 0; k < kWgMaxS; ++k) pre[k] = fetch(slot[k], j - j0);
+        }
+    };
+    auto commit_stage = [&](const u32x4 (&pre)[FAST ? kWgMaxS : 1], int b, int j) {
+#pragma unroll
+        for (int k = 0; k < kWgMaxS; ++k) {
+            if (rtid + k * 256 < NS) {
+                if constexpr (FAST) {
+                    commit(slot[k], b, j - j0, pre[k]);
+                } else {
+                    commit(slot[k], b, j - j0, fetch(slot[k], j - j0));
+                }
+            }
         }
     };
 
-    f32x4 acc[kNT];
+    // prologue: every thread helps to put x period j0 into buffer 1 (stage index j0 - 1 addresses it);
+    // the producers also start on stage j0
+    // (all global loads of the prologue are issued before the first one is used)
+    {
+        constexpr int NP0 = (NX + 511) / 512;
+        Slot w0[NP0];
+        u32x4 v0[NP0];
 #pragma unroll
-    for (int i = 0; i < kNT; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    // prologue: x period j0 -> LDS -> operand ring  (stage index j0 - 1 addresses x period j0)
-    for (int e = tid; e < NX; e += 256) commit(j0 - 1, e, fetch(j0 - 1, e));
-    u32x4 pre[FAST ? kWgMaxS : 1];
-    if constexpr (FAST) {
-#pragma unroll
-        for (int k = 0; k < kWgMaxS; ++k) pre[k] = fetch(j0, tid + k * 256 < NS ? tid + k * 256 : NS - 1);
-    }
-    __syncthreads();
-    const u32x4* xp = xbuf + li * kXR + wave + kb;
-    const u32x4* ap = dybuf + li * kDR + kb;
-    bf16x8 ring[kNT];
-#pragma unroll
-    for (int i = 0; i < kNT; ++i) ring[i] = as_bf16x8(xp[4 * i]);
-
-    for (int j = j0; j < j1; ++j) {
-        __syncthreads();  // ring preload / previous unit's LDS reads are done
-        if constexpr (FAST) {
-#pragma unroll
-            for (int k = 0; k < kWgMaxS; ++k) {
-                const int e = tid + k * 256;
-                if (e < NS) commit(j, e, pre[k]);
-            }
-        } else {
-            for (int e = tid; e < NS; e += 256) commit(j, e, fetch(j, e));
+        for (int k = 0; k < NP0; ++k) {
+            w0[k] = make_slot(min(tid + k * 512, NX - 1));
+            v0[k] = fetch(w0[k], -1);
         }
-        __syncthreads();
-        if constexpr (FAST) {
-            if (j + 1 < j1) {
-#pragma unroll
-                for (int k = 0; k < kWgMaxS; ++k) pre[k] = fetch(j + 1, tid + k * 256 < NS ? tid + k * 256 : NS - 1);
-            }
+        if (!consumer) {
+            prefetch_stage(preA, j0);
+            if (j0 + 1 < j1) prefetch_stage(preB, j0 + 1);
         }
         __builtin_amdgcn_sched_barrier(0);
-        bf16x8 a = as_bf16x8(ap[0]);
 #pragma unroll
-        for (int u = 0; u < kNT; ++u) {
-            // ring slot u is dead once tap slot 0 has consumed it: refill it (and fetch the next dy
-            // operand) right away so the other taps' MFMAs cover the LDS latency
-            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ring[u], acc[0], 0, 0, 0);
-            const bf16x8 a_nxt = as_bf16x8(ap[4 * (u + 1 < kNT ? u + 1 : u)]);
-            ring[u] = as_bf16x8(xp[4 * u]);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 1; i < kNT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ring[(u + i) % kNT], acc[i], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            a = a_nxt;
-        }
+        for (int k = 0; k < NP0; ++k)
+            if (tid + k * 512 < NX) commit(w0[k], 1, -1, v0[k]);
     }
-    const int nt = (p.S - wave + 3) / 4;  // real taps of this wave; the remaining slots hold unused sums
-    float* ws = static_cast<float*>(p.ws) + static_cast<long>(blockIdx.x) * p.S * 256;
+    __syncthreads();
+    bf16x8 ring[kNT];
+    f32x4 acc[kNT];
+    if (consumer) {
+        const u32x4* xp = xbuf[1] + li * kXR + cw + kb;
 #pragma unroll
-    for (int i = 0; i < kNT; ++i) {
-        if (i < nt) {
-            const int s = wave + 4 * i;
+        for (int i = 0; i < kNT; ++i) {
+            ring[i] = as_bf16x8(xp[4 * i]);
+            acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    } else {
+        commit_stage(preA, 0, j0);
+        if (j0 + 2 < j1) prefetch_stage(preA, j0 + 2);
+    }
+    __syncthreads();
+
+    for (int j = j0; j < j1; ++j) {
+        const int b = (j - j0) & 1;
+        if (consumer) {
+            const u32x4* xp = xbuf[b] + li * kXR + cw + kb;
+            const u32x4* ap = dybuf[b] + li * kDR + kb;
+            bf16x8 a = as_bf16x8(ap[0]);
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) ws[s * 256 + (4 * kb + jj) * 16 + li] = acc[i][jj];
+            for (int u = 0; u < kNT; ++u) {
+                // ring slot u is dead once tap slot 0 has consumed it: refill it (and fetch the next dy
+                // operand) right away so the other taps' MFMAs cover the LDS latency
+                acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ring[u], acc[0], 0, 0, 0);
+                const bf16x8 a_nxt = as_bf16x8(ap[4 * (u + 1 < kNT ? u + 1 : u)]);
+                ring[u] = as_bf16x8(xp[4 * u]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 1; i < kNT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ring[(u + i) % kNT], acc[i], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                a = a_nxt;
+            }
+        } else if (j + 1 < j1) {
+            // stage j+1 sits in preB when b == 0 and in preA when b == 1; its registers then take stage j+3
+            if (b == 0) {
+                commit_stage(preB, 1, j + 1);
+                if (j + 3 < j1) prefetch_stage(preB, j + 3);
+            } else {
+                commit_stage(preA, 0, j + 1);
+                if (j + 3 < j1) prefetch_stage(preA, j + 3);
+            }
+        }
+        __syncthreads();
+    }
+    if (consumer) {
+        const int nt = (p.S - cw + 3) / 4;  // real taps of this wave; the remaining slots hold unused sums
+        float* ws = static_cast<float*>(p.ws) + static_cast<long>(blockIdx.x) * p.S * 256;
+#pragma unroll
+        for (int i = 0; i < kNT; ++i) {
+            if (i < nt) {
+                const int s = cw + 4 * i;
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) ws[s * 256 + (4 * kb + jj) * 16 + li] = acc[i][jj];
+            }
         }
     }
 }
@@ -558,9 +613,9 @@ WgradPlan wgrad_plan(const WgradProblem& p) {
     if (!p.bf16 || p.C > 16 || p.K > 16 || p.d != 8 || p.S > 4 * kNT) return pl;
     if (static_cast<long>(p.C) * p.W >= (1L << 30) || static_cast<long>(p.K) * p.Q >= (1L << 30)) return pl;
     pl.units_per_row = cdiv(p.Q, kUnitSlots * 8);
-    // strips of UPS units so that about two workgroups per CU exist
+    // strips of UPS units so that about one workgroup per CU exists
     const long total_units = static_cast<long>(p.N) * pl.units_per_row;
-    pl.UPS = static_cast<int>((total_units + 2 * kNumCU - 1) / (2 * kNumCU));
+    pl.UPS = static_cast<int>((total_units + kNumCU - 1) / kNumCU);
     if (pl.UPS < 1) pl.UPS = 1;
     pl.SPR = cdiv(pl.units_per_row, pl.UPS);
     const long grid = static_cast<long>(p.N) * pl.SPR;
@@ -603,9 +658,9 @@ hipError_t smallc_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     const WgradPlan pl = wgrad_plan(p);
     if (!pl.ok) return hipErrorInvalidValue;
     if (pl.fast) {
-        hipLaunchKernelGGL(smallc_wgrad_bf16_d8_kernel<true>, dim3(pl.grid), dim3(256), 0, st, p, pl.SPR, pl.UPS, pl.units_per_row);
+        hipLaunchKernelGGL(smallc_wgrad_bf16_d8_kernel<true>, dim3(pl.grid), dim3(512), 0, st, p, pl.SPR, pl.UPS, pl.units_per_row);
     } else {
-        hipLaunchKernelGGL(smallc_wgrad_bf16_d8_kernel<false>, dim3(pl.grid), dim3(256), 0, st, p, pl.SPR, pl.UPS, pl.units_per_row);
+        hipLaunchKernelGGL(smallc_wgrad_bf16_d8_kernel<false>, dim3(pl.grid), dim3(512), 0, st, p, pl.SPR, pl.UPS, pl.units_per_row);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
