@@ -253,146 +253,194 @@ hipError_t corr_f32_launch_rc(const CorrProblem& p, const CorrF32Plan& pl, hipSt
 // ------------------------------------------------------------------------------------------------
 // FP32 backward-weight
 // ------------------------------------------------------------------------------------------------
-// Workgroup of 4 waves; wave v owns taps s = v, v+4, v+8, ... (NT slots) and keeps one 16 x 16
-// accumulator tile per tap.  The workgroup walks chunks of QC output columns of one sample:
-//   dyt[16][LQS]  rows = filters, column j <-> q = Qs + j
-//   xt [16][LXS]  rows = channels, column i <-> input position Qs - P + i
-// One MFMA k-step covers 4 positions: A = dy[m][q0 + kb], B = x[c][q0 + kb + s*d - P].
-// The next chunk is fetched into registers (16-byte slots) while the current one is consumed.
-// Partial sums: ws[(wg * S + s) * 256 + m * 16 + c].
+// Workgroup = 8 waves, one per CU, persistent over a contiguous strip of chunks (QC output columns of one
+// sample each).  Waves 0-3 ("consumers"): wave v owns taps s = v, v+4, v+8, ... (NT slots) and keeps one
+// 16 x 16 accumulator tile per tap; one MFMA k-step covers 4 positions, A = dy[m][q0 + kb],
+// B = x[c][q0 + kb + s*d - P], both read from LDS with ds_read_b32 (any dilation), the reads of k-step t+1
+// interleaved with the MFMAs of k-step t.  Waves 4-7 ("producers") fetch chunk i+2 from global memory into
+// registers and write chunk i+1 into the free half of the double-buffered LDS:
+//   dyt[b][16][LQS]  rows = filters, column j <-> q = Qs + j
+//   xt [b][16][LXS]  rows = channels, column i <-> input position Qs - P + i
+// One workgroup barrier per chunk hands the buffers over.  Partial sums: ws[(wg * S + s) * 256 + m * 16 + c].
 template <int NT, int MAXS, bool FAST>
-__global__ __launch_bounds__(256) void smallc_wgrad_f32_kernel(WgradProblem p, int chunks_per_row, int nchunks, int QC, int LQS, int LXS,
-                                                               int LX4) {
+__global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p, int chunks_per_row, int nchunks, int QC, int LQS, int LXS,
+                                                                  int LX4) {
     extern __shared__ float lds[];
-    float* dyt = lds;
-    float* xt = lds + 16 * LQS;
+    const int stage_floats = 16 * (LQS + LXS);
+    auto dyt = [&](int b) { return lds + b * stage_floats; };
+    auto xt = [&](int b) { return lds + b * stage_floats + 16 * LQS; };
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool consumer = wave < 4;
+    const int cw = wave & 3;
+    const int rtid = tid & 255;
     const int li = lane & 15;
     const int kb = lane >> 4;
     const float* __restrict__ x = static_cast<const float*>(p.x);
     const float* __restrict__ dy = static_cast<const float*>(p.dy);
-    const int nt = (p.S - wave + 3) / 4;  // real taps of this wave; slots beyond compute unused sums
     const int Q4 = QC / 4;
     const int ndy = 16 * Q4;
     const int nslots = ndy + 16 * LX4;
 
+    // contiguous strip of chunks; neighbouring strips (shared halos) land on the same XCD
+    int lid = blockIdx.x;
+    if ((gridDim.x & 7) == 0) lid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int c_begin = static_cast<int>(static_cast<long>(lid) * nchunks / gridDim.x);
+    const int c_end = static_cast<int>(static_cast<long>(lid + 1) * nchunks / gridDim.x);
+
     // Staging slot e: first the dy rows (Q4 slots each), then the x rows (LX4 slots each); 4 adjacent
-    // positions per slot.  FAST: one clamped 16-byte load, masked at the LDS write (widths, padding
-    // and pointers are multiples of 4 floats, so a slot never straddles a row end).
-    struct Where { const float* row; int g, limit, rows_ok; float* dst; };
-    auto where = [&](int n, int Qs, int e) -> Where {
-        Where w;
-        const bool is_x = e >= ndy;
+    // positions per slot.  Slot k of a producer thread is e = rtid + 256*k; QC is a multiple of 64, so the
+    // dy/x boundary (16*Q4) is a multiple of 256 and "is this an x slot" is uniform per k.  Everything about
+    // a slot except the chunk origin is worked out once.  FAST: one clamped 16-byte load, masked at the LDS
+    // write (widths, padding and pointers are multiples of 4 floats, so a slot never straddles a row end).
+    constexpr int kRowBad = 1 << 29;
+    struct Slot { unsigned off; int col, lds; };  // row offset in the sample, first column, LDS index (| kRowBad)
+    auto slot_is_x = [&](int k) { return k * 256 >= ndy; };
+    auto make_slot = [&](int k, int e) -> Slot {
+        const bool is_x = slot_is_x(k);
         const int e2 = is_x ? e - ndy : e;
         const int per_row = is_x ? LX4 : Q4;
         const int r = e2 / per_row, i = e2 - r * per_row;
         const int rows = is_x ? p.C : p.K;
-        w.limit = is_x ? p.W : p.Q;
-        w.row = (is_x ? x : dy) + static_cast<long>(n) * rows * w.limit + static_cast<unsigned>(min(r, rows - 1) * w.limit);
-        w.g = (is_x ? Qs - p.P : Qs) + 4 * i;
-        w.rows_ok = r < rows;
-        w.dst = (is_x ? xt + r * LXS : dyt + r * LQS) + 4 * i;
+        Slot w;
+        w.off = static_cast<unsigned>(min(r, rows - 1) * (is_x ? p.W : p.Q));
+        w.col = 4 * i;
+        w.lds = (r * (is_x ? LXS : LQS) + 4 * i) | (r < rows ? 0 : kRowBad);
         return w;
     };
-    auto fetch = [&](int n, int Qs, int e) -> f32x4 {
-        const Where w = where(n, Qs, e);
+    struct Origin { const float* xb; const float* dyb; int Qs; };
+    auto origin = [&](int chunk) -> Origin {
+        const int n = chunk / chunks_per_row;
+        return Origin{x + static_cast<long>(n) * p.C * p.W, dy + static_cast<long>(n) * p.K * p.Q, (chunk - n * chunks_per_row) * QC};
+    };
+    auto fetch = [&](const Origin& o, int k, const Slot& w) -> f32x4 {
+        const bool is_x = slot_is_x(k);
+        const float* row = (is_x ? o.xb : o.dyb) + w.off;
+        const int limit = is_x ? p.W : p.Q;
+        const int g = (is_x ? o.Qs - p.P : o.Qs) + w.col;
         if constexpr (FAST) {
-            const int lim = w.limit - 4;
-            return *reinterpret_cast<const f32x4*>(w.row + (w.g < 0 ? 0 : (w.g > lim ? lim : w.g)));
+            const int lim = limit - 4;
+            return *reinterpret_cast<const f32x4*>(row + (g < 0 ? 0 : (g > lim ? lim : g)));
         } else {
             f32x4 v;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int gj = w.g + j;
-                const float t = w.row[gj < 0 ? 0 : (gj > w.limit - 1 ? w.limit - 1 : gj)];
-                v[j] = (gj >= 0 && gj < w.limit) ? t : 0.f;
+                const int gj = g + j;
+                const float t = row[gj < 0 ? 0 : (gj > limit - 1 ? limit - 1 : gj)];
+                v[j] = (gj >= 0 && gj < limit) ? t : 0.f;
             }
             return v;
         }
     };
-    auto commit = [&](int n, int Qs, int e, f32x4 v) {
-        const Where w = where(n, Qs, e);
-        const bool ok = w.rows_ok && (!FAST || (w.g >= 0 && w.g + 4 <= w.limit));
+    auto commit = [&](int b, const Origin& o, int k, const Slot& w, f32x4 v) {
+        const bool is_x = slot_is_x(k);
+        const int limit = is_x ? p.W : p.Q;
+        const int g = (is_x ? o.Qs - p.P : o.Qs) + w.col;
+        const bool ok = !(w.lds & kRowBad) && (!FAST || (g >= 0 && g + 4 <= limit));
         if (!ok) v = f32x4{0.f, 0.f, 0.f, 0.f};
-        *reinterpret_cast<f32x4*>(w.dst) = v;
+        *reinterpret_cast<f32x4*>((is_x ? xt(b) : dyt(b)) + (w.lds & (kRowBad - 1))) = v;
+    };
+    Slot slot[MAXS];
+    f32x4 pre[FAST ? MAXS : 1];
+    if (!consumer) {
+#pragma unroll
+        for (int k = 0; k < MAXS; ++k) slot[k] = make_slot(k, min(rtid + k * 256, nslots - 1));
+    }
+    auto prefetch_chunk = [&](int chunk) {
+        if constexpr (FAST) {
+            const Origin o = origin(chunk);
+#pragma unroll
+            for (int k = 0; k < MAXS; ++k) pre[k] = fetch(o, k, slot[k]);
+        }
+    };
+    auto commit_chunk = [&](int b, int chunk) {
+        const Origin o = origin(chunk);
+#pragma unroll
+        for (int k = 0; k < MAXS; ++k) {
+            if (rtid + k * 256 < nslots) {
+                if constexpr (FAST) {
+                    commit(b, o, k, slot[k], pre[k]);
+                } else {
+                    commit(b, o, k, slot[k], fetch(o, k, slot[k]));
+                }
+            }
+        }
+        // slots beyond the per-thread register budget (long halos) are staged directly
+        for (int k = MAXS; rtid + k * 256 < nslots; ++k) {
+            const Slot w = make_slot(k, rtid + k * 256);
+            commit(b, o, k, w, fetch(o, k, w));
+        }
     };
 
     f32x4 acc[NT];
 #pragma unroll
     for (int i = 0; i < NT; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    f32x4 pre[FAST ? MAXS : 1];
-    int chunk = blockIdx.x;
-    if constexpr (FAST) {
-        const int n = chunk / chunks_per_row;
-        const int Qs = (chunk - n * chunks_per_row) * QC;
-#pragma unroll
-        for (int k = 0; k < MAXS; ++k) {
-            const int e = tid + k * 256;
-            pre[k] = fetch(n, Qs, e < nslots ? e : nslots - 1);
-        }
+    // prologue: producers stage the first chunk and start on the second
+    if (!consumer && c_begin < c_end) {
+        prefetch_chunk(c_begin);
+        commit_chunk(0, c_begin);
+        if (c_begin + 1 < c_end) prefetch_chunk(c_begin + 1);
     }
-    while (chunk < nchunks) {
-        const int n = chunk / chunks_per_row;
-        const int Qs = (chunk - n * chunks_per_row) * QC;
-        __syncthreads();
-        if constexpr (FAST) {
-#pragma unroll
-            for (int k = 0; k < MAXS; ++k) {
-                const int e = tid + k * 256;
-                if (e < nslots) commit(n, Qs, e, pre[k]);
-            }
-            for (int e = tid + MAXS * 256; e < nslots; e += 256) commit(n, Qs, e, fetch(n, Qs, e));
-        } else {
-            for (int e = tid; e < nslots; e += 256) commit(n, Qs, e, fetch(n, Qs, e));
-        }
-        __syncthreads();
-        const int next = chunk + gridDim.x;
-        if constexpr (FAST) {
-            if (next < nchunks) {
-                const int nn = next / chunks_per_row;
-                const int Qn = (next - nn * chunks_per_row) * QC;
-#pragma unroll
-                for (int k = 0; k < MAXS; ++k) {
-                    const int e = tid + k * 256;
-                    pre[k] = fetch(nn, Qn, e < nslots ? e : nslots - 1);
-                }
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
 
-        const float* ap = dyt + li * LQS + kb;
-        const float* bp = xt + li * LXS + kb + wave * p.d;
-        const int dstep = 4 * p.d;
-        // operands of k-step t+4 are fetched from LDS while the MFMAs of k-step t run
-        float a_cur = ap[0], b_cur[NT];
+    int k = 0;
+    for (int chunk = c_begin; chunk < c_end; ++chunk, ++k) {
+        const int b = k & 1;
+        if (consumer) {
+            const float* ap = dyt(b) + li * LQS + kb;
+            const float* bp = xt(b) + li * LXS + kb + cw * p.d;
+            const int dstep = 4 * p.d;
+            // two k-steps per iteration with ping-pong operand registers: the LDS reads of the next k-step
+            // are issued between the MFMAs of the current one
+            float a0 = ap[0], b0[NT], a1, b1[NT];
 #pragma unroll
-        for (int i = 0; i < NT; ++i) b_cur[i] = bp[i * dstep];
-        for (int t = 0; t < QC; t += 4) {
-            const int tn = t + 4 < QC ? t + 4 : t;
-            const float a_nxt = ap[tn];
-            float b_nxt[NT];
+            for (int i = 0; i < NT; ++i) b0[i] = bp[i * dstep];
+            for (int t = 0; t < QC; t += 8) {
+                const int t1 = t + 4;
+                const int t2 = t + 8 < QC ? t + 8 : t + 4;
+                a1 = ap[t1];
 #pragma unroll
-            for (int i = 0; i < NT; ++i) b_nxt[i] = bp[tn + i * dstep];
-            __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of the MFMA block
+                for (int i = 0; i < NT; ++i) {
+                    b1[i] = bp[t1 + i * dstep];
+                    acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0[i], acc[i], 0, 0, 0);
+                }
 #pragma unroll
-            for (int i = 0; i < NT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur, b_cur[i], acc[i], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            a_cur = a_nxt;
+                for (int i = 0; i < NT; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read ...
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // ... then one MFMA
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                a0 = ap[t2];
 #pragma unroll
-            for (int i = 0; i < NT; ++i) b_cur[i] = b_nxt[i];
+                for (int i = 0; i < NT; ++i) {
+                    b0[i] = bp[t2 + i * dstep];
+                    acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1[i], acc[i], 0, 0, 0);
+                }
+#pragma unroll
+                for (int i = 0; i < NT; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else if (chunk + 1 < c_end) {
+            commit_chunk(b ^ 1, chunk + 1);
+            if (chunk + 2 < c_end) prefetch_chunk(chunk + 2);
         }
-        chunk = next;
+        __syncthreads();
     }
-    float* ws = static_cast<float*>(p.ws) + static_cast<long>(blockIdx.x) * p.S * 256;
+    if (consumer) {
+        const int nt = (p.S - cw + 3) / 4;  // real taps of this wave; slots beyond hold unused sums
+        float* ws = static_cast<float*>(p.ws) + static_cast<long>(blockIdx.x) * p.S * 256;
 #pragma unroll
-    for (int i = 0; i < NT; ++i) {
-        if (i < nt) {
-            const int s = wave + 4 * i;
+        for (int i = 0; i < NT; ++i) {
+            if (i < nt) {
+                const int s = cw + 4 * i;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) ws[s * 256 + (4 * kb + j) * 16 + li] = acc[i][j];
+                for (int j = 0; j < 4; ++j) ws[s * 256 + (4 * kb + j) * 16 + li] = acc[i][j];
+            }
         }
     }
 }
@@ -430,7 +478,7 @@ struct WgradF32Plan {
     bool ok;
 };
 
-constexpr int kWgradNT = 13, kWgradMaxS = 16;
+constexpr int kWgradNT = 13, kWgradMaxS = 15;
 
 WgradF32Plan wgrad_f32_plan(const WgradProblem& p) {
     WgradF32Plan pl{};
@@ -438,28 +486,28 @@ WgradF32Plan wgrad_f32_plan(const WgradProblem& p) {
     if (p.bf16 || p.C > 16 || p.K > 16 || p.S > 4 * kWgradNT) return pl;
     if (static_cast<long>(p.C) * p.W >= (1L << 30) || static_cast<long>(p.K) * p.Q >= (1L << 30)) return pl;
     const long halo = static_cast<long>(4 * kWgradNT - 1) * p.d;  // every tap slot a wave may read
-    const int QC = 256;
-    // row strides == 2 (mod 32) words (and a multiple of 4 words would break that): 16-byte slot
-    // stores need 4-word alignment, so the stride is 4 (mod 32) words instead: 8 rows x 4 columns
-    // of an operand fragment then cover 32 distinct banks
+    // 16-byte slot stores need 4-word aligned rows; a stride of 4 (mod 32) words lets 8 rows x 4 columns
+    // of an operand fragment cover 32 distinct banks
     auto pad = [](long v) { return (v + 31) / 32 * 32 + 4; };
-    const long LQS = pad(QC), LXS = pad(QC + halo);
-    const long bytes = 16 * (LQS + LXS) * 4;
-    if (bytes > kLdsBudget) return pl;
-    pl.QC = QC;
-    pl.LQS = static_cast<int>(LQS);
-    pl.LXS = static_cast<int>(LXS);
-    pl.LX4 = static_cast<int>((QC + halo + 3) / 4);
-    pl.chunks_per_row = cdiv(p.Q, QC);
-    const long nc = static_cast<long>(p.N) * pl.chunks_per_row;
-    if (nc > 0x7fffffffL) return pl;
-    pl.nchunks = static_cast<int>(nc);
-    const int per_cu = bytes <= kLdsBudget / 2 ? 2 : 1;
-    pl.grid = pl.nchunks < per_cu * kNumCU ? pl.nchunks : per_cu * kNumCU;
-    pl.lds_bytes = static_cast<size_t>(bytes);
-    pl.fast = (p.W % 4 == 0) && (p.Q % 4 == 0) && (p.P % 4 == 0) && p.W >= 4 && p.Q >= 4 &&
-              (reinterpret_cast<uintptr_t>(p.x) % 16 == 0) && (reinterpret_cast<uintptr_t>(p.dy) % 16 == 0);
-    pl.ok = true;
+    for (int QC = 256; QC >= 64; QC /= 2) {  // the largest chunk whose two stages fit in LDS
+        const long LQS = pad(QC), LXS = pad(QC + halo);
+        const long bytes = 2 * 16 * (LQS + LXS) * 4;
+        if (bytes > kLdsBudget) continue;
+        pl.QC = QC;
+        pl.LQS = static_cast<int>(LQS);
+        pl.LXS = static_cast<int>(LXS);
+        pl.LX4 = static_cast<int>((QC + halo + 3) / 4);
+        pl.chunks_per_row = cdiv(p.Q, QC);
+        const long nc = static_cast<long>(p.N) * pl.chunks_per_row;
+        if (nc > 0x7fffffffL) return pl;
+        pl.nchunks = static_cast<int>(nc);
+        pl.grid = pl.nchunks < kNumCU ? pl.nchunks : kNumCU;
+        pl.lds_bytes = static_cast<size_t>(bytes);
+        pl.fast = (p.W % 4 == 0) && (p.Q % 4 == 0) && (p.P % 4 == 0) && p.W >= 4 && p.Q >= 4 &&
+                  (reinterpret_cast<uintptr_t>(p.x) % 16 == 0) && (reinterpret_cast<uintptr_t>(p.dy) % 16 == 0);
+        pl.ok = true;
+        return pl;
+    }
     return pl;
 }
 
@@ -507,7 +555,7 @@ hipError_t smallc_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        static_cast<int>(pl.lds_bytes));
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(pl.grid), dim3(256), pl.lds_bytes, st, p, pl.chunks_per_row, pl.nchunks, pl.QC, pl.LQS, pl.LXS,
+    hipLaunchKernelGGL(kern, dim3(pl.grid), dim3(512), pl.lds_bytes, st, p, pl.chunks_per_row, pl.nchunks, pl.QC, pl.LQS, pl.LXS,
                        pl.LX4);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
