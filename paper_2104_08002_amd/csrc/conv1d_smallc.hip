@@ -18,6 +18,7 @@ namespace conv1d {
 namespace {
 
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 constexpr int kLdsBudget = 160 * 1024;
 constexpr int kNumCU = 256;
@@ -25,39 +26,59 @@ constexpr int kNumCU = 256;
 // ------------------------------------------------------------------------------------------------
 // FP32 forward / backward-data
 // ------------------------------------------------------------------------------------------------
-// Workgroup: WAVES waves; wave v owns T adjacent 16-column output tiles.  LDS holds
-//   wfrag[S*RC][64]   weights in MFMA A-operand order: entry (step = s*RC + cc, lane = m + 16*kb)
-//                     is wt(m, 4*cc + kb, s)  (zero outside M x R)
-//   win[4*RC][LPS]    the input window, row r, column i <-> input position G0 + i
-// A workgroup walks tiles blockIdx.x, +gridDim.x, ...; the window of the next tile is fetched
-// from global memory into registers (16-byte slots, MAXS per thread) while the MFMAs of the
-// current tile run, and written to LDS after the barrier that ends the current tile.
-template <int RC, int T, int WAVES, int MAXS, bool FAST>
-__global__ __launch_bounds__(WAVES * 64) void smallc_corr_f32_kernel(CorrProblem p, int tiles_per_row, int ntiles, int LPS, int LP4,
-                                                                     int raw_in_lds) {
+// Workgroup = 8 waves, one per CU, persistent over a contiguous strip of tiles (4*T*16 output columns of one
+// sample each).  LDS holds
+//   wfrag[S*RC][64]      weights in MFMA A-operand order: entry (step = s*RC + cc, lane = m + 16*kb) is
+//                        wt(m, 4*cc + kb, s)  (zero outside M x R)
+//   win[b][4*RC][LPS]    input window b, row r, column i <-> input position G0 + i   (NBUF = 1 or 2 buffers)
+// Waves 0-3 ("consumers") own T adjacent 16-column output tiles each and walk the (tap, channel-chunk)
+// reduction with v_mfma_f32_16x16x4_f32, the LDS reads of tap s+1 interleaved with the MFMAs of tap s;
+// they store their outputs themselves.  Waves 4-7 ("producers") fetch the window of tile t+2 from global
+// memory into registers and write the window of tile t+1 into the free buffer; one workgroup barrier per
+// tile hands the buffers over.  When two windows do not fit in LDS (long halos) the same kernel runs with one
+// buffer and a second barrier per tile.
+template <int RC, int T, int MAXS, bool FAST>
+__global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, int tiles_per_row, int ntiles, int LPS, int LP4,
+                                                                 int nbuf, int raw_in_lds) {
     extern __shared__ float lds[];
-    constexpr int TQ = WAVES * T * 16;
-    constexpr int NTH = WAVES * 64;
+    constexpr int TQ = 4 * T * 16;
     const int nsteps = p.S * RC;
     float* wfrag = lds;
-    float* win = lds + nsteps * 64;
+    auto win = [&](int b) { return lds + nsteps * 64 + b * 4 * RC * LPS; };
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool consumer = wave < 4;
+    const int cw = wave & 3;
+    const int rtid = tid & 255;
     const int li = lane & 15;  // row of A / column of B and D
     const int kb = lane >> 4;  // k index of A/B; row block of D
     const float* __restrict__ in = static_cast<const float*>(p.in);
     const float* __restrict__ wt = static_cast<const float*>(p.wt);
     const int nslots = 4 * RC * LP4;
 
-    // Staging slot e = 4 adjacent positions of row e / LP4.  FAST (row starts, window origin and
-    // base pointer are multiples of 4 floats, so a slot is inside or outside its row as a whole):
-    // one 16-byte load from a clamped address, masked when it is written to LDS.  Otherwise
-    // element loads, done synchronously after the barrier.
-    auto fetch = [&](int n, int G0, int e) -> f32x4 {
-        const int r = e / LP4;
-        const int g = G0 + 4 * (e - r * LP4);
-        const float* row = in + static_cast<long>(n) * p.R * p.Win + static_cast<unsigned>(min(r, p.R - 1) * p.Win);
+    int lid = blockIdx.x;
+    if ((gridDim.x & 7) == 0) lid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int t_begin = static_cast<int>(static_cast<long>(lid) * ntiles / gridDim.x);
+    const int t_end = static_cast<int>(static_cast<long>(lid + 1) * ntiles / gridDim.x);
+    auto tile_n = [&](int t) { return t / tiles_per_row; };
+    auto tile_O0 = [&](int t) { return (t - (t / tiles_per_row) * tiles_per_row) * TQ; };
+
+    // ---- producer side ------------------------------------------------------------------------------
+    // Staging slot e = 4 adjacent positions of row e / LP4; slot k of a producer thread is e = rtid + 256*k
+    // and everything about it except the window origin is worked out once.  FAST (row starts, window origin
+    // and base pointer are multiples of 4 floats, so a slot is inside or outside its row as a whole): one
+    // 16-byte load from a clamped address, masked when it is written to LDS.  Otherwise element loads, done
+    // when the window is written.
+    constexpr int kRowBad = 1 << 29;
+    struct Slot { unsigned off; int col, lds; };
+    auto make_slot = [&](int e) -> Slot {
+        const int r = e / LP4, i = e - r * LP4;
+        return Slot{static_cast<unsigned>(min(r, p.R - 1) * p.Win), 4 * i, (r * LPS + 4 * i) | (r < p.R ? 0 : kRowBad)};
+    };
+    auto fetch = [&](int t, const Slot& w) -> f32x4 {
+        const float* row = in + static_cast<long>(tile_n(t)) * p.R * p.Win + w.off;
+        const int g = tile_O0(t) - p.P + w.col;
         if constexpr (FAST) {
             const int lim = p.Win - 4;  // >= 0 on this path (checked by the host)
             return *reinterpret_cast<const f32x4*>(row + (g < 0 ? 0 : (g > lim ? lim : g)));
@@ -66,123 +87,159 @@ __global__ __launch_bounds__(WAVES * 64) void smallc_corr_f32_kernel(CorrProblem
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int gj = g + j;
-                const float t = row[gj < 0 ? 0 : (gj > p.Win - 1 ? p.Win - 1 : gj)];
-                v[j] = (gj >= 0 && gj < p.Win) ? t : 0.f;
+                const float tt = row[gj < 0 ? 0 : (gj > p.Win - 1 ? p.Win - 1 : gj)];
+                v[j] = (gj >= 0 && gj < p.Win) ? tt : 0.f;
             }
             return v;
         }
     };
-    auto commit = [&](int G0, int e, f32x4 v) {
-        const int r = e / LP4;
-        const int i = e - r * LP4;
-        const int g = G0 + 4 * i;
-        const bool ok = r < p.R && (!FAST || (g >= 0 && g + 4 <= p.Win));
+    auto commit = [&](float* wb, int t, const Slot& w, f32x4 v) {
+        const int g = tile_O0(t) - p.P + w.col;
+        const bool ok = !(w.lds & kRowBad) && (!FAST || (g >= 0 && g + 4 <= p.Win));
         if (!ok) v = f32x4{0.f, 0.f, 0.f, 0.f};
-        *reinterpret_cast<f32x4*>(win + r * LPS + 4 * i) = v;
+        *reinterpret_cast<f32x4*>(wb + (w.lds & (kRowBad - 1))) = v;
     };
-
+    Slot slot[MAXS];
     f32x4 pre[FAST ? MAXS : 1];
-    int tile = blockIdx.x;
-    if constexpr (FAST) {
-        const int n = tile / tiles_per_row;
-        const int G0 = (tile - n * tiles_per_row) * TQ - p.P;
+    auto prefetch_tile = [&](int t) {
+        if constexpr (FAST) {
+#pragma unroll
+            for (int k = 0; k < MAXS; ++k) pre[k] = fetch(t, slot[k]);
+        }
+    };
+    auto commit_tile = [&](float* wb, int t) {
 #pragma unroll
         for (int k = 0; k < MAXS; ++k) {
-            const int e = tid + k * NTH;
-            pre[k] = fetch(n, G0, e < nslots ? e : nslots - 1);
-        }
-    }
-
-    // weights: coalesced copy of the raw tensor into LDS (aliasing the window), then reorder
-    const int nW = p.M * p.R * p.S;
-    if (raw_in_lds) {
-        if ((reinterpret_cast<uintptr_t>(wt) & 15) == 0) {
-            for (int e = tid; e < nW / 4; e += NTH) reinterpret_cast<f32x4*>(win)[e] = reinterpret_cast<const f32x4*>(wt)[e];
-            for (int e = (nW / 4) * 4 + tid; e < nW; e += NTH) win[e] = wt[e];
-        } else {
-            for (int e = tid; e < nW; e += NTH) win[e] = wt[e];
-        }
-        __syncthreads();
-    }
-    for (int e = tid; e < nsteps * 64; e += NTH) {
-        const int step = e >> 6, l = e & 63;
-        const int m = l & 15, r = 4 * (step % RC) + (l >> 4), s = step / RC;
-        float v = 0.f;
-        if (m < p.M && r < p.R) {
-            const long idx = m * p.w_sm + r * p.w_sr + p.w_s0 + s * p.w_ss;
-            v = raw_in_lds ? win[idx] : wt[idx];
-        }
-        wfrag[e] = v;
-    }
-
-    while (tile < ntiles) {
-        const int n = tile / tiles_per_row;
-        const int O0 = (tile - n * tiles_per_row) * TQ;
-        __syncthreads();  // readers of the previous window (or of the raw weights) are done
-        if constexpr (FAST) {
-#pragma unroll
-            for (int k = 0; k < MAXS; ++k) {
-                const int e = tid + k * NTH;
-                if (e < nslots) commit(O0 - p.P, e, pre[k]);
-            }
-            for (int e = tid + MAXS * NTH; e < nslots; e += NTH) commit(O0 - p.P, e, fetch(n, O0 - p.P, e));
-        } else {
-            for (int e = tid; e < nslots; e += NTH) commit(O0 - p.P, e, fetch(n, O0 - p.P, e));
-        }
-        __syncthreads();
-
-        const int next = tile + gridDim.x;
-        if constexpr (FAST) {
-            if (next < ntiles) {
-                const int nn = next / tiles_per_row;
-                const int G0n = (next - nn * tiles_per_row) * TQ - p.P;
-#pragma unroll
-                for (int k = 0; k < MAXS; ++k) {
-                    const int e = tid + k * NTH;
-                    pre[k] = fetch(nn, G0n, e < nslots ? e : nslots - 1);
+            if (rtid + k * 256 < nslots) {
+                if constexpr (FAST) {
+                    commit(wb, t, slot[k], pre[k]);
+                } else {
+                    commit(wb, t, slot[k], fetch(t, slot[k]));
                 }
             }
         }
-        __builtin_amdgcn_sched_barrier(0);
+        for (int e = rtid + MAXS * 256; e < nslots; e += 256) {  // long halos: beyond the register budget
+            const Slot w = make_slot(e);
+            commit(wb, t, w, fetch(t, w));
+        }
+    };
 
+    // ---- prologue: weights (all waves), first window (producers) -------------------------------------
+    if (!consumer) {
+#pragma unroll
+        for (int k = 0; k < MAXS; ++k) slot[k] = make_slot(min(rtid + k * 256, nslots - 1));
+    }
+    {
+        // coalesced copy of the raw tensor into LDS (aliasing the windows), then reorder into wfrag
+        const int nW = p.M * p.R * p.S;
+        float* raw = win(0);
+        if (raw_in_lds) {
+            if ((reinterpret_cast<uintptr_t>(wt) & 15) == 0) {
+                constexpr int NV = (16 * 16 * 64 / 4 + 511) / 512;  // 16-byte pieces per thread for S <= 64
+                const int nvec = nW / 4;
+                f32x4 tmp[NV];
+#pragma unroll
+                for (int k = 0; k < NV; ++k) tmp[k] = reinterpret_cast<const f32x4*>(wt)[min(tid + k * 512, nvec > 0 ? nvec - 1 : 0)];
+                if (!consumer && t_begin < t_end) prefetch_tile(t_begin);  // queued behind the weight loads
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int k = 0; k < NV; ++k)
+                    if (tid + k * 512 < nvec) reinterpret_cast<f32x4*>(raw)[tid + k * 512] = tmp[k];
+                for (int e = NV * 512 + tid; e < nvec; e += 512) reinterpret_cast<f32x4*>(raw)[e] = reinterpret_cast<const f32x4*>(wt)[e];
+                for (int e = nvec * 4 + tid; e < nW; e += 512) raw[e] = wt[e];
+            } else {
+                for (int e = tid; e < nW; e += 512) raw[e] = wt[e];
+                if (!consumer && t_begin < t_end) prefetch_tile(t_begin);
+            }
+            __syncthreads();
+        } else if (!consumer && t_begin < t_end) {
+            prefetch_tile(t_begin);
+        }
+        for (int e = tid; e < nsteps * 64; e += 512) {
+            const int step = e >> 6, l = e & 63;
+            const int m = l & 15, r = 4 * (step % RC) + (l >> 4), s = step / RC;
+            float v = 0.f;
+            if (m < p.M && r < p.R) {
+                const long idx = m * p.w_sm + r * p.w_sr + p.w_s0 + s * p.w_ss;
+                v = raw_in_lds ? raw[idx] : wt[idx];
+            }
+            wfrag[e] = v;
+        }
+        __syncthreads();  // raw copy is dead, wfrag is complete
+    }
+    if (!consumer && t_begin < t_end) {
+        commit_tile(win(0), t_begin);
+        if (t_begin + 1 < t_end) prefetch_tile(t_begin + 1);
+    }
+    __syncthreads();
+
+    // ---- consumer side --------------------------------------------------------------------------------
+    auto compute = [&](const float* wb, int t) {
         f32x4 acc[T];
 #pragma unroll
         for (int j = 0; j < T; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-        const int ob = wave * T * 16;
-        const float* bptr = win + kb * LPS + ob + li;
-        const float* aptr = wfrag + lane;
-        // operands of tap s+1 are fetched from LDS while the MFMAs of tap s run
-        float a_cur[RC], b_cur[RC][T];
+        const int ob = cw * T * 16;
+        // running LDS indices (into lds[]), one per channel chunk, bumped by d per tap: the operand reads then
+        // carry immediate offsets only instead of an address add in front of each of them
+        int wi[RC];
 #pragma unroll
-        for (int cc = 0; cc < RC; ++cc) {
-            a_cur[cc] = aptr[cc * 64];
-#pragma unroll
-            for (int j = 0; j < T; ++j) b_cur[cc][j] = bptr[cc * 4 * LPS + j * 16];
-        }
-        for (int s = 0; s < p.S; ++s) {
-            const int sn = s + 1 < p.S ? s + 1 : s;
-            const float* bs = bptr + sn * p.d;
-            float a_nxt[RC], b_nxt[RC][T];
+        for (int cc = 0; cc < RC; ++cc) wi[cc] = static_cast<int>(wb - lds) + (4 * cc + kb) * LPS + ob + li;
+        int ai = lane;
+        float a0[RC], b0[RC][T], a1[RC], b1[RC][T];
+        auto load_tap = [&](float (&a)[RC], float (&b)[RC][T]) {  // loads the tap the indices point at
 #pragma unroll
             for (int cc = 0; cc < RC; ++cc) {
-                a_nxt[cc] = aptr[(sn * RC + cc) * 64];
+                a[cc] = lds[ai + cc * 64];
 #pragma unroll
-                for (int j = 0; j < T; ++j) b_nxt[cc][j] = bs[cc * 4 * LPS + j * 16];
+                for (int j = 0; j < T; ++j) b[cc][j] = lds[wi[cc] + j * 16];
             }
-            __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of the MFMA block
+        };
+        auto next_tap = [&]() {
+            ai += RC * 64;
 #pragma unroll
-            for (int cc = 0; cc < RC; ++cc) {
+            for (int cc = 0; cc < RC; ++cc) wi[cc] += p.d;
+        };
+        auto mfma_tap = [&](const float (&a)[RC], const float (&b)[RC][T]) {
 #pragma unroll
-                for (int j = 0; j < T; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[cc], b_cur[cc][j], acc[j], 0, 0, 0);
+            for (int cc = 0; cc < RC; ++cc)
+#pragma unroll
+                for (int j = 0; j < T; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[cc], b[cc][j], acc[j], 0, 0, 0);
+        };
+        // the LDS reads of the next tap are spread between the MFMAs of the current one
+        auto interleave = [&]() {
+#pragma unroll
+            for (int i = 0; i < RC * T; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             }
+            __builtin_amdgcn_sched_group_barrier(0x100, RC, 0);
+        };
+        // Keeps the operands of the tap just consumed live to the end of the tap: otherwise the register an
+        // MFMA has just been issued with is handed to the very next LDS read, which then cannot issue until
+        // the MFMA has finished fetching its sources.
+        auto keep = [&](const float (&b)[RC][T]) {
+#pragma unroll
+            for (int cc = 0; cc < RC; ++cc)
+#pragma unroll
+                for (int j = 0; j < T; ++j) asm volatile("" ::"v"(b[cc][j]));
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int cc = 0; cc < RC; ++cc) {
-                a_cur[cc] = a_nxt[cc];
-#pragma unroll
-                for (int j = 0; j < T; ++j) b_cur[cc][j] = b_nxt[cc][j];
-            }
+        };
+        load_tap(a0, b0);
+        int s = 0;
+        for (; s + 1 < p.S; s += 2) {
+            next_tap();
+            load_tap(a1, b1);
+            mfma_tap(a0, b0);
+            interleave();
+            keep(b0);
+            if (s + 2 < p.S) next_tap();  // (S even: the last look-ahead re-reads tap S-1 and is discarded)
+            load_tap(a0, b0);
+            mfma_tap(a1, b1);
+            interleave();
+            keep(b1);
         }
+        if (s < p.S) mfma_tap(a0, b0);  // odd S: the last tap is already loaded
+        const int n = tile_n(t), O0 = tile_O0(t);
 #pragma unroll
         for (int j = 0; j < T; ++j) {
             const int o = O0 + ob + j * 16 + li;
@@ -194,30 +251,52 @@ __global__ __launch_bounds__(WAVES * 64) void smallc_corr_f32_kernel(CorrProblem
                 }
             }
         }
-        tile = next;
+    };
+
+    // ---- steady state -----------------------------------------------------------------------------------
+    int k = 0;
+    for (int t = t_begin; t < t_end; ++t, ++k) {
+        const int b = nbuf == 2 ? (k & 1) : 0;
+        if (consumer) {
+            compute(win(b), t);
+        } else if (nbuf == 2 && t + 1 < t_end) {
+            commit_tile(win(b ^ 1), t + 1);
+            if (t + 2 < t_end) prefetch_tile(t + 2);
+        }
+        __syncthreads();
+        if (nbuf == 1 && t + 1 < t_end) {  // single buffer: refill it while the consumers wait
+            if (!consumer) {
+                commit_tile(win(0), t + 1);
+                if (t + 2 < t_end) prefetch_tile(t + 2);
+            }
+            __syncthreads();
+        }
     }
 }
 
 struct CorrF32Plan {
-    int RC, LPS, LP4, tiles_per_row, ntiles, fast, raw_in_lds;
+    int RC, LPS, LP4, tiles_per_row, ntiles, fast, raw_in_lds, nbuf;
     size_t lds_bytes;
     bool ok;
 };
 
-constexpr int kCorrT = 4, kCorrWaves = 8, kCorrMaxS = 8;
+constexpr int kCorrT = 4, kCorrMaxS = 11;
 
 CorrF32Plan corr_f32_plan(const CorrProblem& p) {
     CorrF32Plan pl{};
     pl.ok = false;
     if (p.bf16 || p.R > 16 || p.M > 16) return pl;
     if (static_cast<long>(p.R) * p.Win >= (1L << 30)) return pl;  // 32-bit element offsets within one sample
-    constexpr int TQ = kCorrWaves * kCorrT * 16;
+    constexpr int TQ = 4 * kCorrT * 16;
     pl.RC = (p.R + 3) / 4;
     const long halo = static_cast<long>(p.S - 1) * p.d;
     const long LP = TQ + halo;
     // row stride == 16 (mod 32) words: the four k rows of a B fragment fall on disjoint bank halves
-    long LPS = (LP + 31) / 32 * 32 + 16;
-    const long bytes = (static_cast<long>(p.S) * pl.RC * 64 + 4L * pl.RC * LPS) * 4;
+    const long LPS = (LP + 31) / 32 * 32 + 16;
+    const long wbytes = static_cast<long>(p.S) * pl.RC * 64 * 4;
+    const long win_bytes = 4L * pl.RC * LPS * 4;
+    pl.nbuf = wbytes + 2 * win_bytes <= kLdsBudget ? 2 : 1;
+    const long bytes = wbytes + pl.nbuf * win_bytes;
     if (bytes > kLdsBudget) return pl;
     pl.LPS = static_cast<int>(LPS);
     pl.LP4 = static_cast<int>((LP + 3) / 4);
@@ -228,19 +307,19 @@ CorrF32Plan corr_f32_plan(const CorrProblem& p) {
     pl.lds_bytes = static_cast<size_t>(bytes);
     // 16-byte window loads need every row start, the window origin and the base pointer aligned
     pl.fast = (p.Win % 4 == 0) && (((p.P % 4) + 4) % 4 == 0) && (reinterpret_cast<uintptr_t>(p.in) % 16 == 0) && p.Win >= 4;
-    pl.raw_in_lds = static_cast<long>(p.M) * p.R * p.S <= 4L * pl.RC * LPS;
+    pl.raw_in_lds = static_cast<long>(p.M) * p.R * p.S * 4 <= pl.nbuf * win_bytes;
     pl.ok = true;
     return pl;
 }
 
 template <int RC, bool FAST>
 hipError_t corr_f32_launch_f(const CorrProblem& p, const CorrF32Plan& pl, hipStream_t st) {
-    auto kern = smallc_corr_f32_kernel<RC, kCorrT, kCorrWaves, kCorrMaxS, FAST>;
+    auto kern = smallc_corr_f32_kernel<RC, kCorrT, kCorrMaxS, FAST>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        static_cast<int>(pl.lds_bytes));
     if (e != hipSuccess) return e;
     const int grid = pl.ntiles < kNumCU ? pl.ntiles : kNumCU;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kCorrWaves * 64), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.LP4,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.LP4, pl.nbuf,
                        pl.raw_in_lds);
     return hipGetLastError();
 }
@@ -339,7 +418,10 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
         const int g = (is_x ? o.Qs - p.P : o.Qs) + w.col;
         const bool ok = !(w.lds & kRowBad) && (!FAST || (g >= 0 && g + 4 <= limit));
         if (!ok) v = f32x4{0.f, 0.f, 0.f, 0.f};
-        *reinterpret_cast<f32x4*>((is_x ? xt(b) : dyt(b)) + (w.lds & (kRowBad - 1))) = v;
+        // rows are only 8-byte aligned (their stride is 2 mod 32 words, see the plan): two 8-byte stores
+        f32x2* dst = reinterpret_cast<f32x2*>((is_x ? xt(b) : dyt(b)) + (w.lds & (kRowBad - 1)));
+        dst[0] = f32x2{v[0], v[1]};
+        dst[1] = f32x2{v[2], v[3]};
     };
     Slot slot[MAXS];
     f32x4 pre[FAST ? MAXS : 1];
@@ -385,25 +467,29 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
     }
     __syncthreads();
 
-    int k = 0;
-    for (int chunk = c_begin; chunk < c_end; ++chunk, ++k) {
-        const int b = k & 1;
-        if (consumer) {
-            const float* ap = dyt(b) + li * LQS + kb;
-            const float* bp = xt(b) + li * LXS + kb + cw * p.d;
-            const int dstep = 4 * p.d;
-            // two k-steps per iteration with ping-pong operand registers: the LDS reads of the next k-step
-            // are issued between the MFMAs of the current one
-            float a0 = ap[0], b0[NT], a1, b1[NT];
+    // The two roles run separate loops (with one barrier per chunk each) so that neither carries the other's
+    // registers through its loop.
+    if (consumer) {
+        int k = 0;
+        for (int chunk = c_begin; chunk < c_end; ++chunk, ++k) {
+            const int b = k & 1;
+            // one running LDS index per tap slot (into lds[]): the reads then need no address arithmetic in
+            // front of them (a dependent v_add before every ds_read costs about a quarter of the MFMA rate)
+            int ai = b * stage_floats + li * LQS + kb;
+            int bi[NT];
 #pragma unroll
-            for (int i = 0; i < NT; ++i) b0[i] = bp[i * dstep];
+            for (int i = 0; i < NT; ++i) bi[i] = b * stage_floats + 16 * LQS + li * LXS + kb + (cw + 4 * i) * p.d;
+            // two k-steps per iteration with ping-pong operand registers: the LDS reads of the next k-step
+            // are issued between the MFMAs of the current one.  The reads of the last iteration run 4
+            // columns past the chunk (into row padding / the slack after the last row) and are discarded.
+            float a0 = lds[ai], b0[NT], a1, b1[NT];
+#pragma unroll
+            for (int i = 0; i < NT; ++i) b0[i] = lds[bi[i]];
             for (int t = 0; t < QC; t += 8) {
-                const int t1 = t + 4;
-                const int t2 = t + 8 < QC ? t + 8 : t + 4;
-                a1 = ap[t1];
+                a1 = lds[ai + 4];
 #pragma unroll
                 for (int i = 0; i < NT; ++i) {
-                    b1[i] = bp[t1 + i * dstep];
+                    b1[i] = lds[bi[i] + 4];
                     acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0[i], acc[i], 0, 0, 0);
                 }
 #pragma unroll
@@ -411,11 +497,16 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read ...
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // ... then one MFMA
                 }
+                // Keep the consumed operands live to the end of the k-step: otherwise the register of the
+                // operand an MFMA has just been issued with is handed to the very next LDS read, and that
+                // read cannot issue until the MFMA has finished fetching its sources.
+#pragma unroll
+                for (int i = 0; i < NT; ++i) asm volatile("" ::"v"(b0[i]));
                 __builtin_amdgcn_sched_barrier(0);
-                a0 = ap[t2];
+                a0 = lds[ai + 8];
 #pragma unroll
                 for (int i = 0; i < NT; ++i) {
-                    b0[i] = bp[t2 + i * dstep];
+                    b0[i] = lds[bi[i] + 8];
                     acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1[i], acc[i], 0, 0, 0);
                 }
 #pragma unroll
@@ -423,13 +514,25 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
                 }
+#pragma unroll
+                for (int i = 0; i < NT; ++i) asm volatile("" ::"v"(b1[i]));
                 __builtin_amdgcn_sched_barrier(0);
+                ai += 8;
+#pragma unroll
+                for (int i = 0; i < NT; ++i) bi[i] += 8;
             }
-        } else if (chunk + 1 < c_end) {
-            commit_chunk(b ^ 1, chunk + 1);
-            if (chunk + 2 < c_end) prefetch_chunk(chunk + 2);
+            __syncthreads();
         }
-        __syncthreads();
+    } else {
+        int k = 0;
+        for (int chunk = c_begin; chunk < c_end; ++chunk, ++k) {
+            const int b = k & 1;
+            if (chunk + 1 < c_end) {
+                commit_chunk(b ^ 1, chunk + 1);
+                if (chunk + 2 < c_end) prefetch_chunk(chunk + 2);
+            }
+            __syncthreads();
+        }
     }
     if (consumer) {
         const int nt = (p.S - cw + 3) / 4;  // real taps of this wave; slots beyond hold unused sums
@@ -486,12 +589,12 @@ WgradF32Plan wgrad_f32_plan(const WgradProblem& p) {
     if (p.bf16 || p.C > 16 || p.K > 16 || p.S > 4 * kWgradNT) return pl;
     if (static_cast<long>(p.C) * p.W >= (1L << 30) || static_cast<long>(p.K) * p.Q >= (1L << 30)) return pl;
     const long halo = static_cast<long>(4 * kWgradNT - 1) * p.d;  // every tap slot a wave may read
-    // 16-byte slot stores need 4-word aligned rows; a stride of 4 (mod 32) words lets 8 rows x 4 columns
-    // of an operand fragment cover 32 distinct banks
-    auto pad = [](long v) { return (v + 31) / 32 * 32 + 4; };
+    // row stride == 2 (mod 32) words: the 32 lanes (16 rows x 2 adjacent columns) that the LDS serves together
+    // fall on 32 distinct banks (a stride of 4 would pair row r with row r+8)
+    auto pad = [](long v) { return (v + 31) / 32 * 32 + 2; };
     for (int QC = 256; QC >= 64; QC /= 2) {  // the largest chunk whose two stages fit in LDS
         const long LQS = pad(QC), LXS = pad(QC + halo);
-        const long bytes = 2 * 16 * (LQS + LXS) * 4;
+        const long bytes = 2 * 16 * (LQS + LXS) * 4 + 64;  // + slack for the discarded look-ahead reads
         if (bytes > kLdsBudget) continue;
         pl.QC = QC;
         pl.LQS = static_cast<int>(LQS);
