@@ -95,16 +95,22 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
     // element loads, done when the window is written.
     struct Task { unsigned v[8]; };
     auto task_h = [&](int task) { return task >= LP2 ? 1 : 0; };
+    // (producer waves share their SIMD's issue slots with an MFMA wave, so their instruction count matters:
+    // one add and one min per load; rows beyond R re-read row R-1, which is harmless because the weight
+    // slices are zero there and the duplicated values are as finite as the originals)
     auto fetch_task = [&](int n, int G0, int task) -> Task {
         const int h = task_h(task);
         int g = G0 + 2 * (task - h * LP2);
         g = g < 0 ? 0 : (g > p.Win - 2 ? p.Win - 2 : g);
-        const unsigned short* base = in + static_cast<long>(n) * p.R * p.Win;  // uniform
+        const char* base = reinterpret_cast<const char*>(in + static_cast<long>(n) * p.R * p.Win);  // uniform
+        const unsigned rowb = static_cast<unsigned>(p.Win) * 2u;                                     // uniform
+        const unsigned offmax = static_cast<unsigned>((p.R - 1) * p.Win + g) * 2u;
+        unsigned off = static_cast<unsigned>(8 * h * p.Win + g) * 2u;
         Task t;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int r = min(8 * h + j, p.R - 1);
-            t.v[j] = *reinterpret_cast<const unsigned*>(base + static_cast<unsigned>(r * p.Win + g));
+            t.v[j] = *reinterpret_cast<const unsigned*>(base + min(off, offmax));
+            off += rowb;
         }
         return t;
     };
@@ -124,19 +130,29 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
         }
         return t;
     };
-    auto store_task = [&](u32x4* wb, int G0, int task, const Task& t) {
+    // FAST windows that lie inside the row need no masking at all (see above for the channel rows);
+    // `edge` is uniform per tile
+    auto store_task = [&](u32x4* wb, int G0, int task, const Task& t, bool edge) {
         const int h = task_h(task);
         const int pp = task - h * LP2;
-        const int g = G0 + 2 * pp;
-        // FAST: a pair is inside or outside the row as a whole (g and Win are even)
-        const bool pos_ok = !FAST || (g >= 0 && g < p.Win);
         u32x4 ev, od;
+        if (FAST && !edge) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const unsigned a = (pos_ok && 8 * h + 2 * q < p.R) ? t.v[2 * q] : 0u;
-            const unsigned b = (pos_ok && 8 * h + 2 * q + 1 < p.R) ? t.v[2 * q + 1] : 0u;
-            ev[q] = __builtin_amdgcn_perm(b, a, kPermLo);
-            od[q] = __builtin_amdgcn_perm(b, a, kPermHi);
+            for (int q = 0; q < 4; ++q) {
+                ev[q] = __builtin_amdgcn_perm(t.v[2 * q + 1], t.v[2 * q], kPermLo);
+                od[q] = __builtin_amdgcn_perm(t.v[2 * q + 1], t.v[2 * q], kPermHi);
+            }
+        } else {
+            const int g = G0 + 2 * pp;
+            // FAST: a pair is inside or outside the row as a whole (g and Win are even)
+            const bool pos_ok = !FAST || (g >= 0 && g < p.Win);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const unsigned a = (pos_ok && 8 * h + 2 * q < p.R) ? t.v[2 * q] : 0u;
+                const unsigned b = (pos_ok && 8 * h + 2 * q + 1 < p.R) ? t.v[2 * q + 1] : 0u;
+                ev[q] = __builtin_amdgcn_perm(b, a, kPermLo);
+                od[q] = __builtin_amdgcn_perm(b, a, kPermHi);
+            }
         }
         wb[h * LPS + 2 * pp] = ev;
         wb[h * LPS + 2 * pp + 1] = od;
@@ -156,15 +172,16 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
     };
     auto commit = [&](int t, u32x4* wb) {  // producers: registers (or memory) -> LDS window of tile t
         const int n = tile_n(t), G0 = tile_O0(t) - p.P;
+        const bool edge = G0 < 0 || G0 + 2 * LP2 > p.Win;
         if constexpr (FAST) {
 #pragma unroll
             for (int k = 0; k < MAXT; ++k) {
                 const int task = rtid + k * 256;
-                if (task < ntasks) store_task(wb, G0, task, pre[k]);
+                if (task < ntasks) store_task(wb, G0, task, pre[k], edge);
             }
-            for (int task = rtid + MAXT * 256; task < ntasks; task += 256) store_task(wb, G0, task, fetch_task(n, G0, task));
+            for (int task = rtid + MAXT * 256; task < ntasks; task += 256) store_task(wb, G0, task, fetch_task(n, G0, task), edge);
         } else {
-            for (int task = rtid; task < ntasks; task += 256) store_task(wb, G0, task, fetch_task_slow(n, G0, task));
+            for (int task = rtid; task < ntasks; task += 256) store_task(wb, G0, task, fetch_task_slow(n, G0, task), true);
         }
     };
     // producers: parked outputs of tile t (staging buffer b) -> global memory
@@ -267,20 +284,28 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
             constexpr int PF = 3;
             constexpr int D = 16 / (G > 0 ? G : 1);
             constexpr int NF = G * (T - 1) + NP;
-            bf16x8 fr[PF + 1];  // rotating: operand m lives in slot m % (PF + 1)
+            // rotating: operand m lives in slot m % (PF + 2); one slot more than the look-ahead needs, so that a
+            // read never targets the registers of the operand whose MFMAs have only just been issued
+            bf16x8 fr[PF + 2];
 #pragma unroll
             for (int m = 0; m < PF && m < NF; ++m) fr[m] = as_bf16x8(bbase[m * D]);
 #pragma unroll
             for (int m = 0; m < NF; ++m) {
-                if (m + PF < NF) fr[(m + PF) % (PF + 1)] = as_bf16x8(bbase[(m + PF) * D]);
+                if (m + PF < NF) fr[(m + PF) % (PF + 2)] = as_bf16x8(bbase[(m + PF) * D]);
 #pragma unroll
                 for (int j = 0; j < T; ++j)
                     if (G * j + NP - 1 == m - 2) park(j);
-                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int j = 0; j < T; ++j) {
                     const int pi = m - G * j;
-                    if (pi >= 0 && pi < NP) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[pi < 0 ? 0 : (pi >= NP ? 0 : pi)], fr[m % (PF + 1)], acc[j], 0, 0, 0);
+                    if (pi >= 0 && pi < NP) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[pi < 0 ? 0 : (pi >= NP ? 0 : pi)], fr[m % (PF + 2)], acc[j], 0, 0, 0);
+                }
+                // issue order within the step: one MFMA, one LDS operation, one MFMA, ... so that the operand
+                // read and the parking writes go out in the shadow of the MFMAs instead of in front of them
+#pragma unroll
+                for (int j = 0; j < T; ++j) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x080, 1, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
