@@ -32,6 +32,7 @@ CorrProblem fwd_problem(const Geom& g, const void* x, const void* w, float* y, i
     p.N = g.N; p.R = g.C; p.M = g.K; p.Win = g.W; p.Wout = g.Q; p.S = g.S; p.d = g.d; p.P = g.P;
     p.w_sm = static_cast<long>(g.C) * g.S; p.w_sr = g.S; p.w_s0 = 0; p.w_ss = 1;
     p.bf16 = bf16;
+    p.in_sn = static_cast<long>(p.R) * p.Win; p.out_sn = static_cast<long>(p.M) * p.Wout; p.accumulate = 0; p.w_contig = 1;
     return p;
 }
 
@@ -43,6 +44,7 @@ CorrProblem bwd_data_problem(const Geom& g, const void* dy, const void* w, float
     p.P = (g.S - 1) * g.d - g.P;
     p.w_sm = g.S; p.w_sr = static_cast<long>(g.C) * g.S; p.w_s0 = g.S - 1; p.w_ss = -1;
     p.bf16 = bf16;
+    p.in_sn = static_cast<long>(p.R) * p.Win; p.out_sn = static_cast<long>(p.M) * p.Wout; p.accumulate = 0; p.w_contig = 1;
     return p;
 }
 
@@ -51,6 +53,8 @@ WgradProblem wgrad_problem(const Geom& g, const void* x, const void* dy, float* 
     p.x = x; p.dy = dy; p.dw = dw; p.ws = ws; p.ws_bytes = wsb;
     p.N = g.N; p.C = g.C; p.K = g.K; p.W = g.W; p.Q = g.Q; p.S = g.S; p.d = g.d; p.P = g.P;
     p.bf16 = bf16;
+    p.x_sn = static_cast<long>(g.C) * g.W; p.dy_sn = static_cast<long>(g.K) * g.Q;
+    p.dw_sk = static_cast<long>(g.C) * g.S; p.dw_sc = g.S;
     return p;
 }
 

@@ -23,7 +23,7 @@ __global__ __launch_bounds__(kThreads) void generic_corr_kernel(CorrProblem p, i
     if (o >= p.Wout) return;
     float acc = 0.f;
     for (int r = 0; r < p.R; ++r) {
-        const long in_row = (static_cast<long>(n) * p.R + r) * p.Win;
+        const long in_row = static_cast<long>(n) * p.in_sn + static_cast<long>(r) * p.Win;
         const long w_row = m * p.w_sm + r * p.w_sr + p.w_s0;
         for (int s = 0; s < p.S; ++s) {
             const int i = o + s * p.d - p.P;
@@ -32,7 +32,8 @@ __global__ __launch_bounds__(kThreads) void generic_corr_kernel(CorrProblem p, i
             }
         }
     }
-    p.out[(static_cast<long>(n) * p.M + m) * p.Wout + o] = acc;
+    float* dst = p.out + static_cast<long>(n) * p.out_sn + static_cast<long>(m) * p.Wout + o;
+    *dst = p.accumulate ? *dst + acc : acc;
 }
 
 // partial[chunk][k][c][s] = sum over the chunk's samples and all q.

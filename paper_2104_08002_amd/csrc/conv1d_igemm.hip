@@ -1,8 +1,87 @@
+// Channel-blocked MFMA family: layers with more than 16 channels or filters.
+//
+// Algorithms 1-4 of the paper block the channel and filter dimensions and run one small GEMM per
+// (tap, block pair).  The same blocking is applied here one level up: C and K are cut into blocks of 16, the
+// width of the MFMA tile the small-channel kernels are built around, and every (filter block, channel block)
+// pair is one launch of those kernels on a strided view of the tensors.
+//   fwd / bwd_data  out[:, mb, :] (+)= corr(in[:, rb, :], wt[mb, rb, :])   the first channel block overwrites,
+//                                                                         the following ones accumulate
+//   bwd_weight      dw[kb, cb, :]  = wgrad(x[:, cb, :], dy[:, kb, :])      each pair owns its block of dw
+// All launches go to the caller's stream in a fixed order, so results are deterministic and the one
+// workspace is reused by every pair.
 #include "conv1d_internal.h"
+
 namespace conv1d {
-bool igemm_corr_supported(const CorrProblem&) { return false; }
-hipError_t igemm_corr_launch(const CorrProblem&, hipStream_t) { return hipErrorInvalidValue; }
-bool igemm_wgrad_supported(const WgradProblem&) { return false; }
-size_t igemm_wgrad_workspace(const WgradProblem&) { return 0; }
-hipError_t igemm_wgrad_launch(const WgradProblem&, hipStream_t) { return hipErrorInvalidValue; }
+namespace {
+
+constexpr int kBlock = 16;
+
+inline const void* advance(const void* base, long elems, int bf16) {
+    return static_cast<const char*>(base) + elems * (bf16 ? 2 : 4);
+}
+
+CorrProblem corr_block(const CorrProblem& p, int m0, int r0) {
+    CorrProblem b = p;
+    b.M = p.M - m0 < kBlock ? p.M - m0 : kBlock;
+    b.R = p.R - r0 < kBlock ? p.R - r0 : kBlock;
+    b.in = advance(p.in, static_cast<long>(r0) * p.Win, p.bf16);
+    b.wt = advance(p.wt, m0 * p.w_sm + r0 * p.w_sr, p.bf16);
+    b.out = p.out + static_cast<long>(m0) * p.Wout;
+    b.accumulate = p.accumulate || r0 > 0;
+    b.w_contig = 0;
+    return b;
+}
+
+WgradProblem wgrad_block(const WgradProblem& p, int k0, int c0) {
+    WgradProblem b = p;
+    b.K = p.K - k0 < kBlock ? p.K - k0 : kBlock;
+    b.C = p.C - c0 < kBlock ? p.C - c0 : kBlock;
+    b.x = advance(p.x, static_cast<long>(c0) * p.W, p.bf16);
+    b.dy = advance(p.dy, static_cast<long>(k0) * p.Q, p.bf16);
+    b.dw = p.dw + k0 * p.dw_sk + c0 * p.dw_sc;
+    return b;
+}
+
+}  // namespace
+
+// The first block pair is the largest one; the others differ from it only by having fewer rows.
+bool igemm_corr_supported(const CorrProblem& p) {
+    if (p.R <= kBlock && p.M <= kBlock) return false;  // one block: that is the small-channel family itself
+    return smallc_corr_supported(corr_block(p, 0, 0));
+}
+
+hipError_t igemm_corr_launch(const CorrProblem& p, hipStream_t st) {
+    if (!igemm_corr_supported(p)) return hipErrorInvalidValue;
+    for (int m0 = 0; m0 < p.M; m0 += kBlock) {
+        for (int r0 = 0; r0 < p.R; r0 += kBlock) {
+            const CorrProblem b = corr_block(p, m0, r0);
+            const hipError_t e = smallc_corr_launch(b, st);
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
+}
+
+bool igemm_wgrad_supported(const WgradProblem& p) {
+    if (p.C <= kBlock && p.K <= kBlock) return false;
+    return smallc_wgrad_supported(wgrad_block(p, 0, 0));
+}
+
+size_t igemm_wgrad_workspace(const WgradProblem& p) {
+    if (!igemm_wgrad_supported(p)) return 0;
+    return smallc_wgrad_workspace(wgrad_block(p, 0, 0));
+}
+
+hipError_t igemm_wgrad_launch(const WgradProblem& p, hipStream_t st) {
+    if (!igemm_wgrad_supported(p)) return hipErrorInvalidValue;
+    for (int k0 = 0; k0 < p.K; k0 += kBlock) {
+        for (int c0 = 0; c0 < p.C; c0 += kBlock) {
+            const WgradProblem b = wgrad_block(p, k0, c0);
+            const hipError_t e = smallc_wgrad_launch(b, st);
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
+}
+
 }  // namespace conv1d

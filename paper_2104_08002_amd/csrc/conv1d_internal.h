@@ -24,6 +24,12 @@ struct CorrProblem {
     long w_sm, w_sr;
     int w_s0, w_ss;
     int bf16;  // 0: float inputs, 1: bfloat16 inputs
+    // A problem may be a channel block of a larger layer: rows r < R / m < M of samples that are in_sn / out_sn
+    // elements apart (in_sn = R*Win, out_sn = M*Wout for a whole layer).  accumulate != 0 adds to `out`.
+    long in_sn, out_sn;
+    int accumulate;
+    // != 0 when the M*R*S weights wt(m,r,s) are exactly the contiguous elements wt[0 .. M*R*S)
+    int w_contig;
 };
 
 // The backward-weight problem (Section 3.3):
@@ -36,6 +42,9 @@ struct WgradProblem {
     size_t ws_bytes;
     int N, C, K, W, Q, S, d, P;
     int bf16;
+    // A problem may be a (filter block, channel block) of a larger layer: sample strides of x and dy in elements
+    // (C*W and K*Q for a whole layer) and the strides of dw between filters and between channels (C*S and S).
+    long x_sn, dy_sn, dw_sk, dw_sc;
 };
 
 // generic (plain FMA) family: any geometry
@@ -57,7 +66,8 @@ bool smallc_bf16_wgrad_supported(const WgradProblem& p);
 size_t smallc_bf16_wgrad_workspace(const WgradProblem& p);
 hipError_t smallc_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st);
 // fixed-order sum of per-workgroup partial tiles ws[(wg*S + s)*256 + k*16 + c] into dw[k][c][s]
-hipError_t smallc_wgrad_reduce_launch(const float* ws, float* dw, int K, int C, int S, int nwg, hipStream_t st);
+hipError_t smallc_wgrad_reduce_launch(const float* ws, float* dw, int K, int C, int S, long dw_sk, long dw_sc, int nwg,
+                                      hipStream_t st);
 
 // implicit-GEMM MFMA family
 bool igemm_corr_supported(const CorrProblem& p);

@@ -77,7 +77,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
         return Slot{static_cast<unsigned>(min(r, p.R - 1) * p.Win), 4 * i, (r * LPS + 4 * i) | (r < p.R ? 0 : kRowBad)};
     };
     auto fetch = [&](int t, const Slot& w) -> f32x4 {
-        const float* row = in + static_cast<long>(tile_n(t)) * p.R * p.Win + w.off;
+        const float* row = in + static_cast<long>(tile_n(t)) * p.in_sn + w.off;
         const int g = tile_O0(t) - p.P + w.col;
         if constexpr (FAST) {
             const int lim = p.Win - 4;  // >= 0 on this path (checked by the host)
@@ -247,7 +247,10 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int m = 4 * kb + i;
-                    if (m < p.M) p.out[(static_cast<long>(n) * p.M + m) * p.Wout + o] = acc[j][i];
+                    if (m < p.M) {
+                        float* dst = p.out + static_cast<long>(n) * p.out_sn + static_cast<long>(m) * p.Wout + o;
+                        *dst = p.accumulate ? *dst + acc[j][i] : acc[j][i];
+                    }
                 }
             }
         }
@@ -307,7 +310,7 @@ CorrF32Plan corr_f32_plan(const CorrProblem& p) {
     pl.lds_bytes = static_cast<size_t>(bytes);
     // 16-byte window loads need every row start, the window origin and the base pointer aligned
     pl.fast = (p.Win % 4 == 0) && (((p.P % 4) + 4) % 4 == 0) && (reinterpret_cast<uintptr_t>(p.in) % 16 == 0) && p.Win >= 4;
-    pl.raw_in_lds = static_cast<long>(p.M) * p.R * p.S * 4 <= pl.nbuf * win_bytes;
+    pl.raw_in_lds = p.w_contig && static_cast<long>(p.M) * p.R * p.S * 4 <= pl.nbuf * win_bytes;
     pl.ok = true;
     return pl;
 }
@@ -391,7 +394,7 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
     struct Origin { const float* xb; const float* dyb; int Qs; };
     auto origin = [&](int chunk) -> Origin {
         const int n = chunk / chunks_per_row;
-        return Origin{x + static_cast<long>(n) * p.C * p.W, dy + static_cast<long>(n) * p.K * p.Q, (chunk - n * chunks_per_row) * QC};
+        return Origin{x + static_cast<long>(n) * p.x_sn, dy + static_cast<long>(n) * p.dy_sn, (chunk - n * chunks_per_row) * QC};
     };
     auto fetch = [&](const Origin& o, int k, const Slot& w) -> f32x4 {
         const bool is_x = slot_is_x(k);
@@ -551,7 +554,8 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
 // Second stage of the backward-weight pass: dw[k][c][s] = sum over workgroups g of
 // ws[(g*S + s)*256 + k*16 + c], always in the same order: 16 contiguous groups of workgroups are
 // summed left to right by 16 threads each, then the 16 group sums are added left to right.
-__global__ __launch_bounds__(256) void smallc_wgrad_reduce_kernel(const float* __restrict__ ws, float* __restrict__ dw, int K, int C, int S, int nwg) {
+__global__ __launch_bounds__(256) void smallc_wgrad_reduce_kernel(const float* __restrict__ ws, float* __restrict__ dw, int K, int C, int S, long dw_sk,
+                                                                  long dw_sc, int nwg) {
     __shared__ float part[16][17];
     const int el = threadIdx.x & 15, grp = threadIdx.x >> 4;
     const int e = blockIdx.x * 16 + el;  // index into one workgroup's S*256 partial tile
@@ -571,7 +575,7 @@ __global__ __launch_bounds__(256) void smallc_wgrad_reduce_kernel(const float* _
 #pragma unroll
         for (int i = 1; i < 16; ++i) sum += part[i][el];
         const int s = e >> 8, k = (e >> 4) & 15, c = e & 15;
-        if (k < K && c < C) dw[(k * C + c) * S + s] = sum;
+        if (k < K && c < C) dw[k * dw_sk + c * dw_sc + s] = sum;
     }
 }
 
@@ -616,8 +620,9 @@ WgradF32Plan wgrad_f32_plan(const WgradProblem& p) {
 
 }  // namespace
 
-hipError_t smallc_wgrad_reduce_launch(const float* ws, float* dw, int K, int C, int S, int nwg, hipStream_t st) {
-    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(cdiv(S * 256, 16)), dim3(256), 0, st, ws, dw, K, C, S, nwg);
+hipError_t smallc_wgrad_reduce_launch(const float* ws, float* dw, int K, int C, int S, long dw_sk, long dw_sc, int nwg,
+                                      hipStream_t st) {
+    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(cdiv(S * 256, 16)), dim3(256), 0, st, ws, dw, K, C, S, dw_sk, dw_sc, nwg);
     return hipGetLastError();
 }
 
@@ -662,7 +667,7 @@ hipError_t smallc_wgrad_launch(const WgradProblem& p, hipStream_t st) {
                        pl.LX4);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return smallc_wgrad_reduce_launch(static_cast<const float*>(p.ws), p.dw, p.K, p.C, p.S, pl.grid, st);
+    return smallc_wgrad_reduce_launch(static_cast<const float*>(p.ws), p.dw, p.K, p.C, p.S, p.dw_sk, p.dw_sc, pl.grid, st);
 }
 
 }  // namespace conv1d

@@ -102,7 +102,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
         const int h = task_h(task);
         int g = G0 + 2 * (task - h * LP2);
         g = g < 0 ? 0 : (g > p.Win - 2 ? p.Win - 2 : g);
-        const char* base = reinterpret_cast<const char*>(in + static_cast<long>(n) * p.R * p.Win);  // uniform
+        const char* base = reinterpret_cast<const char*>(in + static_cast<long>(n) * p.in_sn);  // uniform
         const unsigned rowb = static_cast<unsigned>(p.Win) * 2u;                                     // uniform
         const unsigned offmax = static_cast<unsigned>((p.R - 1) * p.Win + g) * 2u;
         unsigned off = static_cast<unsigned>(8 * h * p.Win + g) * 2u;
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
         const int g = G0 + 2 * (task - h * LP2);
         const int g0 = g < 0 ? 0 : (g > p.Win - 1 ? p.Win - 1 : g);
         const int g1 = g + 1 < 0 ? 0 : (g + 1 > p.Win - 1 ? p.Win - 1 : g + 1);
-        const unsigned short* base = in + static_cast<long>(n) * p.R * p.Win;
+        const unsigned short* base = in + static_cast<long>(n) * p.in_sn;
         Task t;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -194,14 +194,20 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 const f32x4 v = *reinterpret_cast<const f32x4*>(src + (2 * q + orow) * kOS + ocol);
-                float* base = p.out + (static_cast<long>(n) * p.M + 2 * q) * p.Wout + O0 + ob;  // uniform
-                if (2 * q + orow < p.M && o < p.Wout) *reinterpret_cast<f32x4*>(base + static_cast<unsigned>(orow * p.Wout + ocol)) = v;
+                float* base = p.out + static_cast<long>(n) * p.out_sn + static_cast<long>(2 * q) * p.Wout + O0 + ob;  // uniform
+                if (2 * q + orow < p.M && o < p.Wout) {
+                    f32x4* dst = reinterpret_cast<f32x4*>(base + static_cast<unsigned>(orow * p.Wout + ocol));
+                    *dst = p.accumulate ? *dst + v : v;
+                }
             }
         } else {
             for (int idx = lane; idx < 16 * T * 16; idx += 64) {
                 const int m = idx / (T * 16), col = idx - m * (T * 16);
                 const int o = O0 + ob + col;
-                if (m < p.M && o < p.Wout) p.out[(static_cast<long>(n) * p.M + m) * p.Wout + o] = src[m * kOS + col];
+                if (m < p.M && o < p.Wout) {
+                    float* dst = p.out + static_cast<long>(n) * p.out_sn + static_cast<long>(m) * p.Wout + o;
+                    *dst = p.accumulate ? *dst + src[m * kOS + col] : src[m * kOS + col];
+                }
             }
         }
     };
@@ -213,7 +219,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
     // then keeps all NP slices in registers.  Both areas alias the output staging buffers.
     u32x4* entries = lds4 + 4 * LPS;
     unsigned short* raw = reinterpret_cast<unsigned short*>(entries + NP * 64);
-    {
+    if (p.w_contig) {
         const int nW = p.M * p.R * p.S;
         constexpr int NV = (16 * 16 * 2 * NP / 8 + 511) / 512;  // 16-byte pieces per thread, worst case
         if ((reinterpret_cast<uintptr_t>(wt) & 15) == 0) {
@@ -231,6 +237,8 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
             for (int e = tid; e < nW; e += 512) raw[e] = wt[e];
             if (!consumer && t_begin < t_end) prefetch(t_begin);
         }
+    } else if (!consumer && t_begin < t_end) {
+        prefetch(t_begin);
     }
     __syncthreads();
     bf16x8 wreg[NP];
@@ -243,8 +251,13 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
             const int pi = e >> 6, l = e & 63;
             const int m = min(l & 15, p.M - 1), h = (l >> 4) & 1, s = min(pi + NP * (l >> 5), p.S - 1);
             const int base = static_cast<int>(m * p.w_sm + p.w_s0 + s * p.w_ss);
+            if (p.w_contig) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) wv[k][j] = raw[base + min(8 * h + j, p.R - 1) * static_cast<int>(p.w_sr)];
+                for (int j = 0; j < 8; ++j) wv[k][j] = raw[base + min(8 * h + j, p.R - 1) * static_cast<int>(p.w_sr)];
+            } else {  // a block of a larger tensor: gather straight from global memory
+#pragma unroll
+                for (int j = 0; j < 8; ++j) wv[k][j] = wt[m * p.w_sm + p.w_s0 + s * p.w_ss + min(8 * h + j, p.R - 1) * p.w_sr];
+            }
         }
 #pragma unroll
         for (int k = 0; k < NE; ++k) {
@@ -463,8 +476,8 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_bf16_d8_kernel(WgradProbl
     const int j0 = (blockIdx.x - n * SPR) * UPS;
     const int j1 = min(j0 + UPS, units_per_row);
     const int Qb = min(j1 * kUnitSlots * 8, p.Q);  // this strip's dy columns end here
-    const unsigned short* xn = x + static_cast<long>(n) * p.C * p.W;
-    const unsigned short* dyn = dy + static_cast<long>(n) * p.K * p.Q;
+    const unsigned short* xn = x + static_cast<long>(n) * p.x_sn;
+    const unsigned short* dyn = dy + static_cast<long>(n) * p.dy_sn;
 
     constexpr int NX = 16 * kXP, NS = 16 * (kXP + kUnitSlots);
     // Staging slot e of stage j: e < NX is x period j+1 (row e / kXP), the rest is dy unit j.  Everything
@@ -689,7 +702,7 @@ hipError_t smallc_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return smallc_wgrad_reduce_launch(static_cast<const float*>(p.ws), p.dw, p.K, p.C, p.S, pl.grid, st);
+    return smallc_wgrad_reduce_launch(static_cast<const float*>(p.ws), p.dw, p.K, p.C, p.S, p.dw_sk, p.dw_sc, pl.grid, st);
 }
 
 }  // namespace conv1d

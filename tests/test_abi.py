@@ -90,3 +90,19 @@ def test_headline_workloads_dispatch_to_mfma_kernels():
         code = 1 if wl.dtype == "bf16" else 0
         names = [binding.conv1d_kernel_name(i, *wl.geometry(), code) for i in range(3)]
         assert all("mfma" in n for n in names), names
+
+
+def test_wide_layers_dispatch_to_blocked_mfma_kernels():
+    """More than 16 channels or filters: the channel-blocked family, not the plain-FMA fallback."""
+    from paper_2104_08002_amd import inputs
+
+    binding.conv1d_set_variant(binding.VARIANT_AUTO)
+    for wl in (inputs.WIDE_BF16, inputs.sweep_point(51, 8, "fp32"), inputs.sweep_point(9, 1, "fp32")):
+        code = 1 if wl.dtype == "bf16" else 0
+        names = [binding.conv1d_kernel_name(i, *wl.geometry(), code) for i in range(2 if code else 3)]
+        assert all(n.startswith("igemm_") and "mfma" in n for n in names), names
+    # the workspace of the blocked family is that of one 16 x 16 block pair
+    wl = inputs.sweep_point(51, 8, "fp32")
+    g = wl.geometry()
+    small = (g[0], 16, 16) + tuple(g[3:])
+    assert binding.conv1d_bwd_weight_workspace_bytes(*g, 0) == binding.conv1d_bwd_weight_workspace_bytes(*small, 0)

@@ -160,10 +160,12 @@ def test_bwd_weight_is_deterministic(binding, wl):
 
 
 # ---- outputs are overwritten, not accumulated into (beta = 0) ------------------------------------
-def test_outputs_are_overwritten(binding, oracle):
+@pytest.mark.parametrize("wl", [inputs.scaled(inputs.GENOMICS_FP32, N=2, W=3000, name="overwrite"),
+                                inputs.scaled(inputs.sweep_point(9, 4, "fp32"), N=2, W=2000, name="overwrite_blocked")],
+                         ids=lambda w: w.name)
+def test_outputs_are_overwritten(binding, oracle, wl):
     import torch
 
-    wl = inputs.scaled(inputs.GENOMICS_FP32, N=2, W=3000, name="overwrite")
     data = inputs.make_inputs(wl)
     dev = to_device(wl, data)
     y = torch.full((wl.N, wl.K, wl.Q), float("nan"), device="cuda")
