@@ -69,7 +69,13 @@ hipError_t smallc_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st);
 hipError_t smallc_wgrad_reduce_launch(const float* ws, float* dw, int K, int C, int S, long dw_sk, long dw_sc, int nwg,
                                       hipStream_t st);
 
-// implicit-GEMM MFMA family
+// bf16 backward-weight for any dilation and channel count: (filter group x channel block x tap group) tiles, the
+// positions cut into strips whose partial tensors a second kernel adds
+bool blocked_bf16_wgrad_supported(const WgradProblem& p);
+size_t blocked_bf16_wgrad_workspace(const WgradProblem& p);
+hipError_t blocked_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st);
+
+// channel-blocked MFMA family
 bool igemm_corr_supported(const CorrProblem& p);
 hipError_t igemm_corr_launch(const CorrProblem& p, hipStream_t st);
 bool igemm_wgrad_supported(const WgradProblem& p);

@@ -86,6 +86,7 @@ def sweep(dtype: str) -> Iterator[Workload]:
 
 
 WORKLOADS: Dict[str, Workload] = {w.name: w for w in (TINY, GENOMICS_FP32, GENOMICS_BF16, WIDE_BF16)}
+WORKLOADS.update({w.name: w for dt in ("fp32", "bf16") for w in sweep(dt)})
 for _dt in ("fp32", "bf16"):
     for _w in sweep(_dt):
         WORKLOADS[_w.name] = _w
