@@ -36,8 +36,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 constexpr int kLdsBudget = 160 * 1024;
 constexpr int kNumCU = 256;
 constexpr int kMaxY = 8;   // dy staging slots per producer thread
-constexpr int kMaxX = 6;   // x staging slots per producer thread
-constexpr int kRowBad = 1 << 30;
+constexpr int kMaxI = 12;  // x load items (slot, even phase base) per producer thread
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -46,41 +45,27 @@ struct BlkArgs {
     const unsigned short* dy;
     float* ws;
     int C, K, W, Q, S, d, P;
-    long x_sn, dy_sn, KCS;
+    long x_sn, dy_sn;
     int CPR, nchunks, nstrips;  // chunks per sample row, N * CPR, strips
-    int nfg, ncb, ntg;          // filter groups, channel blocks, tap groups
-    int QC, nksw;               // columns per chunk, k-steps (32 columns) per consumer wave = QC / 128
+    int nfg, ncb, ntg;          // filter groups, channel groups, tap groups
+    int ncbw;                   // channel blocks per workgroup (1, 2 or 4): consumer wave v works on block v % ncbw
+    int QC, nksw;               // columns per chunk, k-steps (32 columns) per consumer wave = QC / 32 * ncbw / 4
     int RSY, RSX, NXS;          // LDS row strides in 16-byte slots (odd), x slots staged per row
     unsigned phase_mask;        // bit phi set: a tap with (s*d - P - fl8) % 8 == phi exists in some tap group
-    int xcopy_slots;            // 16 * RSX
+    unsigned gmask;             // bit g set: phase 2g or 2g + 1 is in use
+    int xcopy_slots;            // 16 * ncbw * RSX
     int ybuf_slots;             // FB * 16 * RSY
     int stage_slots;            // ybuf_slots + ncopies * xcopy_slots
 };
 
-// out = elements [phi, phi + 8) of the 16 consecutive elements (lo, hi)
-__device__ __forceinline__ u32x4 shift_elems(u32x4 lo, u32x4 hi, int phi) {
-    switch (phi) {
-        case 0: return lo;
-        case 1: return u32x4{__builtin_amdgcn_alignbit(lo.y, lo.x, 16), __builtin_amdgcn_alignbit(lo.z, lo.y, 16),
-                             __builtin_amdgcn_alignbit(lo.w, lo.z, 16), __builtin_amdgcn_alignbit(hi.x, lo.w, 16)};
-        case 2: return u32x4{lo.y, lo.z, lo.w, hi.x};
-        case 3: return u32x4{__builtin_amdgcn_alignbit(lo.z, lo.y, 16), __builtin_amdgcn_alignbit(lo.w, lo.z, 16),
-                             __builtin_amdgcn_alignbit(hi.x, lo.w, 16), __builtin_amdgcn_alignbit(hi.y, hi.x, 16)};
-        case 4: return u32x4{lo.z, lo.w, hi.x, hi.y};
-        case 5: return u32x4{__builtin_amdgcn_alignbit(lo.w, lo.z, 16), __builtin_amdgcn_alignbit(hi.x, lo.w, 16),
-                             __builtin_amdgcn_alignbit(hi.y, hi.x, 16), __builtin_amdgcn_alignbit(hi.z, hi.y, 16)};
-        case 6: return u32x4{lo.w, hi.x, hi.y, hi.z};
-        default: return u32x4{__builtin_amdgcn_alignbit(hi.x, lo.w, 16), __builtin_amdgcn_alignbit(hi.y, hi.x, 16),
-                              __builtin_amdgcn_alignbit(hi.z, hi.y, 16), __builtin_amdgcn_alignbit(hi.w, hi.z, 16)};
-    }
-}
-
 template <int FB, int NT, bool FAST>
 __global__ __launch_bounds__(512, 2) void blocked_wgrad_bf16_kernel(BlkArgs a) {
     extern __shared__ u32x4 lds4[];
-    // operand prefetch distance in taps: the LDS latency has to be covered by PF * FB MFMAs
-    constexpr int PF = FB == 1 ? 6 : (FB == 2 ? 4 : 2);
-    constexpr int R = PF + 2;                  // operand ring
+    // x operands live in a ring of R registers that is refilled PF = R - 2 taps ahead of its use (the LDS
+    // latency has to be covered by PF * FB MFMAs).  R divides the taps of a k-step wherever the registers
+    // allow, so that the refills run on seamlessly into the next k-step.
+    constexpr int R = NT == 26 ? 13 : ((FB == 2 && NT == 17) ? 6 : NT);
+    constexpr int PF = R - 2;
     constexpr int NTP = (NT + R - 1) / R * R;  // ring positions per k-step (taps padded to a multiple of R)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -102,130 +87,25 @@ __global__ __launch_bounds__(512, 2) void blocked_wgrad_bf16_kernel(BlkArgs a) {
     const int tg = combo % a.ntg;
     const int cbi = (combo / a.ntg) % a.ncb;
     const int fg = combo / (a.ntg * a.ncb);
-    const int s0 = tg * NT, c0 = cbi * 16, k0 = fg * FB * 16;
+    const int xrows = 16 * a.ncbw;
+    const int s0 = tg * NT, c0 = cbi * xrows, k0 = fg * FB * 16;
     const int fl8 = ((s0 * a.d - a.P) >> 3) * 8;  // window origin relative to the chunk: floor to a multiple of 8
     const int ch_begin = static_cast<int>(static_cast<long>(strip) * a.nchunks / a.nstrips);
     const int ch_end = static_cast<int>(static_cast<long>(strip + 1) * a.nchunks / a.nstrips);
+    f32x4* red = reinterpret_cast<f32x4*>(lds4);
 
-    // ---- producer side ---------------------------------------------------------------------------
-    // A staging slot is 8 consecutive columns of one row.  dy slot (row, i) <-> dy[k0 + row][q0 + 8i ..];
-    // x slot (row, i) <-> x[c0 + row][q0 + fl8 + 8i ..], needed with every phase shift, so the next 8 columns
-    // are loaded with it.  FAST (all widths and sample strides multiples of 8 elements, 16-byte aligned
-    // pointers): 16-byte loads from clamped addresses, masked when written to LDS; a slot is then inside or
-    // outside its row as a whole.  Otherwise element loads, done when the stage is written.
-    struct Slot {
-        unsigned off;  // element offset of the (clamped) source row from the sample's base
-        int col;       // column of the slot relative to the chunk's origin
-        int lds;       // row * stride + i, bit 30: row beyond C or K
-    };
-    const int SY = a.QC >> 3;
-    const int NY = FB * 16 * SY, NX = 16 * a.NXS;
-    auto make_y = [&](int e) -> Slot {
-        const int row = e / SY, i = e - row * SY;
-        return Slot{static_cast<unsigned>(min(k0 + row, a.K - 1)) * static_cast<unsigned>(a.Q), 8 * i,
-                    (row * a.RSY + i) | (k0 + row < a.K ? 0 : kRowBad)};
-    };
-    auto make_x = [&](int e) -> Slot {
-        const int row = e / a.NXS, i = e - row * a.NXS;
-        return Slot{static_cast<unsigned>(min(c0 + row, a.C - 1)) * static_cast<unsigned>(a.W), 8 * i,
-                    (row * a.RSX + i) | (c0 + row < a.C ? 0 : kRowBad)};
-    };
-    auto load8 = [&](const unsigned short* row, int g, int limit) -> u32x4 {  // columns g .. g+7 of a row of `limit` columns
-        if constexpr (FAST) {
-            const int lim = limit - 8;  // >= 0 on this path (checked by the host)
-            return *reinterpret_cast<const u32x4*>(row + (g < 0 ? 0 : (g > lim ? lim : g)));
-        } else {
-            unsigned t[8];
-#pragma unroll
-            for (int jj = 0; jj < 8; ++jj) {
-                const int gj = g + jj;
-                const int gc = gj < 0 ? 0 : (gj > limit - 1 ? limit - 1 : gj);
-                t[jj] = (gj >= 0 && gj < limit) ? row[gc] : 0u;
-            }
-            return u32x4{t[0] | (t[1] << 16), t[2] | (t[3] << 16), t[4] | (t[5] << 16), t[6] | (t[7] << 16)};
-        }
-    };
-    auto inside = [&](int g, int limit) { return !FAST || (g >= 0 && g + 8 <= limit); };
-    const u32x4 zero4 = u32x4{0u, 0u, 0u, 0u};
-
-    Slot ys[kMaxY], xs[kMaxX];
-    u32x4 ypre[FAST ? kMaxY : 1], xlo[FAST ? kMaxX : 1], xhi[FAST ? kMaxX : 1];
-    if (!consumer) {
-#pragma unroll
-        for (int k = 0; k < kMaxY; ++k) ys[k] = make_y(min(rtid + k * 256, NY - 1));
-#pragma unroll
-        for (int k = 0; k < kMaxX; ++k) xs[k] = make_x(min(rtid + k * 256, NX - 1));
-    }
-    auto origin = [&](int ch, const unsigned short*& xn, const unsigned short*& dyn, int& q0) {
-        const int n = ch / a.CPR;
-        q0 = (ch - n * a.CPR) * a.QC;
-        xn = a.x + static_cast<long>(n) * a.x_sn;
-        dyn = a.dy + static_cast<long>(n) * a.dy_sn;
-    };
-    auto prefetch = [&](int ch) {
-        if constexpr (FAST) {
-            const unsigned short *xn, *dyn;
-            int q0;
-            origin(ch, xn, dyn, q0);
-#pragma unroll
-            for (int k = 0; k < kMaxY; ++k) ypre[k] = load8(dyn + ys[k].off, q0 + ys[k].col, a.Q);
-#pragma unroll
-            for (int k = 0; k < kMaxX; ++k) {
-                xlo[k] = load8(xn + xs[k].off, q0 + fl8 + xs[k].col, a.W);
-                xhi[k] = load8(xn + xs[k].off, q0 + fl8 + xs[k].col + 8, a.W);
-            }
-        }
-    };
-    auto commit = [&](int ch, int b) {
-        const unsigned short *xn, *dyn;
-        int q0;
-        origin(ch, xn, dyn, q0);
-        u32x4* ybuf = lds4 + b * a.stage_slots;
-        u32x4* xbuf = ybuf + a.ybuf_slots;
-#pragma unroll
-        for (int k = 0; k < kMaxY; ++k) {
-            if (rtid + k * 256 < NY) {
-                const int g = q0 + ys[k].col;
-                u32x4 v;
-                if constexpr (FAST) v = ypre[k]; else v = load8(dyn + ys[k].off, g, a.Q);
-                if ((ys[k].lds & kRowBad) || !inside(g, a.Q)) v = zero4;
-                ybuf[ys[k].lds & (kRowBad - 1)] = v;
-            }
-        }
-#pragma unroll
-        for (int k = 0; k < kMaxX; ++k) {
-            if (rtid + k * 256 < NX) {
-                const int g = q0 + fl8 + xs[k].col;
-                u32x4 lo, hi;
-                if constexpr (FAST) {
-                    lo = xlo[k];
-                    hi = xhi[k];
-                } else {
-                    lo = load8(xn + xs[k].off, g, a.W);
-                    hi = load8(xn + xs[k].off, g + 8, a.W);
-                }
-                const bool bad = xs[k].lds & kRowBad;
-                if (bad || !inside(g, a.W)) lo = zero4;
-                if (bad || !inside(g + 8, a.W)) hi = zero4;
-                u32x4* dst = xbuf + (xs[k].lds & (kRowBad - 1));
-                for (unsigned m = a.phase_mask; m != 0; m &= m - 1) {  // uniform: one copy per phase in use
-                    *dst = shift_elems(lo, hi, __builtin_ctz(m));
-                    dst += a.xcopy_slots;
-                }
-            }
-        }
-    };
-
-    // ---- consumer side ---------------------------------------------------------------------------
-    // Byte offsets into LDS of this lane's operands in stage 0, k-step 0 of this wave's quarter:
-    //   dy operand of filter block fb:  row 16 fb + li, slot 4 ks + kb
-    //   x operand of tap s0 + i:        copy of phase (delta & 7), row li, slot 4 ks + kb + (delta >> 3),
-    //                                   delta = (s0 + i) d - P - fl8 >= 0
-    // Taps beyond S (last tap group) are clamped to tap S - 1 for addressing; their sums are not stored.
-    unsigned ay[FB], bx[NT];
-    f32x4 acc[FB][NT];
-    {
-        const int ks0 = cw * a.nksw;
+    if (consumer) {
+        // ---- consumer side -----------------------------------------------------------------------
+        // Wave cw works on channel block cw % ncbw and on the k-steps [ks0, ks0 + nksw) of every chunk.
+        // Byte offsets into LDS of this lane's operands in stage 0, k-step ks0:
+        //   dy operand of filter block fb:  row 16 fb + li, slot 4 ks + kb
+        //   x operand of tap s0 + i:        copy of phase (delta & 7), row 16 (cw % ncbw) + li,
+        //                                   slot 4 ks + kb + (delta >> 3),  delta = (s0 + i) d - P - fl8 >= 0
+        // Taps beyond S (last tap group) are clamped to tap S - 1 for addressing; their sums are not stored.
+        const int cbl = cw % a.ncbw;
+        const int ks0 = (cw / a.ncbw) * a.nksw;
+        unsigned ay[FB], bx[NT];
+        f32x4 acc[FB][NT];
 #pragma unroll
         for (int fb = 0; fb < FB; ++fb) ay[fb] = 16u * static_cast<unsigned>((fb * 16 + li) * a.RSY + 4 * ks0 + kb);
 #pragma unroll
@@ -233,111 +113,270 @@ __global__ __launch_bounds__(512, 2) void blocked_wgrad_bf16_kernel(BlkArgs a) {
             const int s = min(s0 + i, a.S - 1);
             const int delta = s * a.d - a.P - fl8;
             const int ci = __builtin_popcount(a.phase_mask & ((1u << (delta & 7)) - 1u));
-            bx[i] = 16u * static_cast<unsigned>(a.ybuf_slots + ci * a.xcopy_slots + li * a.RSX + 4 * ks0 + kb + (delta >> 3));
+            bx[i] = 16u * static_cast<unsigned>(a.ybuf_slots + ci * a.xcopy_slots + (cbl * 16 + li) * a.RSX + 4 * ks0 + kb + (delta >> 3));
 #pragma unroll
             for (int fb = 0; fb < FB; ++fb) acc[fb][i] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
-    }
-    const char* ldsb = reinterpret_cast<const char*>(lds4);
-    auto ld = [&](unsigned off) { return as_bf16x8(*reinterpret_cast<const u32x4*>(ldsb + off)); };
+        const char* ldsb = reinterpret_cast<const char*>(lds4);
+        auto ld = [&](unsigned off) { return as_bf16x8(*reinterpret_cast<const u32x4*>(ldsb + off)); };
 
-    auto compute = [&](int b) {
-        unsigned ko = static_cast<unsigned>(b * a.stage_slots) * 16u;
-        bf16x8 acur[FB], anxt[FB], ring[R];
-#pragma unroll
-        for (int fb = 0; fb < FB; ++fb) acur[fb] = ld(ay[fb] + ko);
-#pragma unroll
-        for (int i = 0; i < PF; ++i)
-            if (i < NT) ring[i % R] = ld(bx[i] + ko);
-        for (int ks = 0; ks < a.nksw; ++ks) {
-            // (the reads issued for "the next k-step" in the last k-step fall into the slack behind the rows)
-#pragma unroll
-            for (int fb = 0; fb < FB; ++fb) anxt[fb] = ld(ay[fb] + ko + 64);
-#pragma unroll
-            for (int i = 0; i < NTP; ++i) {
-                const int f = i + PF;  // ring position to refill
-                if (f < NTP) {
-                    if (f < NT) ring[f % R] = ld(bx[f] + ko);
-                } else if (f - NTP < NT) {
-                    ring[f % R] = ld(bx[f - NTP] + ko + 64);
-                }
-                if (i < NT) {
-#pragma unroll
-                    for (int fb = 0; fb < FB; ++fb)
-                        acc[fb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(acur[fb], ring[i % R], acc[fb][i], 0, 0, 0);
-                }
-            }
-#pragma unroll
-            for (int fb = 0; fb < FB; ++fb) acur[fb] = anxt[fb];
-            ko += 64;
-        }
-    };
-
-    // ---- pipeline (one loop per role: the register allocation of one role is not burdened by the other's) ------
-    f32x4* red = reinterpret_cast<f32x4*>(lds4);
-    if (consumer) {
         __syncthreads();
         for (int ch = ch_begin; ch < ch_end; ++ch) {
-            compute((ch - ch_begin) & 1);
+            {
+                // The operand addresses run along with the k-steps (one add per operand and k-step, off the
+                // critical path) and hop to the other stage at the end of the chunk.  Within a k-step the x
+                // operand of tap i + PF and, in the first FB positions, the dy operands of the next k-step are
+                // read while the MFMAs of tap i run; the group barriers pin that interleaving.
+                bf16x8 acur[FB], anxt[FB], ring[R];
+#pragma unroll
+                for (int fb = 0; fb < FB; ++fb) acur[fb] = ld(ay[fb]);
+#pragma unroll
+                for (int i = 0; i < PF; ++i)
+                    if (i < NT) ring[i % R] = ld(bx[i]);
+                for (int ks = 0; ks < a.nksw; ++ks) {
+                    // (the reads issued for "the next k-step" in the last k-step fall into the slack behind the rows)
+#pragma unroll
+                    for (int i = 0; i < NTP; ++i) {
+                        const int f = i + PF;  // ring position to refill
+                        int nreads = 0;
+                        if (f < NTP) {
+                            if (f < NT) {
+                                ring[f % R] = ld(bx[f]);
+                                ++nreads;
+                            }
+                        } else if (f - NTP < NT) {
+                            ring[f % R] = ld(bx[f - NTP] + 64);
+                            ++nreads;
+                        }
+                        if (i < FB) {
+                            anxt[i] = ld(ay[i] + 64);
+                            ++nreads;
+                        }
+                        if (i < NT) {
+#pragma unroll
+                            for (int fb = 0; fb < FB; ++fb)
+                                acc[fb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(acur[fb], ring[i % R], acc[fb][i], 0, 0, 0);
+                        }
+                        if (nreads == 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                        if (nreads == 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        if (i < NT) __builtin_amdgcn_sched_group_barrier(0x008, FB, 0);
+                    }
+#pragma unroll
+                    for (int fb = 0; fb < FB; ++fb) {
+                        acur[fb] = anxt[fb];
+                        ay[fb] += 64;
+                    }
+#pragma unroll
+                    for (int i = 0; i < NT; ++i) bx[i] += 64;
+                }
+                const unsigned hop = (((ch - ch_begin) & 1) ? 0u - static_cast<unsigned>(a.stage_slots) : static_cast<unsigned>(a.stage_slots)) * 16u -
+                                     static_cast<unsigned>(a.nksw) * 64u;
+#pragma unroll
+                for (int fb = 0; fb < FB; ++fb) ay[fb] += hop;
+#pragma unroll
+                for (int i = 0; i < NT; ++i) bx[i] += hop;
+            }
             __syncthreads();
         }
-        // ---- add the four consumers' sums and write this strip's partial block ----------------------
+        // park the sums: the waves that share a channel block are added below
 #pragma unroll
         for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
             for (int i = 0; i < NT; ++i) red[((cw * FB + fb) * NT + i) * 64 + lane] = acc[fb][i];
     } else {
+        // ---- producer side -----------------------------------------------------------------------
+        // A staging slot is 8 consecutive columns of one row; consecutive threads stage consecutive slots of a
+        // row (coalesced loads, conflict-free LDS writes).  dy slot (row, i) <-> dy[k0 + row][q0 + 8i ..].
+        // x slot (row, i) of the copy of phase phi <-> x[c0 + row][q0 + fl8 + phi + 8i ..].  16-byte global loads
+        // run at full speed from any 4-byte aligned address, so an even phase is simply loaded where it starts;
+        // an odd phase phi = e + 1 is made from the load of the even phase e and the dword behind it, shifted
+        // by one element.  A load item is (slot, even base e); every thread owns up to kMaxI of them.
+        // Rows beyond C or K re-read the last row: their sums are never stored and no other sum depends on them.
+        // FAST (widths, sample strides and pointers multiples of 2 elements) and the chunk "interior" (its whole
+        // window inside the rows: all but the first and last chunks of a row): loads from scalar base +
+        // per-thread constant offsets, fetched one chunk ahead, written unmasked.  Every other chunk is loaded
+        // element by element, zero outside the row, when it is written to LDS.
+        const int SY = a.QC >> 3;
+        const int NY = FB * 16 * SY, NXT = xrows * a.NXS;
+        const int ng = __builtin_popcount(a.gmask);
+        const int nitems = ((NXT + 255) >> 8) * ng;
+        unsigned yoffb[kMaxY], xoffb[kMaxI];  // byte offset of the slot's first column (phase 0) from the chunk origin of the sample
+        int ylds[kMaxY], xlds[kMaxI];         // row * stride + slot
+        int ycol[kMaxY], xcol[kMaxI];         // first column relative to the chunk / window origin
+        unsigned yrow[kMaxY], xrow[kMaxI];    // element offset of the (clamped) row from the sample's base
+#pragma unroll
+        for (int k = 0; k < kMaxY; ++k) {
+            const int e = min(rtid + k * 256, NY - 1);
+            const int row = e / SY, i = e - row * SY;
+            yrow[k] = static_cast<unsigned>(min(k0 + row, a.K - 1)) * static_cast<unsigned>(a.Q);
+            ycol[k] = 8 * i;
+            yoffb[k] = 2u * (yrow[k] + 8u * static_cast<unsigned>(i));
+            ylds[k] = row * a.RSY + i;
+        }
+        // item it = (slot task it / ng, even base = 2 * (it % ng)-th set bit of gmask); all of that is uniform
+        auto item_base = [&](int it) {
+            unsigned m = a.gmask;
+            for (int g = it % ng; g > 0; --g) m &= m - 1;
+            return 2 * __builtin_ctz(m);
+        };
+#pragma unroll
+        for (int it = 0; it < kMaxI; ++it) {
+            const int e = min(rtid + (it / ng) * 256, NXT - 1);
+            const int row = e / a.NXS, i = e - row * a.NXS;
+            xrow[it] = static_cast<unsigned>(min(c0 + row, a.C - 1)) * static_cast<unsigned>(a.W);
+            xcol[it] = 8 * i + (it < nitems ? item_base(it) : 0);
+            xoffb[it] = 2u * (xrow[it] + static_cast<unsigned>(xcol[it]));
+            xlds[it] = row * a.RSX + i;
+        }
+        // columns g .. g+7 of a row of `limit` columns that starts `off` elements behind `base`, zero outside the row
+        auto load8 = [&](const unsigned short* base, unsigned off, int g, int limit) -> u32x4 {
+            unsigned t[8];
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) {  // unconditional loads from clamped columns: all in flight together
+                const int gj = g + jj;
+                t[jj] = base[off + static_cast<unsigned>(gj < 0 ? 0 : (gj > limit - 1 ? limit - 1 : gj))];
+            }
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj)
+                if (g + jj < 0 || g + jj >= limit) t[jj] = 0u;
+            return u32x4{t[0] | (t[1] << 16), t[2] | (t[3] << 16), t[4] | (t[5] << 16), t[6] | (t[7] << 16)};
+        };
+        struct Stage {
+            u32x4 y[kMaxY];
+            u32x4 x[kMaxI];
+            unsigned xd[kMaxI];  // the dword behind x[it] (odd phases)
+        };
+        struct Geo {
+            const unsigned short* xn;
+            const unsigned short* dyn;
+            int q0;
+            bool interior;
+        };
+        auto geo = [&](int ch) -> Geo {
+            Geo g;
+            const int n = ch / a.CPR;
+            g.q0 = (ch - n * a.CPR) * a.QC;
+            g.xn = a.x + static_cast<long>(n) * a.x_sn;
+            g.dyn = a.dy + static_cast<long>(n) * a.dy_sn;
+            const int x0 = g.q0 + fl8;
+            g.interior = FAST && g.q0 + a.QC <= a.Q && x0 >= 0 && x0 + 8 * a.NXS + 16 <= a.W;
+            return g;
+        };
+        auto has_odd = [&](int it) { return (a.phase_mask >> (item_base(it) + 1)) & 1u; };
+        auto prefetch = [&](Stage& st, int ch) {
+            const Geo g = geo(ch);
+            if (!g.interior) return;
+            const char* yb = reinterpret_cast<const char*>(g.dyn + g.q0);
+            const char* xb = reinterpret_cast<const char*>(g.xn + (g.q0 + fl8));
+#pragma unroll
+            for (int k = 0; k < kMaxY; ++k)
+                if (k * 256 < NY) st.y[k] = *reinterpret_cast<const u32x4*>(yb + yoffb[k]);
+#pragma unroll
+            for (int it = 0; it < kMaxI; ++it)
+                if (it < nitems) {
+                    st.x[it] = *reinterpret_cast<const u32x4*>(xb + xoffb[it]);
+                    if (has_odd(it)) st.xd[it] = *reinterpret_cast<const unsigned*>(xb + xoffb[it] + 16);
+                }
+        };
+        auto commit = [&](Stage& st, int ch, int b) {
+            const Geo g = geo(ch);
+            if (!g.interior) {
+#pragma unroll
+                for (int k = 0; k < kMaxY; ++k)
+                    if (k * 256 < NY) st.y[k] = load8(g.dyn, yrow[k], g.q0 + ycol[k], a.Q);
+#pragma unroll
+                for (int it = 0; it < kMaxI; ++it)
+                    if (it < nitems) {
+                        const int c = g.q0 + fl8 + xcol[it];
+                        st.x[it] = load8(g.xn, xrow[it], c, a.W);
+                        const int c8 = c + 8;
+                        const unsigned xd = g.xn[xrow[it] + static_cast<unsigned>(c8 < 0 ? 0 : (c8 > a.W - 1 ? a.W - 1 : c8))];
+                        st.xd[it] = (c8 >= 0 && c8 < a.W) ? xd : 0u;
+                    }
+            }
+            u32x4* ybuf = lds4 + b * a.stage_slots;
+            u32x4* xbuf = ybuf + a.ybuf_slots;
+#pragma unroll
+            for (int k = 0; k < kMaxY; ++k)
+                if (rtid + k * 256 < NY) ybuf[ylds[k]] = st.y[k];
+#pragma unroll
+            for (int it = 0; it < kMaxI; ++it)
+                if (it < nitems && rtid + (it / ng) * 256 < NXT) {
+                    const int e = item_base(it);
+                    const unsigned below = a.phase_mask & ((1u << e) - 1u);
+                    u32x4* dst = xbuf + __builtin_popcount(below) * a.xcopy_slots + xlds[it];
+                    const u32x4 v = st.x[it];
+                    if ((a.phase_mask >> e) & 1u) {
+                        *dst = v;
+                        dst += a.xcopy_slots;
+                    }
+                    if ((a.phase_mask >> (e + 1)) & 1u)
+                        *dst = u32x4{__builtin_amdgcn_alignbit(v.y, v.x, 16), __builtin_amdgcn_alignbit(v.z, v.y, 16),
+                                     __builtin_amdgcn_alignbit(v.w, v.z, 16), __builtin_amdgcn_alignbit(st.xd[it], v.w, 16)};
+                }
+        };
+        Stage st;
         if (ch_begin < ch_end) {
-            prefetch(ch_begin);
-            commit(ch_begin, 0);
-            if (ch_begin + 1 < ch_end) prefetch(ch_begin + 1);
+            prefetch(st, ch_begin);
+            commit(st, ch_begin, 0);
+            if (ch_begin + 1 < ch_end) prefetch(st, ch_begin + 1);
         }
         __syncthreads();
         for (int ch = ch_begin; ch < ch_end; ++ch) {
             if (ch + 1 < ch_end) {
-                commit(ch + 1, ((ch - ch_begin) & 1) ^ 1);
-                if (ch + 2 < ch_end) prefetch(ch + 2);
+                commit(st, ch + 1, ((ch - ch_begin) & 1) ^ 1);
+                    if (ch + 2 < ch_end) prefetch(st, ch + 2);
             }
             __syncthreads();
         }
     }
+
+    // ---- add the sums of the waves that share a channel block; one contiguous tile per workgroup ----------
+    //   tile element ((cbl * FB + fb) * NT + i) * 256 + 4 * lane + jj  <->  filter k0 + 16 fb + 4 (lane >> 4) + jj,
+    //   channel c0 + 16 cbl + (lane & 15), tap s0 + i
     __syncthreads();
     const float* redf = reinterpret_cast<const float*>(lds4);
-    float* ws = a.ws + static_cast<long>(strip) * a.KCS;
-    for (int e = tid; e < FB * NT * 256; e += 512) {
-        float sum = redf[e];
-#pragma unroll
-        for (int w = 1; w < 4; ++w) sum += redf[w * FB * NT * 256 + e];
-        const int blk = e >> 8, r = e & 255;
-        const int fb = blk / NT, i = blk - fb * NT;
-        const int l = r >> 2, jj = r & 3;
-        const int k = k0 + 16 * fb + 4 * (l >> 4) + jj, c = c0 + (l & 15), s = s0 + i;
-        if (k < a.K && c < a.C && s < a.S) ws[(static_cast<long>(k) * a.C + c) * a.S + s] = sum;
+    const int tile = a.ncbw * FB * NT * 256;
+    float* ws = a.ws + static_cast<long>(lid) * tile;
+    const int nparts = 4 / a.ncbw;
+    for (int e = tid; e < tile; e += 512) {
+        const int cbl = e / (FB * NT * 256), r = e - cbl * (FB * NT * 256);
+        float sum = redf[cbl * (FB * NT * 256) + r];
+        for (int part = 1; part < nparts; ++part) sum += redf[(cbl + part * a.ncbw) * (FB * NT * 256) + r];
+        ws[e] = sum;
     }
 }
 
-// dw[e] = sum over strips of ws[strip][e], strips added in a fixed order: 16 interleaved running sums per
-// element, then those 16 in order.
-__global__ __launch_bounds__(256) void blocked_wgrad_reduce_kernel(const float* __restrict__ ws, float* __restrict__ dw, long KCS, int nstrips) {
+// Adds the strips in a fixed order (16 interleaved running sums per element, then those 16 in order) and
+// scatters the tiles into dw[k][c][s].  One thread group of 16 x 16 per 16 consecutive tile elements.
+__global__ __launch_bounds__(256) void blocked_wgrad_reduce_kernel(const float* __restrict__ ws, float* __restrict__ dw, BlkArgs a, int FB, int NT) {
     __shared__ float part[16][17];
     const int el = threadIdx.x & 15, g = threadIdx.x >> 4;
-    const long e = static_cast<long>(blockIdx.x) * 16 + el;
+    const int tile = a.ncbw * FB * NT * 256;
+    const int ncombos = a.nfg * a.ncb * a.ntg;
+    const long idx = static_cast<long>(blockIdx.x) * 16 + el;  // (combo, tile element)
+    const int combo = static_cast<int>(idx / tile), e = static_cast<int>(idx - static_cast<long>(combo) * tile);
     float sum = 0.f;
-    if (e < KCS)
-        for (int s = g; s < nstrips; s += 16) sum += ws[s * KCS + e];
+    if (combo < ncombos)
+        for (int s = g; s < a.nstrips; s += 16) sum += ws[(static_cast<long>(s) * ncombos + combo) * tile + e];
     part[g][el] = sum;
     __syncthreads();
-    if (g == 0 && e < KCS) {
+    if (g == 0 && combo < ncombos) {
         float t = part[0][el];
 #pragma unroll
         for (int j = 1; j < 16; ++j) t += part[j][el];
-        dw[e] = t;
+        const int tg = combo % a.ntg, cbi = (combo / a.ntg) % a.ncb, fg = combo / (a.ntg * a.ncb);
+        const int blk = e >> 8, r = e & 255;
+        const int i = blk % NT, fb = (blk / NT) % FB, cbl = blk / (NT * FB);
+        const int l = r >> 2, jj = r & 3;
+        const int k = (fg * FB + fb) * 16 + 4 * (l >> 4) + jj, c = (cbi * a.ncbw + cbl) * 16 + (l & 15), s = tg * NT + i;
+        if (k < a.K && c < a.C && s < a.S) dw[(static_cast<long>(k) * a.C + c) * a.S + s] = t;
     }
 }
 
 struct BlkPlan {
     bool ok;
-    int FB, NT, fast, grid;
+    int FB, NT, fast, grid, tile;
     size_t lds_bytes;
     BlkArgs a;
 };
@@ -376,7 +415,6 @@ BlkPlan blk_plan(const WgradProblem& p) {
     pl.NT = kShapes[order[oi]].NT;
     a.ntg = cdiv(p.S, pl.NT);
     a.nfg = cdiv(nfb, pl.FB);
-    a.ncb = cdiv(p.C, 16);
     // phases in use: delta = s*d - P - fl8(group) over all taps of all groups
     a.phase_mask = 0;
     for (int s = 0; s < p.S; ++s) {
@@ -385,18 +423,27 @@ BlkPlan blk_plan(const WgradProblem& p) {
         a.phase_mask |= 1u << ((static_cast<long>(s) * p.d - p.P - fl8) & 7);
     }
     const int ncopies = __builtin_popcount(a.phase_mask);
+    a.gmask = 0;
+    for (int g = 0; g < 4; ++g)
+        if ((a.phase_mask >> (2 * g)) & 3u) a.gmask |= 1u << g;
+    const int ng = __builtin_popcount(a.gmask);
     const long span = static_cast<long>(pl.NT - 1) * p.d + 7;  // largest delta
+    // as many channel blocks per workgroup as fit (every x row then serves FB filter blocks and every dy row
+    // ncbw channel blocks), then the longest chunk
+    for (int ncbw = p.C > 32 ? 4 : (p.C > 16 ? 2 : 1); ncbw >= 1; ncbw /= 2) {
     for (int QC = 512; QC >= 128; QC /= 2) {
         const int SY = QC / 8;
         if (pl.FB * 16 * SY > 256 * kMaxY) continue;
         const long NXS = SY + span / 8 + 1;
-        if (16 * NXS > 256 * kMaxX) continue;
+        if ((16 * ncbw * NXS + 255) / 256 * ng > kMaxI) continue;
+        a.ncbw = ncbw;
+        a.ncb = cdiv(p.C, 16 * ncbw);
         a.QC = QC;
-        a.nksw = QC / 128;
+        a.nksw = QC / 32 * ncbw / 4;
         a.RSY = SY + 1;
         a.NXS = static_cast<int>(NXS);
-        a.RSX = static_cast<int>(NXS | 1);
-        a.xcopy_slots = 16 * a.RSX;
+        a.RSX = a.NXS | 1;
+        a.xcopy_slots = 16 * ncbw * a.RSX;
         a.ybuf_slots = pl.FB * 16 * a.RSY;
         a.stage_slots = a.ybuf_slots + ncopies * a.xcopy_slots;
         // + slack for the look-ahead reads of the last k-step (4 slots behind the last row)
@@ -417,15 +464,17 @@ BlkPlan blk_plan(const WgradProblem& p) {
         const long grid = static_cast<long>(ncombos) * nstrips;
         if (grid > 0x7fffffffL) return pl;
         pl.grid = static_cast<int>(grid);
+        pl.tile = ncbw * pl.FB * pl.NT * 256;
         a.x = static_cast<const unsigned short*>(p.x);
         a.dy = static_cast<const unsigned short*>(p.dy);
         a.ws = static_cast<float*>(p.ws);
         a.C = p.C; a.K = p.K; a.W = p.W; a.Q = p.Q; a.S = p.S; a.d = p.d; a.P = p.P;
-        a.x_sn = p.x_sn; a.dy_sn = p.dy_sn; a.KCS = KCS;
-        pl.fast = (p.W % 8 == 0) && (p.Q % 8 == 0) && (p.x_sn % 8 == 0) && (p.dy_sn % 8 == 0) && p.W >= 8 && p.Q >= 8 &&
-                  (reinterpret_cast<uintptr_t>(p.x) % 16 == 0) && (reinterpret_cast<uintptr_t>(p.dy) % 16 == 0);
+        a.x_sn = p.x_sn; a.dy_sn = p.dy_sn;
+        pl.fast = (p.W % 2 == 0) && (p.Q % 2 == 0) && (p.x_sn % 2 == 0) && (p.dy_sn % 2 == 0) &&
+                  (reinterpret_cast<uintptr_t>(p.x) % 4 == 0) && (reinterpret_cast<uintptr_t>(p.dy) % 4 == 0);
         pl.ok = true;
         return pl;
+    }
     }
     }
     return pl;
@@ -447,7 +496,7 @@ bool blocked_bf16_wgrad_supported(const WgradProblem& p) { return blk_plan(p).ok
 
 size_t blocked_bf16_wgrad_workspace(const WgradProblem& p) {
     const BlkPlan pl = blk_plan(p);
-    return pl.ok ? static_cast<size_t>(pl.a.nstrips) * pl.a.KCS * sizeof(float) : 0;
+    return pl.ok ? static_cast<size_t>(pl.grid) * pl.tile * sizeof(float) : 0;
 }
 
 hipError_t blocked_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st) {
@@ -469,8 +518,9 @@ hipError_t blocked_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st) {
         default: break;
     }
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(blocked_wgrad_reduce_kernel, dim3(cdiv(pl.a.KCS, 16)), dim3(256), 0, st, static_cast<const float*>(p.ws), p.dw, pl.a.KCS,
-                       pl.a.nstrips);
+    const long nel = static_cast<long>(pl.grid / pl.a.nstrips) * pl.tile;
+    hipLaunchKernelGGL(blocked_wgrad_reduce_kernel, dim3(cdiv(nel, 16)), dim3(256), 0, st, static_cast<const float*>(p.ws), p.dw, pl.a, pl.FB,
+                       pl.NT);
     return hipGetLastError();
 }
 
