@@ -37,9 +37,20 @@ def sources():
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
     extra = ["-DCONV1D_DEV_FEW_KERNELS"] if os.environ.get("CONV1D_DEV_FEW_KERNELS") else []  # faster edit-compile loop
-    cmd = [hipcc(), *HIP_FLAGS, *extra, "-c", src, "-o", obj]
+    cmd = [hipcc(), *HIP_FLAGS, *extra, "-Rpass-analysis=kernel-resource-usage", "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
-    msgs = "\n".join(l for l in (r.stdout + r.stderr).splitlines() if "packed-fp32-ops" not in l)
+    lines = (r.stdout + r.stderr).splitlines()
+    # a kernel that keeps an array in scratch memory runs orders of magnitude slower than intended: say so loudly
+    name = None
+    for l in lines:
+        if "Function Name:" in l:
+            name = l.split("Function Name:")[1].strip()
+        elif "ScratchSize [bytes/lane]:" in l and name is not None:
+            nbytes = int(l.split("ScratchSize [bytes/lane]:")[1].split()[0])
+            if nbytes > 128:
+                print(f"WARNING: {os.path.basename(src)}: kernel {name} uses {nbytes} bytes of scratch per lane", file=sys.stderr)
+            name = None
+    msgs = "\n".join(l for l in lines if "packed-fp32-ops" not in l and "remark:" not in l and "[-Rpass-analysis" not in l)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{msgs}")
     if msgs.strip():

@@ -46,12 +46,14 @@ WgradProblem wgrad_block(const WgradProblem& p, int k0, int c0) {
 
 // The first block pair is the largest one; the others differ from it only by having fewer rows.
 bool igemm_corr_supported(const CorrProblem& p) {
+    if (p.bf16 && igemm_bf16_corr_supported(p)) return true;
     if (p.R <= kBlock && p.M <= kBlock) return false;  // one block: that is the small-channel family itself
     return smallc_corr_supported(corr_block(p, 0, 0));
 }
 
 hipError_t igemm_corr_launch(const CorrProblem& p, hipStream_t st) {
     if (!igemm_corr_supported(p)) return hipErrorInvalidValue;
+    if (p.bf16 && igemm_bf16_corr_supported(p)) return igemm_bf16_corr_launch(p, st);
     for (int m0 = 0; m0 < p.M; m0 += kBlock) {
         for (int r0 = 0; r0 < p.R; r0 += kBlock) {
             const CorrProblem b = corr_block(p, m0, r0);

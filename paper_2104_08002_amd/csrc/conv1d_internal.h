@@ -75,6 +75,11 @@ bool blocked_bf16_wgrad_supported(const WgradProblem& p);
 size_t blocked_bf16_wgrad_workspace(const WgradProblem& p);
 hipError_t blocked_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st);
 
+// bf16 forward / backward-data for many channels: implicit GEMM over (channel chunk, tap) with the weights
+// gathered into LDS stage by stage
+bool igemm_bf16_corr_supported(const CorrProblem& p);
+hipError_t igemm_bf16_corr_launch(const CorrProblem& p, hipStream_t st);
+
 // channel-blocked MFMA family
 bool igemm_corr_supported(const CorrProblem& p);
 hipError_t igemm_corr_launch(const CorrProblem& p, hipStream_t st);

@@ -381,7 +381,7 @@ CorrPlan corr_plan(const CorrProblem& p) {
     // operand reuse across tiles pays when a tile shift is a few taps (d = 4, 8, 16); for d = 1, 2 the
     // shift is 16 or 8 taps, little is shared and the unrolled schedule gets very long
     pl.G = (p.d == 4 || p.d == 8 || p.d == 16) ? 16 / p.d : 0;
-    if (pl.NP == 17 && pl.G == 4) pl.G = 0;  // this instantiation does not fit the register budget
+    if (pl.NP >= 13 && pl.G == 4) pl.G = 0;  // these instantiations do not fit the register budget
     constexpr int TQ = 4 * kCorrT * 16;
     const long LP = TQ + static_cast<long>(2 * pl.NP - 1) * p.d;
     const long LPS = (LP + 2 + 7) / 8 * 8;
@@ -424,7 +424,7 @@ hipError_t corr_launch_np(const CorrProblem& p, const CorrPlan& pl, hipStream_t 
 #ifndef CONV1D_DEV_FEW_KERNELS
         case 1: return corr_launch_t<NP, 1>(p, pl, st);
         case 4:
-            if constexpr (NP != 17) return corr_launch_t<NP, 4>(p, pl, st);  // (17, 4) is routed to G = 0 by the plan
+            if constexpr (NP < 13) return corr_launch_t<NP, 4>(p, pl, st);  // (>= 13, 4) is routed to G = 0 by the plan
             return hipErrorInvalidValue;
 #endif
         case 2: return corr_launch_t<NP, 2>(p, pl, st);
