@@ -42,6 +42,7 @@ constexpr int kTW = 4 * kT * 16;  // output columns per tile
 constexpr int kMaxNQ = 13;        // MFMA steps per stage
 constexpr int kMaxWT = 5;         // window tasks per producer thread
 constexpr int kMaxWI = 7;         // weight entries per producer thread
+constexpr int kMaxRP = 7;         // raw 16-byte pieces per producer thread
 constexpr int kQS = 68;           // slots per (filter block, step): 4 k-blocks x 17
 constexpr unsigned kPermLo = 0x05040100u;  // {b.lo16, a.lo16} -> a.lo | b.lo << 16
 constexpr unsigned kPermHi = 0x07060302u;  // {b.hi16, a.hi16} -> a.hi | b.hi << 16
@@ -60,6 +61,11 @@ struct IgArgs {
     int LP, LPS;      // window positions staged (even), plane stride in slots
     int delta;        // (o0 - P) - window origin: 0 or 1
     int stage_slots;  // NG * LPS + kFB * NQ * kQS
+    int fwd_mode;     // weights are [m][r][s] (forward) or [r][m][S-1-s] (backward-data)
+    int NU, NPc;      // raw runs per stage, 16-byte pieces per run
+    long su;          // elements between the starts of consecutive runs
+    long wbytes;      // size of the weight tensor
+    int raw_slots;    // NU * NPc
 };
 
 __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
@@ -113,6 +119,7 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
             for (int t = 0; t < kT; ++t) acc[fb][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
         int tile = t_begin, cc = 0;
+        __syncthreads();  // raw weights of stage 0 are in LDS
         __syncthreads();  // stage 0 is in LDS
         for (int st = 0; st < nstages; ++st) {
             const unsigned sb = static_cast<unsigned>((st & 1) * a.stage_slots) * 16u;
@@ -167,14 +174,18 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
         // ---- producer side -----------------------------------------------------------------------
         // Window task (plane g, pair i): positions G0 + 2i, G0 + 2i + 1 of the 8 channels of plane g; 8 dword
         // loads (row starts, the window origin and Win are even) from clamped addresses, two slots out.
-        // Weight entry (m, g, s): 8 loads of one element, one slot out; consecutive threads take consecutive
-        // taps, which are adjacent in memory for both passes.
+        //
+        // Weights travel in three steps, one stage apart each.  The weights of a stage are NU contiguous
+        // runs of the [K][C][S] tensor (forward: one run of 8 NG channels x S taps per filter; backward-data:
+        // one run of 32 channels-of-dx x S taps per channel-of-dy).  (1) The runs are fetched as 16-byte pieces
+        // from 4-byte aligned addresses into registers, (2) written as they are into a raw LDS area, and (3)
+        // the operand entries (8 channels of one tap per lane) are gathered from the raw area with 2-byte LDS
+        // reads.  Sub-dword global loads would cost one memory instruction per element instead.
         const int LP2 = a.LP >> 1;
         const int NWT = a.NG * LP2;
         const int NWI = kFB * 16 * a.NG * a.S;
-        int wt_plane8[kMaxWT], wt_pair[kMaxWT];   // 8 * plane, pair index within the plane
-        unsigned wi_off[kMaxWI];                  // element offset of (m, channel 8 g, tap s) from the filter group / chunk base
-        int wi_lds[kMaxWI], wi_g8[kMaxWI];        // slot within the weights area, 8 * g
+        const int NRP = a.NU * a.NPc;
+        int wt_plane8[kMaxWT], wt_pair[kMaxWT];  // 8 * plane, pair index within the plane
 #pragma unroll
         for (int k = 0; k < kMaxWT; ++k) {
             const int e = min(rtid + k * 256, NWT - 1);
@@ -182,20 +193,34 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
             wt_plane8[k] = 8 * g;
             wt_pair[k] = e - g * LP2;
         }
+        int rp_u[kMaxRP], rp_q[kMaxRP];  // run and piece of a raw-copy task
+#pragma unroll
+        for (int k = 0; k < kMaxRP; ++k) {
+            const int e = min(rtid + k * 256, NRP - 1);
+            rp_u[k] = e / a.NPc;
+            rp_q[k] = e - rp_u[k] * a.NPc;
+        }
+        // entry (m, g, s): raw halfword index of channel c8 = idx0 + c8 * cs + (parity of the run's start), slot
+        int wi_idx0[kMaxWI], wi_lds[kMaxWI], wi_g8[kMaxWI], wi_par[kMaxWI];
 #pragma unroll
         for (int k = 0; k < kMaxWI; ++k) {
             const int e = min(rtid + k * 256, NWI - 1);
-            const int s = e % a.S, mg = e / a.S;
+            const int sx = e % a.S, mg = e / a.S;
             const int g = mg % a.NG, ml = mg / a.NG;
-            const int i = g * a.S + s;
-            wi_off[k] = static_cast<unsigned>(ml * a.w_sm + 8 * g * a.w_sr + a.w_s0 + s * a.w_ss);
+            const int i = g * a.S + sx;
+            const int RSH = a.NPc * 8;  // halfwords per raw run
+            if (a.fwd_mode) {
+                wi_idx0[k] = ml * RSH + 8 * g * a.S + sx;
+                const int pm = static_cast<int>((ml * a.w_sm) & 1);
+                wi_par[k] = pm | (pm << 1);
+            } else {
+                wi_idx0[k] = 8 * g * RSH + ml * a.S + (a.S - 1 - sx);
+                wi_par[k] = static_cast<int>(a.w_sr & 1) << 1;  // runs of odd channels start at the other parity
+            }
             wi_lds[k] = ((ml >> 4) * a.NQ + (i >> 2)) * kQS + 17 * (i & 3) + (ml & 15);
             wi_g8[k] = 8 * g;
         }
-        struct Stage {
-            unsigned win[kMaxWT][8];
-            unsigned wgt[kMaxWI][8];
-        };
+        const int cs = a.fwd_mode ? a.S : a.NPc * 8;
         struct Geo {
             int n, G0, fg, r0;  // sample, window origin, filter group, first channel of the chunk
         };
@@ -209,7 +234,9 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
             g.r0 = cc * a.NG * 8;
             return g;
         };
-        auto prefetch = [&](Stage& sg, int st) {
+        unsigned wreg[kMaxWT][8];
+        u32x4 rreg[kMaxRP];
+        auto window_prefetch = [&](int st) {
             const Geo g = geo(st);
             const char* ib = reinterpret_cast<const char*>(a.in + static_cast<long>(g.n) * a.in_sn);
             const unsigned rowb = static_cast<unsigned>(a.Win) * 2u;
@@ -222,30 +249,14 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
                     unsigned off = static_cast<unsigned>((g.r0 + wt_plane8[k]) * a.Win + pos) * 2u;
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
-                        sg.win[k][j] = *reinterpret_cast<const unsigned*>(ib + min(off, offmax));
+                        wreg[k][j] = *reinterpret_cast<const unsigned*>(ib + min(off, offmax));
                         off += rowb;
                     }
                 }
-            // (m beyond M re-reads filter M - 1 and channels beyond R channel R - 1; both are zeroed when written)
-            const int m0 = g.fg * kFB * 16;
-#pragma unroll
-            for (int k = 0; k < kMaxWI; ++k)
-                if (k * 256 < NWI) {
-                    const int e = min(rtid + k * 256, NWI - 1);
-                    const int ml = e / (a.S * a.NG);
-                    const long mshift = (m0 + ml < a.M ? static_cast<long>(m0) : static_cast<long>(a.M - 1 - ml)) * a.w_sm;
-                    const unsigned short* wp = a.wt + mshift + wi_off[k];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const int r = min(g.r0 + wi_g8[k] + j, a.R - 1) - wi_g8[k];
-                        sg.wgt[k][j] = wp[static_cast<long>(r) * a.w_sr];
-                    }
-                }
         };
-        auto commit = [&](const Stage& sg, int st, int b) {
+        auto window_commit = [&](int st, int b) {
             const Geo g = geo(st);
             u32x4* win = lds4 + b * a.stage_slots;
-            u32x4* wgt = win + wbase;
 #pragma unroll
             for (int k = 0; k < kMaxWT; ++k)
                 if (rtid + k * 256 < NWT) {
@@ -254,7 +265,7 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
                     u32x4 ev, od;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        const unsigned lo = ok ? sg.win[k][2 * q] : 0u, hi = ok ? sg.win[k][2 * q + 1] : 0u;
+                        const unsigned lo = ok ? wreg[k][2 * q] : 0u, hi = ok ? wreg[k][2 * q + 1] : 0u;
                         ev[q] = __builtin_amdgcn_perm(hi, lo, kPermLo);
                         od[q] = __builtin_amdgcn_perm(hi, lo, kPermHi);
                     }
@@ -262,29 +273,103 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
                     dst[0] = ev;
                     dst[1] = od;
                 }
+        };
+        // element offset of the stage's first run from the tensor base (runs beyond the last filter / channel
+        // re-read the last one; their entries are zeroed in the gather)
+        auto stage_base = [&](const Geo& g) -> long {
+            return static_cast<long>(g.fg * kFB * 16) * a.w_sm + static_cast<long>(g.r0) * a.w_sr;
+        };
+        auto raw_prefetch = [&](int st) {
+            const Geo g = geo(st);
+            const unsigned eb = static_cast<unsigned>(stage_base(g));  // the tensor has fewer than 2^31 elements
+            const int umax = a.fwd_mode ? a.M - 1 - g.fg * kFB * 16 : a.R - 1 - g.r0;
+            const char* wb = reinterpret_cast<const char*>(a.wt);
+            const unsigned su = static_cast<unsigned>(a.su);
+            const unsigned wb4 = static_cast<unsigned>(a.wbytes) & ~3u;
+            // only the pieces of the last runs of the tensor can reach beyond its end (uniform test)
+            const unsigned reach = ((eb + static_cast<unsigned>(min(a.NU - 1, umax)) * su) * 2u & ~3u) + 16u * static_cast<unsigned>(a.NPc);
+            if (reach <= wb4) {
+#pragma unroll
+                for (int k = 0; k < kMaxRP; ++k)
+                    if (k * 256 < NRP) {
+                        const unsigned eu = eb + static_cast<unsigned>(min(rp_u[k], umax)) * su;
+                        rreg[k] = *reinterpret_cast<const u32x4*>(wb + (((eu * 2u) & ~3u) + 16u * static_cast<unsigned>(rp_q[k])));
+                    }
+            } else {
+                const unsigned last_dw = static_cast<unsigned>(a.wbytes - 2) & ~3u;  // the last dword that holds an element
+#pragma unroll
+                for (int k = 0; k < kMaxRP; ++k)
+                    if (k * 256 < NRP) {
+                        const unsigned eu = eb + static_cast<unsigned>(min(rp_u[k], umax)) * su;
+                        const unsigned B = ((eu * 2u) & ~3u) + 16u * static_cast<unsigned>(rp_q[k]);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) rreg[k][i] = *reinterpret_cast<const unsigned*>(wb + min(B + 4u * i, last_dw));
+                    }
+            }
+        };
+        auto raw_commit = [&](int rb) {
+            u32x4* raw = lds4 + 2 * a.stage_slots + rb * a.raw_slots;
+#pragma unroll
+            for (int k = 0; k < kMaxRP; ++k)
+                if (rtid + k * 256 < NRP) raw[rp_u[k] * a.NPc + rp_q[k]] = rreg[k];
+        };
+        auto gather = [&](int st, int b) {
+            const Geo g = geo(st);
+            const unsigned short* raw = reinterpret_cast<const unsigned short*>(lds4 + 2 * a.stage_slots + b * a.raw_slots);
+            u32x4* wgt = lds4 + b * a.stage_slots + wbase;
+            const int pb = static_cast<int>(stage_base(g) & 1);
             const int m0 = g.fg * kFB * 16;
+            // all reads first (one LDS round trip for the lot), then the packing
+            unsigned v[kMaxWI][8];
+#pragma unroll
+            for (int k = 0; k < kMaxWI; ++k)
+                if (k * 256 < NWI) {
+                    const int ie = wi_idx0[k] + (pb ^ (wi_par[k] & 1)), io = wi_idx0[k] + (pb ^ (wi_par[k] >> 1));
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) v[k][j] = raw[((j & 1) ? io : ie) + j * cs];
+                }
+            __builtin_amdgcn_sched_barrier(0);
+            // channels beyond R and filters beyond M are zero: an entry keeps its first nv channels
+            const bool full = (a.R % (8 * a.NG)) == 0 && (a.M % (kFB * 16)) == 0;
 #pragma unroll
             for (int k = 0; k < kMaxWI; ++k)
                 if (rtid + k * 256 < NWI) {
-                    const int ml = (rtid + k * 256) / (a.S * a.NG);
-                    const bool mok = m0 + ml < a.M;
-                    unsigned v[8];
+                    if (!full) {
+                        const int ml = (rtid + k * 256) / (a.S * a.NG);
+                        const int nv = m0 + ml < a.M ? a.R - g.r0 - wi_g8[k] : 0;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) v[j] = (mok && g.r0 + wi_g8[k] + j < a.R) ? sg.wgt[k][j] : 0u;
-                    wgt[wi_lds[k]] = u32x4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+                        for (int j = 0; j < 8; ++j) v[k][j] = j < nv ? v[k][j] : 0u;
+                    }
+                    wgt[wi_lds[k]] = u32x4{v[k][0] | (v[k][1] << 16), v[k][2] | (v[k][3] << 16), v[k][4] | (v[k][5] << 16), v[k][6] | (v[k][7] << 16)};
                 }
         };
-        Stage sg;
+        // iteration t: window t+1 -> LDS, window t+2 -> registers; entries t+1 <- raw[(t+1)&1],
+        // raw[t&1] <- registers (stage t+2), registers <- global (stage t+3)
         if (nstages > 0) {
-            prefetch(sg, 0);
-            commit(sg, 0, 0);
-            if (nstages > 1) prefetch(sg, 1);
+            raw_prefetch(0);
+            window_prefetch(0);
+            raw_commit(0);
+            if (nstages > 1) raw_prefetch(1);
+        }
+        __syncthreads();
+        if (nstages > 0) {
+            gather(0, 0);
+            window_commit(0, 0);
+            if (nstages > 1) {
+                raw_commit(1);
+                window_prefetch(1);
+            }
+            if (nstages > 2) raw_prefetch(2);
         }
         __syncthreads();
         for (int st = 0; st < nstages; ++st) {
             if (st + 1 < nstages) {
-                commit(sg, st + 1, (st + 1) & 1);
-                if (st + 2 < nstages) prefetch(sg, st + 2);
+                // registers are refilled as soon as they are free, so every load has a whole stage to arrive
+                window_commit(st + 1, (st + 1) & 1);
+                if (st + 2 < nstages) window_prefetch(st + 2);
+                if (st + 2 < nstages) raw_commit(st & 1);
+                if (st + 3 < nstages) raw_prefetch(st + 3);
+                gather(st + 1, (st + 1) & 1);
             }
             __syncthreads();
         }
@@ -306,6 +391,10 @@ IgPlan ig_plan(const CorrProblem& p) {
     if (p.S < 4 || p.S > 4 * kMaxNQ) return pl;
     // dword loads of position pairs: even row starts and an even window origin
     if ((p.Win & 1) || (p.in_sn & 1) || (reinterpret_cast<uintptr_t>(p.in) & 3) || p.Win < 2) return pl;
+    if (reinterpret_cast<uintptr_t>(p.wt) & 3) return pl;
+    const bool fwd_mode = p.w_ss == 1 && p.w_sr == p.S && p.w_s0 == 0;
+    const bool bwd_mode = p.w_ss == -1 && p.w_sm == p.S && p.w_s0 == p.S - 1;
+    if (!fwd_mode && !bwd_mode) return pl;
     if (static_cast<long>(p.R) * p.Win >= (1L << 30)) return pl;                                  // 32-bit byte offsets within a sample
     if (static_cast<long>(p.M) * p.R * p.S >= (1L << 31) || p.M * p.w_sm >= (1L << 31) || p.R * p.w_sr >= (1L << 31)) return pl;
     IgArgs& a = pl.a;
@@ -327,7 +416,11 @@ IgPlan ig_plan(const CorrProblem& p) {
         if (cdiv(static_cast<long>(kFB) * 16 * NG * p.S, 256) > kMaxWI) continue;
         const long LPS = LP + 8;  // the operand of a padded k-block never leaves the plane; a little slack anyway
         const long stage = NG * LPS + static_cast<long>(kFB) * NQ * kQS;
-        const size_t bytes = static_cast<size_t>(2 * stage) * 16;
+        const int NU = fwd_mode ? kFB * 16 : 8 * NG;
+        const long L = fwd_mode ? 8L * NG * p.S : static_cast<long>(kFB) * 16 * p.S;
+        const long NPc = (2 * L + 2 + 15) / 16;
+        if (cdiv(NU * NPc, 256) > kMaxRP) continue;
+        const size_t bytes = static_cast<size_t>(2 * stage + 2 * NU * NPc) * 16;
         if (bytes > static_cast<size_t>(kLdsBudget)) continue;
         a.NG = NG;
         a.NQ = NQ;
@@ -335,6 +428,12 @@ IgPlan ig_plan(const CorrProblem& p) {
         a.LP = static_cast<int>(LP);
         a.LPS = static_cast<int>(LPS);
         a.stage_slots = static_cast<int>(stage);
+        a.fwd_mode = fwd_mode;
+        a.NU = NU;
+        a.NPc = static_cast<int>(NPc);
+        a.raw_slots = static_cast<int>(NU * NPc);
+        a.su = fwd_mode ? p.w_sm : p.w_sr;
+        a.wbytes = (fwd_mode ? static_cast<long>(p.M) * p.w_sm : static_cast<long>(p.R) * p.w_sr) * 2;
         a.tiles_per_row = cdiv(p.Wout, kTW);
         a.nfg = cdiv(p.M, kFB * 16);
         const long ntiles = static_cast<long>(p.N) * a.tiles_per_row * a.nfg;
