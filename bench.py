@@ -45,6 +45,48 @@ def stored_traffic(workload, pass_name):
         return None
 
 
+def sweep_table(args, np, torch, binding, inputs) -> int:
+    """Median device time (HIP events), TFLOP/s and fraction of the dense MFMA peak per pass and sweep point."""
+    wls = list(inputs.sweep(args.sweep)) + ([inputs.WIDE_BF16] if args.sweep == "bf16" else [])
+    print(f"# {'workload':22s} " + " ".join(f"| {p:>10s}: kernel family, us, TFLOP/s, % of peak" for p in PASSES))
+    for wl in wls:
+        data = inputs.make_inputs(wl)
+        dev = {}
+        for k in ("x", "w", "dy"):
+            if wl.dtype == "bf16":
+                dev[k] = torch.from_numpy(data[k + "_bits"].view(np.int16)).cuda().view(torch.bfloat16)
+            else:
+                dev[k] = torch.from_numpy(data[k]).cuda()
+        code = 1 if wl.dtype == "bf16" else 0
+        y = torch.empty((wl.N, wl.K, wl.Q), dtype=torch.float32, device="cuda")
+        dx = torch.empty((wl.N, wl.C, wl.W), dtype=torch.float32, device="cuda")
+        dw = torch.empty((wl.K, wl.C, wl.S), dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(256, binding.conv1d_bwd_weight_workspace_bytes(*wl.geometry(), code)), dtype=torch.uint8,
+                         device="cuda")
+        launch = {
+            "fwd": lambda: binding.conv1d_fwd(dev["x"], dev["w"], wl.d, wl.P, out=y),
+            "bwd_data": lambda: binding.conv1d_bwd_data(dev["dy"], dev["w"], wl.W, wl.d, wl.P, out=dx),
+            "bwd_weight": lambda: binding.conv1d_bwd_weight(dev["x"], dev["dy"], wl.S, wl.d, wl.P, out=dw, workspace=ws),
+        }
+        cols = []
+        for i, p in enumerate(PASSES):
+            for _ in range(args.warmup):
+                launch[p]()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+            torch.cuda.synchronize()
+            for a, b in evs:
+                a.record()
+                launch[p]()
+                b.record()
+            torch.cuda.synchronize()
+            ms = sorted(a.elapsed_time(b) for a, b in evs)[len(evs) // 2]
+            tf = wl.flops / (ms * 1e-3) / 1e12
+            fam = binding.conv1d_kernel_name(i, *wl.geometry(), code).split("_")[0]
+            cols.append(f"| {fam:>7s} {ms * 1e3:8.1f} us {tf:7.1f} TF {100 * tf / PEAK[wl.dtype]:5.1f} %")
+        print(f"{wl.name:24s} " + " ".join(cols), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,6 +99,9 @@ def main() -> int:
                     help="only run a plain 256 MiB device-to-device copy 5 times (reference for HBM byte counters)")
     ap.add_argument("--passes", default=",".join(PASSES),
                     help="comma-separated subset of passes to run (profiling runs; the headline needs all three)")
+    ap.add_argument("--sweep", choices=["fp32", "bf16"],
+                    help="instead of the headline line: per-pass device times of the 25 filter-width x dilation "
+                         "points (C = K = 64) of that dtype, plus the wide configuration for bf16, one text line each")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -81,6 +126,8 @@ def main() -> int:
         return 0
     binding.load()
     binding.conv1d_set_variant(args.variant)
+    if args.sweep:
+        return sweep_table(args, np, torch, binding, inputs)
     wl = inputs.WORKLOADS[args.workload]
     data = inputs.make_inputs(wl)
     dev = {}

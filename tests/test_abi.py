@@ -97,10 +97,14 @@ def test_wide_layers_dispatch_to_blocked_mfma_kernels():
     from paper_2104_08002_amd import inputs
 
     binding.conv1d_set_variant(binding.VARIANT_AUTO)
-    for wl in (inputs.WIDE_BF16, inputs.sweep_point(51, 8, "fp32"), inputs.sweep_point(9, 1, "fp32")):
+    wls = [inputs.WIDE_BF16] + [inputs.sweep_point(S, d, dt) for S in inputs.SWEEP_S for d in inputs.SWEEP_D for dt in ("fp32", "bf16")]
+    for wl in wls:
         code = 1 if wl.dtype == "bf16" else 0
-        names = [binding.conv1d_kernel_name(i, *wl.geometry(), code) for i in range(2 if code else 3)]
-        assert all(n.startswith("igemm_") and "mfma" in n for n in names), names
+        names = [binding.conv1d_kernel_name(i, *wl.geometry(), code) for i in range(3)]
+        assert all(n.startswith("igemm_") and "mfma" in n for n in names), (wl.name, names)
+    # small channel counts at a dilation other than 8: bf16 backward-weight still runs on MFMA
+    for d in (1, 2, 3, 4, 16):
+        assert "mfma" in binding.conv1d_kernel_name(binding.PASS_BWD_WEIGHT, 4, 15, 15, 5000, 51, d, 25 * d, 1)
     # the workspace of the blocked family is that of one 16 x 16 block pair
     wl = inputs.sweep_point(51, 8, "fp32")
     g = wl.geometry()

@@ -86,6 +86,9 @@ SMALL = [
     ("c64_k64_d16",       1, 64, 64, 2500, 33, 16, 256),
     ("c48_k80",           2, 48, 80, 700,  5,  8,  16),
     ("c256_k256",         1, 256, 256, 600, 9, 4,  16),
+    ("c40_k24_odd_W",     2, 40, 24, 901,  7,  3,  9),     # odd width: no dword-aligned rows
+    ("c20_k20_S3",        2, 20, 20, 500,  3,  2,  2),     # fewer taps than one MFMA step of the many-channel kernel
+    ("c64_k64_odd_P",     2, 64, 64, 1536, 9,  2,  7),     # odd padding: window origin one column early
     ("halo_gt_width",     2, 15, 15, 300,  51, 8,  200),   # halo (S-1)d = 400 exceeds W
     ("long_halo_short_W", 4, 4,  4,  64,   33, 16, 256),
 ]
