@@ -236,32 +236,54 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
         };
         unsigned wreg[kMaxWT][8];
         u32x4 rreg[kMaxRP];
+        // A stage is "interior" when its whole window lies inside the rows and all its channels exist: the
+        // loads then go to scalar row bases + one per-thread constant and nothing is masked (the producer waves
+        // share their SIMDs' issue slots with the MFMA waves, so every instruction they do not execute counts).
+        auto interior = [&](const Geo& g) { return g.G0 >= 0 && g.G0 + a.LP <= a.Win && g.r0 + 8 * a.NG <= a.R; };
+        unsigned wt_voff[kMaxWT];  // byte offset of the task's pair from the first row of its chunk at the window origin
+        int wt_dst[kMaxWT];        // slot of the task's first output
+#pragma unroll
+        for (int k = 0; k < kMaxWT; ++k) {
+            wt_voff[k] = 2u * (static_cast<unsigned>(wt_plane8[k]) * static_cast<unsigned>(a.Win) + 2u * static_cast<unsigned>(wt_pair[k]));
+            wt_dst[k] = (wt_plane8[k] >> 3) * a.LPS + 2 * wt_pair[k];
+        }
         auto window_prefetch = [&](int st) {
             const Geo g = geo(st);
             const char* ib = reinterpret_cast<const char*>(a.in + static_cast<long>(g.n) * a.in_sn);
             const unsigned rowb = static_cast<unsigned>(a.Win) * 2u;
+            if (interior(g)) {
+                const char* rb = ib + 2 * (static_cast<long>(g.r0) * a.Win + g.G0);  // uniform
 #pragma unroll
-            for (int k = 0; k < kMaxWT; ++k)
-                if (k * 256 < NWT) {
-                    int pos = g.G0 + 2 * wt_pair[k];
-                    pos = pos < 0 ? 0 : (pos > a.Win - 2 ? a.Win - 2 : pos);
-                    const unsigned offmax = static_cast<unsigned>((a.R - 1) * a.Win + pos) * 2u;
-                    unsigned off = static_cast<unsigned>((g.r0 + wt_plane8[k]) * a.Win + pos) * 2u;
+                for (int k = 0; k < kMaxWT; ++k)
+                    if (k * 256 < NWT) {
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        wreg[k][j] = *reinterpret_cast<const unsigned*>(ib + min(off, offmax));
-                        off += rowb;
+                        for (int j = 0; j < 8; ++j) wreg[k][j] = *reinterpret_cast<const unsigned*>(rb + j * static_cast<long>(rowb) + wt_voff[k]);
                     }
-                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < kMaxWT; ++k)
+                    if (k * 256 < NWT) {
+                        int pos = g.G0 + 2 * wt_pair[k];
+                        pos = pos < 0 ? 0 : (pos > a.Win - 2 ? a.Win - 2 : pos);
+                        const unsigned offmax = static_cast<unsigned>((a.R - 1) * a.Win + pos) * 2u;
+                        unsigned off = static_cast<unsigned>((g.r0 + wt_plane8[k]) * a.Win + pos) * 2u;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            wreg[k][j] = *reinterpret_cast<const unsigned*>(ib + min(off, offmax));
+                            off += rowb;
+                        }
+                    }
+            }
         };
         auto window_commit = [&](int st, int b) {
             const Geo g = geo(st);
             u32x4* win = lds4 + b * a.stage_slots;
+            const bool inner = interior(g);
 #pragma unroll
             for (int k = 0; k < kMaxWT; ++k)
                 if (rtid + k * 256 < NWT) {
                     const int pos = g.G0 + 2 * wt_pair[k];
-                    const bool ok = pos >= 0 && pos < a.Win;  // a pair is inside or outside the row as a whole
+                    const bool ok = inner || (pos >= 0 && pos < a.Win);  // a pair is inside or outside the row as a whole
                     u32x4 ev, od;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
@@ -269,7 +291,7 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
                         ev[q] = __builtin_amdgcn_perm(hi, lo, kPermLo);
                         od[q] = __builtin_amdgcn_perm(hi, lo, kPermHi);
                     }
-                    u32x4* dst = win + (wt_plane8[k] >> 3) * a.LPS + 2 * wt_pair[k];
+                    u32x4* dst = win + wt_dst[k];
                     dst[0] = ev;
                     dst[1] = od;
                 }
