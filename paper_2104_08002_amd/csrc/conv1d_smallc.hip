@@ -580,19 +580,23 @@ __global__ __launch_bounds__(256) void smallc_wgrad_reduce_kernel(const float* _
 }
 
 struct WgradF32Plan {
-    int QC, LQS, LXS, LX4, chunks_per_row, nchunks, grid, fast;
+    int QC, LQS, LXS, LX4, chunks_per_row, nchunks, grid, fast, NT;
     size_t lds_bytes;
     bool ok;
 };
 
-constexpr int kWgradNT = 13, kWgradMaxS = 15;
+constexpr int kWgradNT = 13, kWgradMaxS = 15;  // most taps per wave; staging slots per producer thread held in registers
+constexpr int kWgradNTs[] = {2, 3, 5, 9, 13};    // instantiated taps per wave: 4 * NT tap slots are multiplied whatever S is
 
 WgradF32Plan wgrad_f32_plan(const WgradProblem& p) {
     WgradF32Plan pl{};
     pl.ok = false;
     if (p.bf16 || p.C > 16 || p.K > 16 || p.S > 4 * kWgradNT) return pl;
     if (static_cast<long>(p.C) * p.W >= (1L << 30) || static_cast<long>(p.K) * p.Q >= (1L << 30)) return pl;
-    const long halo = static_cast<long>(4 * kWgradNT - 1) * p.d;  // every tap slot a wave may read
+    pl.NT = kWgradNT;
+    for (int i = 4; i >= 0; --i)
+        if (4 * kWgradNTs[i] >= p.S) pl.NT = kWgradNTs[i];
+    const long halo = static_cast<long>(4 * pl.NT - 1) * p.d;  // every tap slot a wave may read
     // row stride == 2 (mod 32) words: the 32 lanes (16 rows x 2 adjacent columns) that the LDS serves together
     // fall on 32 distinct banks (a stride of 4 would pair row r with row r+8)
     auto pad = [](long v) { return (v + 31) / 32 * 32 + 2; };
@@ -616,6 +620,17 @@ WgradF32Plan wgrad_f32_plan(const WgradProblem& p) {
         return pl;
     }
     return pl;
+}
+
+template <int NT>
+hipError_t wgrad_f32_launch_nt(const WgradProblem& p, const WgradF32Plan& pl, hipStream_t st) {
+    auto kern = pl.fast ? smallc_wgrad_f32_kernel<NT, kWgradMaxS, true> : smallc_wgrad_f32_kernel<NT, kWgradMaxS, false>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       static_cast<int>(pl.lds_bytes));
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(pl.grid), dim3(512), pl.lds_bytes, st, p, pl.chunks_per_row, pl.nchunks, pl.QC, pl.LQS, pl.LXS,
+                       pl.LX4);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -659,13 +674,14 @@ hipError_t smallc_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     if (p.bf16) return smallc_bf16_wgrad_launch(p, st);
     const WgradF32Plan pl = wgrad_f32_plan(p);
     if (!pl.ok) return hipErrorInvalidValue;
-    auto kern = pl.fast ? smallc_wgrad_f32_kernel<kWgradNT, kWgradMaxS, true> : smallc_wgrad_f32_kernel<kWgradNT, kWgradMaxS, false>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(pl.lds_bytes));
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(pl.grid), dim3(512), pl.lds_bytes, st, p, pl.chunks_per_row, pl.nchunks, pl.QC, pl.LQS, pl.LXS,
-                       pl.LX4);
-    e = hipGetLastError();
+    hipError_t e;
+    switch (pl.NT) {
+        case 2: e = wgrad_f32_launch_nt<2>(p, pl, st); break;
+        case 3: e = wgrad_f32_launch_nt<3>(p, pl, st); break;
+        case 5: e = wgrad_f32_launch_nt<5>(p, pl, st); break;
+        case 9: e = wgrad_f32_launch_nt<9>(p, pl, st); break;
+        default: e = wgrad_f32_launch_nt<kWgradNT>(p, pl, st); break;
+    }
     if (e != hipSuccess) return e;
     return smallc_wgrad_reduce_launch(static_cast<const float*>(p.ws), p.dw, p.K, p.C, p.S, p.dw_sk, p.dw_sc, pl.grid, st);
 }
