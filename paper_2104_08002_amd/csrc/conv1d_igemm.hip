@@ -4,8 +4,10 @@
 // (tap, block pair).  The same blocking is applied here one level up: C and K are cut into blocks of 16, the
 // width of the MFMA tile the small-channel kernels are built around, and every (filter block, channel block)
 // pair is one launch of those kernels on a strided view of the tensors.
-//   fwd / bwd_data  out[:, mb, :] (+)= corr(in[:, rb, :], wt[mb, rb, :])   the first channel block overwrites,
-//                                                                         the following ones accumulate
+//   fwd / bwd_data  out[:, mb, :] = sum over rb of corr(in[:, rb, :], wt[mb, rb, :])   one launch per filter block
+//                   when the kernel can hold the weights of all channel blocks (it then reduces over them in
+//                   its accumulators), else one launch per pair: the first channel block overwrites the output,
+//                   the following ones accumulate
 //   bwd_weight      dw[kb, cb, :]  = wgrad(x[:, cb, :], dy[:, kb, :])      each pair owns its block of dw
 // All launches go to the caller's stream in a fixed order, so results are deterministic and the one
 // workspace is reused by every pair.
@@ -55,6 +57,15 @@ hipError_t igemm_corr_launch(const CorrProblem& p, hipStream_t st) {
     if (!igemm_corr_supported(p)) return hipErrorInvalidValue;
     if (p.bf16 && igemm_bf16_corr_supported(p)) return igemm_bf16_corr_launch(p, st);
     for (int m0 = 0; m0 < p.M; m0 += kBlock) {
+        // all channel blocks in one launch when the kernel can keep their weights in LDS ...
+        CorrProblem rows = corr_block(p, m0, 0);
+        rows.R = p.R;
+        if (smallc_corr_supported(rows)) {
+            const hipError_t e = smallc_corr_launch(rows, st);
+            if (e != hipSuccess) return e;
+            continue;
+        }
+        // ... else one launch per channel block, accumulating into the output
         for (int r0 = 0; r0 < p.R; r0 += kBlock) {
             const CorrProblem b = corr_block(p, m0, r0);
             const hipError_t e = smallc_corr_launch(b, st);

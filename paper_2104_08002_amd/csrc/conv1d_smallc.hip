@@ -33,18 +33,20 @@ constexpr int kNumCU = 256;
 //   win[b][4*RC][LPS]    input window b, row r, column i <-> input position G0 + i   (NBUF = 1 or 2 buffers)
 // Waves 0-3 ("consumers") own T adjacent 16-column output tiles each and walk the (tap, channel-chunk)
 // reduction with v_mfma_f32_16x16x4_f32, the LDS reads of tap s+1 interleaved with the MFMAs of tap s;
-// they store their outputs themselves.  Waves 4-7 ("producers") fetch the window of tile t+2 from global
+// they store their outputs themselves.  With more than 16 channels (ncb > 1 channel blocks of 16) a tile is
+// reduced in ncb stages, one window per channel block, with the sums kept in the accumulators in between;
+// wfrag then holds the weights of all blocks.  Waves 4-7 ("producers") fetch the window of tile t+2 from global
 // memory into registers and write the window of tile t+1 into the free buffer; one workgroup barrier per
 // tile hands the buffers over.  When two windows do not fit in LDS (long halos) the same kernel runs with one
 // buffer and a second barrier per tile.
 template <int RC, int T, int MAXS, bool FAST>
 __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, int tiles_per_row, int ntiles, int LPS, int LP4,
-                                                                 int nbuf, int raw_in_lds) {
+                                                                 int nbuf, int raw_in_lds, int ncb) {
     extern __shared__ float lds[];
     constexpr int TQ = 4 * T * 16;
-    const int nsteps = p.S * RC;
+    const int nsteps = p.S * RC;  // MFMA steps per channel block
     float* wfrag = lds;
-    auto win = [&](int b) { return lds + nsteps * 64 + b * 4 * RC * LPS; };
+    auto win = [&](int b) { return lds + ncb * nsteps * 64 + b * 4 * RC * LPS; };
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -59,10 +61,13 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
 
     int lid = blockIdx.x;
     if ((gridDim.x & 7) == 0) lid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    const int t_begin = static_cast<int>(static_cast<long>(lid) * ntiles / gridDim.x);
-    const int t_end = static_cast<int>(static_cast<long>(lid + 1) * ntiles / gridDim.x);
-    auto tile_n = [&](int t) { return t / tiles_per_row; };
-    auto tile_O0 = [&](int t) { return (t - (t / tiles_per_row) * tiles_per_row) * TQ; };
+    const int t_begin = static_cast<int>(static_cast<long>(lid) * ntiles / gridDim.x) * ncb;      // first stage of the strip
+    const int t_end = static_cast<int>(static_cast<long>(lid + 1) * ntiles / gridDim.x) * ncb;  // one past its last stage
+    // stage u = tile * ncb + channel block (all of the strip's stages in one sequence)
+    auto stage_tile = [&](int u) { return ncb == 1 ? u : u / ncb; };
+    auto tile_n = [&](int u) { return stage_tile(u) / tiles_per_row; };
+    auto tile_O0 = [&](int u) { const int t = stage_tile(u); return (t - (t / tiles_per_row) * tiles_per_row) * TQ; };
+    auto stage_cb = [&](int u) { return ncb == 1 ? 0 : u - (u / ncb) * ncb; };
 
     // ---- producer side ------------------------------------------------------------------------------
     // Staging slot e = 4 adjacent positions of row e / LP4; slot k of a producer thread is e = rtid + 256*k
@@ -77,7 +82,9 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
         return Slot{static_cast<unsigned>(min(r, p.R - 1) * p.Win), 4 * i, (r * LPS + 4 * i) | (r < p.R ? 0 : kRowBad)};
     };
     auto fetch = [&](int t, const Slot& w) -> f32x4 {
-        const float* row = in + static_cast<long>(tile_n(t)) * p.in_sn + w.off;
+        // (rows beyond R re-read row R - 1; they are zeroed when written to LDS)
+        const unsigned rowoff = min(w.off + static_cast<unsigned>(stage_cb(t) * 16 * p.Win), static_cast<unsigned>((p.R - 1) * p.Win));
+        const float* row = in + static_cast<long>(tile_n(t)) * p.in_sn + rowoff;
         const int g = tile_O0(t) - p.P + w.col;
         if constexpr (FAST) {
             const int lim = p.Win - 4;  // >= 0 on this path (checked by the host)
@@ -95,7 +102,8 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
     };
     auto commit = [&](float* wb, int t, const Slot& w, f32x4 v) {
         const int g = tile_O0(t) - p.P + w.col;
-        const bool ok = !(w.lds & kRowBad) && (!FAST || (g >= 0 && g + 4 <= p.Win));
+        const bool row_ok = ncb == 1 ? !(w.lds & kRowBad) : w.off + static_cast<unsigned>(stage_cb(t) * 16 * p.Win) < static_cast<unsigned>(p.R * p.Win);
+        const bool ok = row_ok && (!FAST || (g >= 0 && g + 4 <= p.Win));
         if (!ok) v = f32x4{0.f, 0.f, 0.f, 0.f};
         *reinterpret_cast<f32x4*>(wb + (w.lds & (kRowBad - 1))) = v;
     };
@@ -155,9 +163,9 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
         } else if (!consumer && t_begin < t_end) {
             prefetch_tile(t_begin);
         }
-        for (int e = tid; e < nsteps * 64; e += 512) {
-            const int step = e >> 6, l = e & 63;
-            const int m = l & 15, r = 4 * (step % RC) + (l >> 4), s = step / RC;
+        for (int e = tid; e < ncb * nsteps * 64; e += 512) {
+            const int cb = (e >> 6) / nsteps, step = (e >> 6) - cb * nsteps, l = e & 63;
+            const int m = l & 15, r = 16 * cb + 4 * (step % RC) + (l >> 4), s = step / RC;
             float v = 0.f;
             if (m < p.M && r < p.R) {
                 const long idx = m * p.w_sm + r * p.w_sr + p.w_s0 + s * p.w_ss;
@@ -174,17 +182,20 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
     __syncthreads();
 
     // ---- consumer side --------------------------------------------------------------------------------
+    f32x4 acc[T];  // lives across the channel blocks of a tile
     auto compute = [&](const float* wb, int t) {
-        f32x4 acc[T];
+        const int cb = stage_cb(t);
+        if (cb == 0) {
 #pragma unroll
-        for (int j = 0; j < T; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int j = 0; j < T; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
         const int ob = cw * T * 16;
         // running LDS indices (into lds[]), one per channel chunk, bumped by d per tap: the operand reads then
         // carry immediate offsets only instead of an address add in front of each of them
         int wi[RC];
 #pragma unroll
         for (int cc = 0; cc < RC; ++cc) wi[cc] = static_cast<int>(wb - lds) + (4 * cc + kb) * LPS + ob + li;
-        int ai = lane;
+        int ai = lane + cb * nsteps * 64;
         float a0[RC], b0[RC][T], a1[RC], b1[RC][T];
         auto load_tap = [&](float (&a)[RC], float (&b)[RC][T]) {  // loads the tap the indices point at
 #pragma unroll
@@ -239,6 +250,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
             keep(b1);
         }
         if (s < p.S) mfma_tap(a0, b0);  // odd S: the last tap is already loaded
+        if (cb + 1 < ncb) return;       // more channel blocks to come
         const int n = tile_n(t), O0 = tile_O0(t);
 #pragma unroll
         for (int j = 0; j < T; ++j) {
@@ -278,7 +290,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
 }
 
 struct CorrF32Plan {
-    int RC, LPS, LP4, tiles_per_row, ntiles, fast, raw_in_lds, nbuf;
+    int RC, LPS, LP4, tiles_per_row, ntiles, fast, raw_in_lds, nbuf, ncb;
     size_t lds_bytes;
     bool ok;
 };
@@ -288,15 +300,18 @@ constexpr int kCorrT = 4, kCorrMaxS = 11;
 CorrF32Plan corr_f32_plan(const CorrProblem& p) {
     CorrF32Plan pl{};
     pl.ok = false;
-    if (p.bf16 || p.R > 16 || p.M > 16) return pl;
+    if (p.bf16 || p.M > 16) return pl;
     if (static_cast<long>(p.R) * p.Win >= (1L << 30)) return pl;  // 32-bit element offsets within one sample
     constexpr int TQ = 4 * kCorrT * 16;
-    pl.RC = (p.R + 3) / 4;
+    // more than 16 channels: blocks of 16, reduced one after the other inside the kernel
+    pl.ncb = cdiv(p.R, 16);
+    if (pl.ncb > 1 && p.accumulate) return pl;
+    pl.RC = pl.ncb > 1 ? 4 : (p.R + 3) / 4;
     const long halo = static_cast<long>(p.S - 1) * p.d;
     const long LP = TQ + halo;
     // row stride == 16 (mod 32) words: the four k rows of a B fragment fall on disjoint bank halves
     const long LPS = (LP + 31) / 32 * 32 + 16;
-    const long wbytes = static_cast<long>(p.S) * pl.RC * 64 * 4;
+    const long wbytes = static_cast<long>(pl.ncb) * p.S * pl.RC * 64 * 4;
     const long win_bytes = 4L * pl.RC * LPS * 4;
     pl.nbuf = wbytes + 2 * win_bytes <= kLdsBudget ? 2 : 1;
     const long bytes = wbytes + pl.nbuf * win_bytes;
@@ -323,7 +338,7 @@ hipError_t corr_f32_launch_f(const CorrProblem& p, const CorrF32Plan& pl, hipStr
     if (e != hipSuccess) return e;
     const int grid = pl.ntiles < kNumCU ? pl.ntiles : kNumCU;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(512), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.LP4, pl.nbuf,
-                       pl.raw_in_lds);
+                       pl.raw_in_lds, pl.ncb);
     return hipGetLastError();
 }
 
