@@ -41,7 +41,7 @@ constexpr int kNumCU = 256;
 // buffer and a second barrier per tile.
 template <int RC, int T, int MAXS, bool FAST>
 __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, int tiles_per_row, int ntiles, int LPS, int LP4,
-                                                                 int nbuf, int raw_in_lds, int ncb) {
+                                                                 int nbuf, int raw_in_lds, int ncb, int vec_out) {
     extern __shared__ float lds[];
     constexpr int TQ = 4 * T * 16;
     const int nsteps = p.S * RC;  // MFMA steps per channel block
@@ -68,6 +68,16 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
     auto tile_n = [&](int u) { return stage_tile(u) / tiles_per_row; };
     auto tile_O0 = [&](int u) { const int t = stage_tile(u); return (t - (t / tiles_per_row) * tiles_per_row) * TQ; };
     auto stage_cb = [&](int u) { return ncb == 1 ? 0 : u - (u / ncb) * ncb; };
+    // everything a staging slot needs to know about its stage, worked out once per stage (the divisions above
+    // are not something to repeat for every slot)
+    struct Geo {
+        long nbase;        // element offset of the stage's sample
+        int gorg;          // input position of window column 0
+        unsigned rowbase;  // element offset of the stage's first channel row within the sample
+    };
+    auto geo = [&](int u) -> Geo {
+        return Geo{static_cast<long>(tile_n(u)) * p.in_sn, tile_O0(u) - p.P, static_cast<unsigned>(stage_cb(u) * 16 * p.Win)};
+    };
 
     // ---- producer side ------------------------------------------------------------------------------
     // Staging slot e = 4 adjacent positions of row e / LP4; slot k of a producer thread is e = rtid + 256*k
@@ -81,11 +91,11 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
         const int r = e / LP4, i = e - r * LP4;
         return Slot{static_cast<unsigned>(min(r, p.R - 1) * p.Win), 4 * i, (r * LPS + 4 * i) | (r < p.R ? 0 : kRowBad)};
     };
-    auto fetch = [&](int t, const Slot& w) -> f32x4 {
+    auto fetch = [&](const Geo& t, const Slot& w) -> f32x4 {
         // (rows beyond R re-read row R - 1; they are zeroed when written to LDS)
-        const unsigned rowoff = min(w.off + static_cast<unsigned>(stage_cb(t) * 16 * p.Win), static_cast<unsigned>((p.R - 1) * p.Win));
-        const float* row = in + static_cast<long>(tile_n(t)) * p.in_sn + rowoff;
-        const int g = tile_O0(t) - p.P + w.col;
+        const unsigned rowoff = min(w.off + t.rowbase, static_cast<unsigned>((p.R - 1) * p.Win));
+        const float* row = in + t.nbase + rowoff;
+        const int g = t.gorg + w.col;
         if constexpr (FAST) {
             const int lim = p.Win - 4;  // >= 0 on this path (checked by the host)
             return *reinterpret_cast<const f32x4*>(row + (g < 0 ? 0 : (g > lim ? lim : g)));
@@ -100,22 +110,27 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
             return v;
         }
     };
-    auto commit = [&](float* wb, int t, const Slot& w, f32x4 v) {
-        const int g = tile_O0(t) - p.P + w.col;
-        const bool row_ok = ncb == 1 ? !(w.lds & kRowBad) : w.off + static_cast<unsigned>(stage_cb(t) * 16 * p.Win) < static_cast<unsigned>(p.R * p.Win);
+    auto commit = [&](float* wb, const Geo& t, const Slot& w, f32x4 v) {
+        const int g = t.gorg + w.col;
+        const bool row_ok = ncb == 1 ? !(w.lds & kRowBad) : w.off + t.rowbase < static_cast<unsigned>(p.R * p.Win);
         const bool ok = row_ok && (!FAST || (g >= 0 && g + 4 <= p.Win));
         if (!ok) v = f32x4{0.f, 0.f, 0.f, 0.f};
         *reinterpret_cast<f32x4*>(wb + (w.lds & (kRowBad - 1))) = v;
     };
     Slot slot[MAXS];
-    f32x4 pre[FAST ? MAXS : 1];
-    auto prefetch_tile = [&](int t) {
+    // two stages in flight: stage u travels in register set u & 1, fetched two stages before it is written to LDS
+    // (a stage of a narrow filter is shorter than the memory latency)
+    f32x4 preA[FAST ? MAXS : 1], preB[FAST ? MAXS : 1];
+    auto prefetch_set = [&](f32x4 (&pre)[FAST ? MAXS : 1], int u) {
         if constexpr (FAST) {
+            const Geo t = geo(u);
 #pragma unroll
-            for (int k = 0; k < MAXS; ++k) pre[k] = fetch(t, slot[k]);
+            for (int k = 0; k < MAXS; ++k)
+                if (k * 256 < nslots) pre[k] = fetch(t, slot[k]);
         }
     };
-    auto commit_tile = [&](float* wb, int t) {
+    auto commit_set = [&](const f32x4 (&pre)[FAST ? MAXS : 1], float* wb, int u) {
+        const Geo t = geo(u);
 #pragma unroll
         for (int k = 0; k < MAXS; ++k) {
             if (rtid + k * 256 < nslots) {
@@ -126,6 +141,9 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
                 }
             }
         }
+    };
+    auto commit_rest = [&](float* wb, int u) {
+        const Geo t = geo(u);
         for (int e = rtid + MAXS * 256; e < nslots; e += 256) {  // long halos: beyond the register budget
             const Slot w = make_slot(e);
             commit(wb, t, w, fetch(t, w));
@@ -148,7 +166,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
                 f32x4 tmp[NV];
 #pragma unroll
                 for (int k = 0; k < NV; ++k) tmp[k] = reinterpret_cast<const f32x4*>(wt)[min(tid + k * 512, nvec > 0 ? nvec - 1 : 0)];
-                if (!consumer && t_begin < t_end) prefetch_tile(t_begin);  // queued behind the weight loads
+                if (!consumer && t_begin < t_end) prefetch_set(preA, t_begin);  // queued behind the weight loads
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int k = 0; k < NV; ++k)
@@ -157,11 +175,11 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
                 for (int e = nvec * 4 + tid; e < nW; e += 512) raw[e] = wt[e];
             } else {
                 for (int e = tid; e < nW; e += 512) raw[e] = wt[e];
-                if (!consumer && t_begin < t_end) prefetch_tile(t_begin);
+                if (!consumer && t_begin < t_end) prefetch_set(preA, t_begin);
             }
             __syncthreads();
         } else if (!consumer && t_begin < t_end) {
-            prefetch_tile(t_begin);
+            prefetch_set(preA, t_begin);
         }
         for (int e = tid; e < ncb * nsteps * 64; e += 512) {
             const int cb = (e >> 6) / nsteps, step = (e >> 6) - cb * nsteps, l = e & 63;
@@ -176,8 +194,10 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
         __syncthreads();  // raw copy is dead, wfrag is complete
     }
     if (!consumer && t_begin < t_end) {
-        commit_tile(win(0), t_begin);
-        if (t_begin + 1 < t_end) prefetch_tile(t_begin + 1);
+        if (t_begin + 1 < t_end) prefetch_set(preB, t_begin + 1);
+        commit_set(preA, win(0), t_begin);
+        commit_rest(win(0), t_begin);
+        if (t_begin + 2 < t_end) prefetch_set(preA, t_begin + 2);
     }
     __syncthreads();
 
@@ -214,7 +234,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
 #pragma unroll
             for (int cc = 0; cc < RC; ++cc)
 #pragma unroll
-                for (int j = 0; j < T; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[cc], b[cc][j], acc[j], 0, 0, 0);
+                for (int j = 0; j < T; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(b[cc][j], a[cc], acc[j], 0, 0, 0);
         };
         // the LDS reads of the next tap are spread between the MFMAs of the current one
         auto interleave = [&]() {
@@ -251,18 +271,22 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
         }
         if (s < p.S) mfma_tap(a0, b0);  // odd S: the last tap is already loaded
         if (cb + 1 < ncb) return;       // more channel blocks to come
+        // The input fragment is the A operand and the weight fragment the B operand, so the accumulator tile is
+        // [position][filter]: lane (li, kb) holds filter li at the 4 adjacent columns 4 kb .. 4 kb + 3 of each
+        // 16-column block, one 16-byte store per block when the row starts allow it.
         const int n = tile_n(t), O0 = tile_O0(t);
+        if (li < p.M) {
+            float* row = p.out + static_cast<long>(n) * p.out_sn + static_cast<long>(li) * p.Wout;
 #pragma unroll
-        for (int j = 0; j < T; ++j) {
-            const int o = O0 + ob + j * 16 + li;
-            if (o < p.Wout) {
+            for (int j = 0; j < T; ++j) {
+                const int o = O0 + ob + j * 16 + 4 * kb;
+                if (vec_out && o + 4 <= p.Wout) {
+                    f32x4* dst = reinterpret_cast<f32x4*>(row + o);
+                    *dst = p.accumulate ? *dst + acc[j] : acc[j];
+                } else {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int m = 4 * kb + i;
-                    if (m < p.M) {
-                        float* dst = p.out + static_cast<long>(n) * p.out_sn + static_cast<long>(m) * p.Wout + o;
-                        *dst = p.accumulate ? *dst + acc[j][i] : acc[j][i];
-                    }
+                    for (int i = 0; i < 4; ++i)
+                        if (o + i < p.Wout) row[o + i] = p.accumulate ? row[o + i] + acc[j][i] : acc[j][i];
                 }
             }
         }
@@ -275,14 +299,26 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
         if (consumer) {
             compute(win(b), t);
         } else if (nbuf == 2 && t + 1 < t_end) {
-            commit_tile(win(b ^ 1), t + 1);
-            if (t + 2 < t_end) prefetch_tile(t + 2);
+            if ((k + 1) & 1) {
+                commit_set(preB, win(b ^ 1), t + 1);
+                if (t + 3 < t_end) prefetch_set(preB, t + 3);
+            } else {
+                commit_set(preA, win(b ^ 1), t + 1);
+                if (t + 3 < t_end) prefetch_set(preA, t + 3);
+            }
+            commit_rest(win(b ^ 1), t + 1);
         }
         __syncthreads();
         if (nbuf == 1 && t + 1 < t_end) {  // single buffer: refill it while the consumers wait
             if (!consumer) {
-                commit_tile(win(0), t + 1);
-                if (t + 2 < t_end) prefetch_tile(t + 2);
+                if ((k + 1) & 1) {
+                    commit_set(preB, win(0), t + 1);
+                    if (t + 3 < t_end) prefetch_set(preB, t + 3);
+                } else {
+                    commit_set(preA, win(0), t + 1);
+                    if (t + 3 < t_end) prefetch_set(preA, t + 3);
+                }
+                commit_rest(win(0), t + 1);
             }
             __syncthreads();
         }
@@ -290,7 +326,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
 }
 
 struct CorrF32Plan {
-    int RC, LPS, LP4, tiles_per_row, ntiles, fast, raw_in_lds, nbuf, ncb;
+    int RC, LPS, LP4, tiles_per_row, ntiles, fast, raw_in_lds, nbuf, ncb, vec_out;
     size_t lds_bytes;
     bool ok;
 };
@@ -325,6 +361,7 @@ CorrF32Plan corr_f32_plan(const CorrProblem& p) {
     pl.lds_bytes = static_cast<size_t>(bytes);
     // 16-byte window loads need every row start, the window origin and the base pointer aligned
     pl.fast = (p.Win % 4 == 0) && (((p.P % 4) + 4) % 4 == 0) && (reinterpret_cast<uintptr_t>(p.in) % 16 == 0) && p.Win >= 4;
+    pl.vec_out = (p.Wout % 4 == 0) && (p.out_sn % 4 == 0) && (reinterpret_cast<uintptr_t>(p.out) % 16 == 0);
     pl.raw_in_lds = p.w_contig && static_cast<long>(p.M) * p.R * p.S * 4 <= pl.nbuf * win_bytes;
     pl.ok = true;
     return pl;
@@ -338,7 +375,7 @@ hipError_t corr_f32_launch_f(const CorrProblem& p, const CorrF32Plan& pl, hipStr
     if (e != hipSuccess) return e;
     const int grid = pl.ntiles < kNumCU ? pl.ntiles : kNumCU;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(512), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.LP4, pl.nbuf,
-                       pl.raw_in_lds, pl.ncb);
+                       pl.raw_in_lds, pl.ncb, pl.vec_out);
     return hipGetLastError();
 }
 
