@@ -58,6 +58,9 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
     const float* __restrict__ in = static_cast<const float*>(p.in);
     const float* __restrict__ wt = static_cast<const float*>(p.wt);
     const int nslots = 4 * RC * LP4;
+    // window column 0 is the input position (tile start - P) rounded down to a multiple of 4, so that 16-byte
+    // staging loads stay aligned for any padding; the consumers skip the psh extra columns
+    const int psh = ((-p.P) % 4 + 4) % 4;
 
     int lid = blockIdx.x;
     if ((gridDim.x & 7) == 0) lid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
@@ -76,7 +79,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
         unsigned rowbase;  // element offset of the stage's first channel row within the sample
     };
     auto geo = [&](int u) -> Geo {
-        return Geo{static_cast<long>(tile_n(u)) * p.in_sn, tile_O0(u) - p.P, static_cast<unsigned>(stage_cb(u) * 16 * p.Win)};
+        return Geo{static_cast<long>(tile_n(u)) * p.in_sn, tile_O0(u) - p.P - psh, static_cast<unsigned>(stage_cb(u) * 16 * p.Win)};
     };
 
     // ---- producer side ------------------------------------------------------------------------------
@@ -214,7 +217,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
         // carry immediate offsets only instead of an address add in front of each of them
         int wi[RC];
 #pragma unroll
-        for (int cc = 0; cc < RC; ++cc) wi[cc] = static_cast<int>(wb - lds) + (4 * cc + kb) * LPS + ob + li;
+        for (int cc = 0; cc < RC; ++cc) wi[cc] = static_cast<int>(wb - lds) + (4 * cc + kb) * LPS + ob + li + psh;
         int ai = lane + cb * nsteps * 64;
         float a0[RC], b0[RC][T], a1[RC], b1[RC][T];
         auto load_tap = [&](float (&a)[RC], float (&b)[RC][T]) {  // loads the tap the indices point at
@@ -344,7 +347,7 @@ CorrF32Plan corr_f32_plan(const CorrProblem& p) {
     if (pl.ncb > 1 && p.accumulate) return pl;
     pl.RC = pl.ncb > 1 ? 4 : (p.R + 3) / 4;
     const long halo = static_cast<long>(p.S - 1) * p.d;
-    const long LP = TQ + halo;
+    const long LP = TQ + halo + 3;  // + the columns in front of an unaligned window origin
     // row stride == 16 (mod 32) words: the four k rows of a B fragment fall on disjoint bank halves
     const long LPS = (LP + 31) / 32 * 32 + 16;
     const long wbytes = static_cast<long>(pl.ncb) * p.S * pl.RC * 64 * 4;
@@ -360,7 +363,7 @@ CorrF32Plan corr_f32_plan(const CorrProblem& p) {
     pl.ntiles = static_cast<int>(nt);
     pl.lds_bytes = static_cast<size_t>(bytes);
     // 16-byte window loads need every row start, the window origin and the base pointer aligned
-    pl.fast = (p.Win % 4 == 0) && (((p.P % 4) + 4) % 4 == 0) && (reinterpret_cast<uintptr_t>(p.in) % 16 == 0) && p.Win >= 4;
+    pl.fast = (p.Win % 4 == 0) && (p.in_sn % 4 == 0) && (reinterpret_cast<uintptr_t>(p.in) % 16 == 0) && p.Win >= 4;
     pl.vec_out = (p.Wout % 4 == 0) && (p.out_sn % 4 == 0) && (reinterpret_cast<uintptr_t>(p.out) % 16 == 0);
     pl.raw_in_lds = p.w_contig && static_cast<long>(p.M) * p.R * p.S * 4 <= pl.nbuf * win_bytes;
     pl.ok = true;
@@ -443,6 +446,9 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
         w.lds = (r * (is_x ? LXS : LQS) + 4 * i) | (r < rows ? 0 : kRowBad);
         return w;
     };
+    // x column 0 is the input position (chunk start - P) rounded down to a multiple of 4, so that 16-byte staging
+    // loads stay aligned for any padding; the consumers skip the psh extra columns
+    const int psh = ((-p.P) % 4 + 4) % 4;
     struct Origin { const float* xb; const float* dyb; int Qs; };
     auto origin = [&](int chunk) -> Origin {
         const int n = chunk / chunks_per_row;
@@ -452,7 +458,7 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
         const bool is_x = slot_is_x(k);
         const float* row = (is_x ? o.xb : o.dyb) + w.off;
         const int limit = is_x ? p.W : p.Q;
-        const int g = (is_x ? o.Qs - p.P : o.Qs) + w.col;
+        const int g = (is_x ? o.Qs - p.P - psh : o.Qs) + w.col;
         if constexpr (FAST) {
             const int lim = limit - 4;
             return *reinterpret_cast<const f32x4*>(row + (g < 0 ? 0 : (g > lim ? lim : g)));
@@ -470,7 +476,7 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
     auto commit = [&](int b, const Origin& o, int k, const Slot& w, f32x4 v) {
         const bool is_x = slot_is_x(k);
         const int limit = is_x ? p.W : p.Q;
-        const int g = (is_x ? o.Qs - p.P : o.Qs) + w.col;
+        const int g = (is_x ? o.Qs - p.P - psh : o.Qs) + w.col;
         const bool ok = !(w.lds & kRowBad) && (!FAST || (g >= 0 && g + 4 <= limit));
         if (!ok) v = f32x4{0.f, 0.f, 0.f, 0.f};
         // rows are only 8-byte aligned (their stride is 2 mod 32 words, see the plan): two 8-byte stores
@@ -533,7 +539,7 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
             int ai = b * stage_floats + li * LQS + kb;
             int bi[NT];
 #pragma unroll
-            for (int i = 0; i < NT; ++i) bi[i] = b * stage_floats + 16 * LQS + li * LXS + kb + (cw + 4 * i) * p.d;
+            for (int i = 0; i < NT; ++i) bi[i] = b * stage_floats + 16 * LQS + li * LXS + kb + (cw + 4 * i) * p.d + psh;
             // two k-steps per iteration with ping-pong operand registers: the LDS reads of the next k-step
             // are issued between the MFMAs of the current one.  The reads of the last iteration run 4
             // columns past the chunk (into row padding / the slack after the last row) and are discarded.
@@ -648,7 +654,7 @@ WgradF32Plan wgrad_f32_plan(const WgradProblem& p) {
     pl.NT = kWgradNT;
     for (int i = 4; i >= 0; --i)
         if (4 * kWgradNTs[i] >= p.S) pl.NT = kWgradNTs[i];
-    const long halo = static_cast<long>(4 * pl.NT - 1) * p.d;  // every tap slot a wave may read
+    const long halo = static_cast<long>(4 * pl.NT - 1) * p.d + 3;  // every tap slot a wave may read, + an unaligned window origin
     // row stride == 2 (mod 32) words: the 32 lanes (16 rows x 2 adjacent columns) that the LDS serves together
     // fall on 32 distinct banks (a stride of 4 would pair row r with row r+8)
     auto pad = [](long v) { return (v + 31) / 32 * 32 + 2; };
@@ -666,7 +672,7 @@ WgradF32Plan wgrad_f32_plan(const WgradProblem& p) {
         pl.nchunks = static_cast<int>(nc);
         pl.grid = pl.nchunks < kNumCU ? pl.nchunks : kNumCU;
         pl.lds_bytes = static_cast<size_t>(bytes);
-        pl.fast = (p.W % 4 == 0) && (p.Q % 4 == 0) && (p.P % 4 == 0) && p.W >= 4 && p.Q >= 4 &&
+        pl.fast = (p.W % 4 == 0) && (p.Q % 4 == 0) && (p.x_sn % 4 == 0) && (p.dy_sn % 4 == 0) && p.W >= 4 && p.Q >= 4 &&
                   (reinterpret_cast<uintptr_t>(p.x) % 16 == 0) && (reinterpret_cast<uintptr_t>(p.dy) % 16 == 0);
         pl.ok = true;
         return pl;
