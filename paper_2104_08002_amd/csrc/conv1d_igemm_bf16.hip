@@ -247,8 +247,7 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
             wt_voff[k] = 2u * (static_cast<unsigned>(wt_plane8[k]) * static_cast<unsigned>(a.Win) + 2u * static_cast<unsigned>(wt_pair[k]));
             wt_dst[k] = (wt_plane8[k] >> 3) * a.LPS + 2 * wt_pair[k];
         }
-        auto window_prefetch = [&](int st) {
-            const Geo g = geo(st);
+        auto window_prefetch = [&](const Geo& g) {
             const char* ib = reinterpret_cast<const char*>(a.in + static_cast<long>(g.n) * a.in_sn);
             const unsigned rowb = static_cast<unsigned>(a.Win) * 2u;
             if (interior(g)) {
@@ -275,8 +274,7 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
                     }
             }
         };
-        auto window_commit = [&](int st, int b) {
-            const Geo g = geo(st);
+        auto window_commit = [&](const Geo& g, int b) {
             u32x4* win = lds4 + b * a.stage_slots;
             const bool inner = interior(g);
 #pragma unroll
@@ -301,8 +299,7 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
         auto stage_base = [&](const Geo& g) -> long {
             return static_cast<long>(g.fg * kFB * 16) * a.w_sm + static_cast<long>(g.r0) * a.w_sr;
         };
-        auto raw_prefetch = [&](int st) {
-            const Geo g = geo(st);
+        auto raw_prefetch = [&](const Geo& g) {
             const unsigned eb = static_cast<unsigned>(stage_base(g));  // the tensor has fewer than 2^31 elements
             const int umax = a.fwd_mode ? a.M - 1 - g.fg * kFB * 16 : a.R - 1 - g.r0;
             const char* wb = reinterpret_cast<const char*>(a.wt);
@@ -335,8 +332,7 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
             for (int k = 0; k < kMaxRP; ++k)
                 if (rtid + k * 256 < NRP) raw[rp_u[k] * a.NPc + rp_q[k]] = rreg[k];
         };
-        auto gather = [&](int st, int b) {
-            const Geo g = geo(st);
+        auto gather = [&](const Geo& g, int b) {
             const unsigned short* raw = reinterpret_cast<const unsigned short*>(lds4 + 2 * a.stage_slots + b * a.raw_slots);
             u32x4* wgt = lds4 + b * a.stage_slots + wbase;
             const int pb = static_cast<int>(stage_base(g) & 1);
@@ -367,32 +363,40 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
         };
         // iteration t: window t+1 -> LDS, window t+2 -> registers; entries t+1 <- raw[(t+1)&1],
         // raw[t&1] <- registers (stage t+2), registers <- global (stage t+3)
+        // (the geometry of a stage costs four integer divisions: it is worked out once, when the stage enters
+        // the pipeline, and handed down: g1, g2, g3 are the stages st + 1, st + 2, st + 3)
+        Geo g1 = geo(0), g2 = geo(1 < nstages ? 1 : 0), g3 = geo(2 < nstages ? 2 : 0);
         if (nstages > 0) {
-            raw_prefetch(0);
-            window_prefetch(0);
+            raw_prefetch(g1);
+            window_prefetch(g1);
             raw_commit(0);
-            if (nstages > 1) raw_prefetch(1);
+            if (nstages > 1) raw_prefetch(g2);
         }
         __syncthreads();
         if (nstages > 0) {
-            gather(0, 0);
-            window_commit(0, 0);
+            gather(g1, 0);
+            window_commit(g1, 0);
             if (nstages > 1) {
                 raw_commit(1);
-                window_prefetch(1);
+                window_prefetch(g2);
             }
-            if (nstages > 2) raw_prefetch(2);
+            if (nstages > 2) raw_prefetch(g3);
         }
         __syncthreads();
+        g1 = g2;
+        g2 = g3;
         for (int st = 0; st < nstages; ++st) {
+            if (st + 3 < nstages) g3 = geo(st + 3);
             if (st + 1 < nstages) {
                 // registers are refilled as soon as they are free, so every load has a whole stage to arrive
-                window_commit(st + 1, (st + 1) & 1);
-                if (st + 2 < nstages) window_prefetch(st + 2);
+                window_commit(g1, (st + 1) & 1);
+                if (st + 2 < nstages) window_prefetch(g2);
                 if (st + 2 < nstages) raw_commit(st & 1);
-                if (st + 3 < nstages) raw_prefetch(st + 3);
-                gather(st + 1, (st + 1) & 1);
+                if (st + 3 < nstages) raw_prefetch(g3);
+                gather(g1, (st + 1) & 1);
             }
+            g1 = g2;
+            g2 = g3;
             __syncthreads();
         }
     }
