@@ -20,6 +20,9 @@ OBJ_DIR = os.path.join(HERE, "_build")
 HIP_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-Wall", "-Wno-unused-function",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the fully unrolled MFMA schedules are long: with the default threshold the larger instantiations are left
+    # as loops, their register arrays go to scratch memory and they run two orders of magnitude slower
+    "-mllvm", "-pragma-unroll-threshold=262144",
 ]
 
 

@@ -7,7 +7,7 @@
 // registers for the lifetime of a workgroup.  The input window (tile + halo) is transposed into
 // LDS as [position][8 channels] 16-byte slots so that one lane's 8 k-values are one ds_read_b128.
 // A batch-reduce GEMM over taps (Algorithm 2) would re-read the window once per tap; here the
-// Toeplitz structure of the shifted-input matrix is used instead: when d divides 16, the operand
+// Toeplitz structure of the shifted-input matrix is used instead: when d divides 16 (G = 16/d), the operand
 // for (tile j, tap p) is the operand for (tile j+1, tap p - 16/d), so a wave that owns T adjacent
 // tiles loads each operand once and feeds up to T MFMAs from it.
 //
@@ -380,8 +380,7 @@ CorrPlan corr_plan(const CorrProblem& p) {
     if (pl.NP == 0) return pl;
     // operand reuse across tiles pays when a tile shift is a few taps (d = 4, 8, 16); for d = 1, 2 the
     // shift is 16 or 8 taps, little is shared and the unrolled schedule gets very long
-    pl.G = (p.d == 4 || p.d == 8 || p.d == 16) ? 16 / p.d : 0;
-    if (pl.NP >= 13 && pl.G == 4) pl.G = 0;  // these instantiations do not fit the register budget
+    pl.G = (p.d == 1 || p.d == 2 || p.d == 4 || p.d == 8 || p.d == 16) ? 16 / p.d : 0;
     constexpr int TQ = 4 * kCorrT * 16;
     const long LP = TQ + static_cast<long>(2 * pl.NP - 1) * p.d;
     const long LPS = (LP + 2 + 7) / 8 * 8;
@@ -424,8 +423,9 @@ hipError_t corr_launch_np(const CorrProblem& p, const CorrPlan& pl, hipStream_t 
 #ifndef CONV1D_DEV_FEW_KERNELS
         case 1: return corr_launch_t<NP, 1>(p, pl, st);
         case 4:
-            if constexpr (NP < 13) return corr_launch_t<NP, 4>(p, pl, st);  // (>= 13, 4) is routed to G = 0 by the plan
-            return hipErrorInvalidValue;
+            return corr_launch_t<NP, 4>(p, pl, st);
+        case 8: return corr_launch_t<NP, 8>(p, pl, st);
+        case 16: return corr_launch_t<NP, 16>(p, pl, st);
 #endif
         case 2: return corr_launch_t<NP, 2>(p, pl, st);
         default: return corr_launch_t<NP, 0>(p, pl, st);
