@@ -74,7 +74,10 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
     const unsigned short* __restrict__ in = static_cast<const unsigned short*>(p.in);
     const unsigned short* __restrict__ wt = static_cast<const unsigned short*>(p.wt);
     const int d = (G > 0) ? 16 / (G > 0 ? G : 1) : p.d;
-    const int LP = TQ + (2 * NP - 1) * d;
+    // window slot 0 is the input position (tile start - P) rounded down to an even one, so that the dword loads of
+    // position pairs stay aligned for any padding; the consumers skip the extra slot
+    const int psh = p.P & 1;
+    const int LP = TQ + (2 * NP - 1) * d + psh;
     const int LP2 = (LP + 1) >> 1;
     const int ntasks = 2 * LP2;
     const int ob = cw * T * 16;
@@ -162,7 +165,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
     Task pre[FAST ? MAXT : 1];
     auto prefetch = [&](int t) {  // producers: window of tile t -> registers
         if constexpr (FAST) {
-            const int n = tile_n(t), G0 = tile_O0(t) - p.P;
+            const int n = tile_n(t), G0 = tile_O0(t) - p.P - psh;
 #pragma unroll
             for (int k = 0; k < MAXT; ++k) {
                 const int task = rtid + k * 256;
@@ -171,7 +174,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
         }
     };
     auto commit = [&](int t, u32x4* wb) {  // producers: registers (or memory) -> LDS window of tile t
-        const int n = tile_n(t), G0 = tile_O0(t) - p.P;
+        const int n = tile_n(t), G0 = tile_O0(t) - p.P - psh;
         const bool edge = G0 < 0 || G0 + 2 * LP2 > p.Win;
         if constexpr (FAST) {
 #pragma unroll
@@ -285,7 +288,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
         f32x4 acc[T];
 #pragma unroll
         for (int j = 0; j < T; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-        const u32x4* bbase = wb + (kb & 1) * LPS + ob + li + (kb >> 1) * NP * d;
+        const u32x4* bbase = wb + (kb & 1) * LPS + ob + li + (kb >> 1) * NP * d + psh;
         auto park = [&](int j) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) dst[(4 * kb + i) * kOS + j * 16 + li] = acc[j][i];
@@ -382,7 +385,7 @@ CorrPlan corr_plan(const CorrProblem& p) {
     // shift is 16 or 8 taps, little is shared and the unrolled schedule gets very long
     pl.G = (p.d == 1 || p.d == 2 || p.d == 4 || p.d == 8 || p.d == 16) ? 16 / p.d : 0;
     constexpr int TQ = 4 * kCorrT * 16;
-    const long LP = TQ + static_cast<long>(2 * pl.NP - 1) * p.d;
+    const long LP = TQ + static_cast<long>(2 * pl.NP - 1) * p.d + 1;  // + the slot in front of an odd window origin
     const long LPS = (LP + 2 + 7) / 8 * 8;
     // [2 window buffers | 2 output staging buffers]; the weight-slice assembly area aliases the staging buffers
     const long slots = 4 * LPS + 2 * kOstSlots;
@@ -394,7 +397,7 @@ CorrPlan corr_plan(const CorrProblem& p) {
     pl.ntiles = static_cast<int>(nt);
     pl.lds_bytes = static_cast<size_t>(slots) * 16;
     // dword loads of position pairs need even row starts and an even window origin
-    pl.fast = (p.Win % 2 == 0) && (p.P % 2 == 0) && (reinterpret_cast<uintptr_t>(p.in) % 4 == 0) && p.Win >= 2;
+    pl.fast = (p.Win % 2 == 0) && (p.in_sn % 2 == 0) && (reinterpret_cast<uintptr_t>(p.in) % 4 == 0) && p.Win >= 2;
     pl.vec_out = (p.Wout % 4 == 0) && (reinterpret_cast<uintptr_t>(p.out) % 16 == 0) &&
                  static_cast<long>(p.M) * p.Wout < (1L << 30);
     pl.ok = true;
