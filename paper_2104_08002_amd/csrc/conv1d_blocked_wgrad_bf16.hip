@@ -348,29 +348,35 @@ __global__ __launch_bounds__(512, 2) void blocked_wgrad_bf16_kernel(BlkArgs a) {
 }
 
 // Adds the strips in a fixed order (16 interleaved running sums per element, then those 16 in order) and
-// scatters the tiles into dw[k][c][s].  One thread group of 16 x 16 per 16 consecutive tile elements.
+// scatters the tiles into dw[k][c][s].  A block of 16 x 16 threads handles 64 consecutive tile elements: thread
+// (g, el) adds the strips g, g + 16, ... of the 4 elements 4 el .. 4 el + 3 with 16-byte loads.  The tile size is
+// a multiple of 256, so a block never straddles two combinations.
 __global__ __launch_bounds__(256) void blocked_wgrad_reduce_kernel(const float* __restrict__ ws, float* __restrict__ dw, BlkArgs a, int FB, int NT) {
-    __shared__ float part[16][17];
+    __shared__ f32x4 part[16][17];
     const int el = threadIdx.x & 15, g = threadIdx.x >> 4;
     const int tile = a.ncbw * FB * NT * 256;
     const int ncombos = a.nfg * a.ncb * a.ntg;
-    const long idx = static_cast<long>(blockIdx.x) * 16 + el;  // (combo, tile element)
+    const long idx = static_cast<long>(blockIdx.x) * 64 + 4 * el;  // (combo, tile element)
     const int combo = static_cast<int>(idx / tile), e = static_cast<int>(idx - static_cast<long>(combo) * tile);
-    float sum = 0.f;
+    f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
     if (combo < ncombos)
-        for (int s = g; s < a.nstrips; s += 16) sum += ws[(static_cast<long>(s) * ncombos + combo) * tile + e];
+        for (int s = g; s < a.nstrips; s += 16) sum += *reinterpret_cast<const f32x4*>(ws + (static_cast<long>(s) * ncombos + combo) * tile + e);
     part[g][el] = sum;
     __syncthreads();
     if (g == 0 && combo < ncombos) {
-        float t = part[0][el];
+        f32x4 t = part[0][el];
 #pragma unroll
         for (int j = 1; j < 16; ++j) t += part[j][el];
+        // the 4 elements are the filters 4 (l >> 4) .. + 3 of one (block, tap, channel)
         const int tg = combo % a.ntg, cbi = (combo / a.ntg) % a.ncb, fg = combo / (a.ntg * a.ncb);
-        const int blk = e >> 8, r = e & 255;
+        const int blk = e >> 8, l = (e & 255) >> 2;
         const int i = blk % NT, fb = (blk / NT) % FB, cbl = blk / (NT * FB);
-        const int l = r >> 2, jj = r & 3;
-        const int k = (fg * FB + fb) * 16 + 4 * (l >> 4) + jj, c = (cbi * a.ncbw + cbl) * 16 + (l & 15), s = tg * NT + i;
-        if (k < a.K && c < a.C && s < a.S) dw[(static_cast<long>(k) * a.C + c) * a.S + s] = t;
+        const int k0 = (fg * FB + fb) * 16 + 4 * (l >> 4), c = (cbi * a.ncbw + cbl) * 16 + (l & 15), s = tg * NT + i;
+        if (c < a.C && s < a.S) {
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+                if (k0 + jj < a.K) dw[(static_cast<long>(k0 + jj) * a.C + c) * a.S + s] = t[jj];
+        }
     }
 }
 
@@ -519,7 +525,7 @@ hipError_t blocked_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     }
     if (e != hipSuccess) return e;
     const long nel = static_cast<long>(pl.grid / pl.a.nstrips) * pl.tile;
-    hipLaunchKernelGGL(blocked_wgrad_reduce_kernel, dim3(cdiv(nel, 16)), dim3(256), 0, st, static_cast<const float*>(p.ws), p.dw, pl.a, pl.FB,
+    hipLaunchKernelGGL(blocked_wgrad_reduce_kernel, dim3(cdiv(nel, 64)), dim3(256), 0, st, static_cast<const float*>(p.ws), p.dw, pl.a, pl.FB,
                        pl.NT);
     return hipGetLastError();
 }
