@@ -79,8 +79,7 @@ __global__ __launch_bounds__(512, 2) void blocked_wgrad_bf16_kernel(BlkArgs a) {
 
     // Workgroups are dealt round-robin to the 8 XCDs: the logical index puts the combinations of one strip
     // (which read the same x and dy chunks) next to each other on one XCD and its L2.
-    int lid = blockIdx.x;
-    if ((gridDim.x & 7) == 0) lid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int lid = xcd_logical_id(blockIdx.x, gridDim.x);
     const int ncombos = a.nfg * a.ncb * a.ntg;
     const int strip = lid / ncombos;
     const int combo = lid - strip * ncombos;

@@ -56,7 +56,7 @@ struct IgArgs {
     int N, R, M, Win, Wout, S, d, P;
     long w_sm, w_sr, in_sn, out_sn;
     int w_s0, w_ss;
-    int tiles_per_row, nfg, ntiles;
+    int tiles_per_row, nfg, nct, nteams;  // column blocks per row, filter groups, N * tiles_per_row, teams of nfg workgroups
     int NG, NQ, ncc;  // channel groups of 8 per stage, MFMA steps per stage, stages per tile
     int LP, LPS;      // window positions staged (even), plane stride in slots
     int delta;        // (o0 - P) - window origin: 0 or 1
@@ -80,13 +80,13 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
     const int li = lane & 15;
     const int kb = lane >> 4;
 
-    // Contiguous strip of tiles per workgroup; tile index = (sample, column block, filter group) with the filter
-    // group fastest, so the tiles that share an input window are neighbours.  Workgroups are dealt round-robin
-    // to the 8 XCDs: the logical index keeps neighbouring strips on one XCD and its L2.
-    int lid = blockIdx.x;
-    if ((gridDim.x & 7) == 0) lid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    const int t_begin = static_cast<int>(static_cast<long>(lid) * a.ntiles / gridDim.x);
-    const int t_end = static_cast<int>(static_cast<long>(lid + 1) * a.ntiles / gridDim.x);
+    // A tile is (column block ct of one sample, filter group fg).  nfg workgroups with consecutive logical indices
+    // form a team that walks one contiguous strip of column blocks, one filter group each: the team's members
+    // run side by side on one XCD, so a window is fetched from HBM once and found in L2 by the others.
+    const int lid = xcd_logical_id(blockIdx.x, gridDim.x);
+    const int team = lid / a.nfg, fg = lid - team * a.nfg;
+    const int t_begin = static_cast<int>(static_cast<long>(team) * a.nct / a.nteams);
+    const int t_end = static_cast<int>(static_cast<long>(team + 1) * a.nct / a.nteams);
     const int nstages = (t_end - t_begin) * a.ncc;
     const int wbase = a.NG * a.LPS;  // weights behind the window planes
 
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
             }
             if (++cc == a.ncc) {
                 // the tile is complete: lane (li, kb) holds filters 4 kb .. 4 kb + 3 of each block at column li
-                const int fg = tile % a.nfg, ct = tile / a.nfg;
+                const int ct = tile;
                 const int n = ct / a.tiles_per_row;
                 const int o = (ct - n * a.tiles_per_row) * kTW + cw * (kT * 16) + li;
                 float* base = a.out + static_cast<long>(n) * a.out_sn;
@@ -225,10 +225,9 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
             int n, G0, fg, r0;  // sample, window origin, filter group, first channel of the chunk
         };
         auto geo = [&](int st) -> Geo {
-            const int tile = t_begin + st / a.ncc, cc = st - (st / a.ncc) * a.ncc;
+            const int ct = t_begin + st / a.ncc, cc = st - (st / a.ncc) * a.ncc;
             Geo g;
-            g.fg = tile % a.nfg;
-            const int ct = tile / a.nfg;
+            g.fg = fg;
             g.n = ct / a.tiles_per_row;
             g.G0 = (ct - g.n * a.tiles_per_row) * kTW - a.P - a.delta;
             g.r0 = cc * a.NG * 8;
@@ -462,10 +461,12 @@ IgPlan ig_plan(const CorrProblem& p) {
         a.wbytes = (fwd_mode ? static_cast<long>(p.M) * p.w_sm : static_cast<long>(p.R) * p.w_sr) * 2;
         a.tiles_per_row = cdiv(p.Wout, kTW);
         a.nfg = cdiv(p.M, kFB * 16);
-        const long ntiles = static_cast<long>(p.N) * a.tiles_per_row * a.nfg;
-        if (ntiles > 0x7fffffffL / 16) return pl;
-        a.ntiles = static_cast<int>(ntiles);
-        pl.grid = a.ntiles < kNumCU ? a.ntiles : kNumCU;
+        const long nct = static_cast<long>(p.N) * a.tiles_per_row;
+        if (nct > 0x7fffffffL / 16 || a.nfg > 65535) return pl;
+        a.nct = static_cast<int>(nct);
+        const int fit = kNumCU / a.nfg > 0 ? kNumCU / a.nfg : 1;  // teams that run at the same time
+        a.nteams = a.nct < fit ? a.nct : fit;
+        pl.grid = a.nteams * a.nfg;
         pl.lds_bytes = bytes;
         pl.ok = true;
         return pl;

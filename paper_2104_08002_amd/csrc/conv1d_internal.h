@@ -101,6 +101,13 @@ __device__ __forceinline__ float load_elem(const void* base, long idx) {
     }
 }
 
+// Workgroups are dealt round-robin to the 8 XCDs (workgroup b runs on XCD b % 8).  The logical index numbers
+// the workgroups XCD by XCD, so that consecutive logical indices share an XCD and its L2, for any grid size.
+__device__ __forceinline__ int xcd_logical_id(int b, int grid) {
+    const int x = b & 7, base = grid >> 3, rem = grid & 7;
+    return x * base + (x < rem ? x : rem) + (b >> 3);
+}
+
 inline int cdiv(long a, long b) { return static_cast<int>((a + b - 1) / b); }
 
 }  // namespace conv1d

@@ -62,8 +62,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
     // staging loads stay aligned for any padding; the consumers skip the psh extra columns
     const int psh = ((-p.P) % 4 + 4) % 4;
 
-    int lid = blockIdx.x;
-    if ((gridDim.x & 7) == 0) lid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int lid = xcd_logical_id(blockIdx.x, gridDim.x);
     const int t_begin = static_cast<int>(static_cast<long>(lid) * ntiles / gridDim.x) * ncb;      // first stage of the strip
     const int t_end = static_cast<int>(static_cast<long>(lid + 1) * ntiles / gridDim.x) * ncb;  // one past its last stage
     // stage u = tile * ncb + channel block (all of the strip's stages in one sequence)
@@ -421,8 +420,7 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
     const int nslots = ndy + 16 * LX4;
 
     // contiguous strip of chunks; neighbouring strips (shared halos) land on the same XCD
-    int lid = blockIdx.x;
-    if ((gridDim.x & 7) == 0) lid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int lid = xcd_logical_id(blockIdx.x, gridDim.x);
     const int c_begin = static_cast<int>(static_cast<long>(lid) * nchunks / gridDim.x);
     const int c_end = static_cast<int>(static_cast<long>(lid + 1) * nchunks / gridDim.x);
 

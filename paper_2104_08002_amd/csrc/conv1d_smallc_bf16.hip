@@ -86,8 +86,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
 
     // Contiguous strip of tiles per workgroup.  Workgroups are dealt round-robin to the 8 XCDs, so the
     // logical index puts neighbouring strips (which share halos) on the same XCD and its L2.
-    int lid = blockIdx.x;
-    if ((gridDim.x & 7) == 0) lid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int lid = xcd_logical_id(blockIdx.x, gridDim.x);
     const int t_begin = static_cast<int>(static_cast<long>(lid) * ntiles / gridDim.x);
     const int t_end = static_cast<int>(static_cast<long>(lid + 1) * ntiles / gridDim.x);
 
