@@ -44,6 +44,14 @@ WgradProblem wgrad_block(const WgradProblem& p, int k0, int c0) {
     return b;
 }
 
+// FP32 backward-weight: all block pairs as one launch while their partial sums fit a moderate workspace
+constexpr size_t kMaxPairsWorkspace = 512u << 20;
+bool fp32_pairs_in_one_launch(const WgradProblem& p) {
+    if (p.bf16 || p.dw_sc != p.S) return false;
+    const size_t bytes = smallc_wgrad_f32_blocks_workspace(p);
+    return bytes > 0 && bytes <= kMaxPairsWorkspace;
+}
+
 }  // namespace
 
 // The first block pair is the largest one; the others differ from it only by having fewer rows.
@@ -84,12 +92,14 @@ bool igemm_wgrad_supported(const WgradProblem& p) {
 size_t igemm_wgrad_workspace(const WgradProblem& p) {
     if (!igemm_wgrad_supported(p)) return 0;
     if (p.bf16 && blocked_bf16_wgrad_supported(p)) return blocked_bf16_wgrad_workspace(p);
+    if (fp32_pairs_in_one_launch(p)) return smallc_wgrad_f32_blocks_workspace(p);
     return smallc_wgrad_workspace(wgrad_block(p, 0, 0));
 }
 
 hipError_t igemm_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     if (!igemm_wgrad_supported(p)) return hipErrorInvalidValue;
     if (p.bf16 && blocked_bf16_wgrad_supported(p)) return blocked_bf16_wgrad_launch(p, st);
+    if (fp32_pairs_in_one_launch(p)) return smallc_wgrad_f32_blocks_launch(p, st);
     for (int k0 = 0; k0 < p.K; k0 += kBlock) {
         for (int c0 = 0; c0 < p.C; c0 += kBlock) {
             const WgradProblem b = wgrad_block(p, k0, c0);

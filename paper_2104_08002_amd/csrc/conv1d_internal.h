@@ -59,6 +59,10 @@ bool smallc_wgrad_supported(const WgradProblem& p);
 size_t smallc_wgrad_workspace(const WgradProblem& p);
 hipError_t smallc_wgrad_launch(const WgradProblem& p, hipStream_t st);
 
+// FP32 backward-weight with any C, K: every 16 x 16 block pair as one row of a single grid, one second stage
+size_t smallc_wgrad_f32_blocks_workspace(const WgradProblem& p);  // 0: not supported
+hipError_t smallc_wgrad_f32_blocks_launch(const WgradProblem& p, hipStream_t st);
+
 // bf16 members of the small-channel family (own translation unit)
 bool smallc_bf16_corr_supported(const CorrProblem& p);
 hipError_t smallc_bf16_corr_launch(const CorrProblem& p, hipStream_t st);

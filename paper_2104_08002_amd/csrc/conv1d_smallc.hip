@@ -413,8 +413,13 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
     const int rtid = tid & 255;
     const int li = lane & 15;
     const int kb = lane >> 4;
-    const float* __restrict__ x = static_cast<const float*>(p.x);
-    const float* __restrict__ dy = static_cast<const float*>(p.dy);
+    // More than 16 channels or filters: blockIdx.y numbers the (filter block, channel block) pairs; a workgroup
+    // works on the 16 x 16 block pair of its row of the grid and writes its own slice of the workspace.
+    const int ncbp = (p.C + 15) >> 4;
+    const int pair = blockIdx.y, kbi = pair / ncbp, cbi = pair - kbi * ncbp;
+    const int Cb = min(16, p.C - 16 * cbi), Kb = min(16, p.K - 16 * kbi);  // channels / filters of this block
+    const float* __restrict__ x = static_cast<const float*>(p.x) + static_cast<long>(cbi) * 16 * p.W;
+    const float* __restrict__ dy = static_cast<const float*>(p.dy) + static_cast<long>(kbi) * 16 * p.Q;
     const int Q4 = QC / 4;
     const int ndy = 16 * Q4;
     const int nslots = ndy + 16 * LX4;
@@ -437,7 +442,7 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
         const int e2 = is_x ? e - ndy : e;
         const int per_row = is_x ? LX4 : Q4;
         const int r = e2 / per_row, i = e2 - r * per_row;
-        const int rows = is_x ? p.C : p.K;
+        const int rows = is_x ? Cb : Kb;
         Slot w;
         w.off = static_cast<unsigned>(min(r, rows - 1) * (is_x ? p.W : p.Q));
         w.col = 4 * i;
@@ -595,7 +600,7 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
     }
     if (consumer) {
         const int nt = (p.S - cw + 3) / 4;  // real taps of this wave; slots beyond hold unused sums
-        float* ws = static_cast<float*>(p.ws) + static_cast<long>(blockIdx.x) * p.S * 256;
+        float* ws = static_cast<float*>(p.ws) + (static_cast<long>(pair) * gridDim.x + blockIdx.x) * p.S * 256;
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
             if (i < nt) {
@@ -610,9 +615,18 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
 // Second stage of the backward-weight pass: dw[k][c][s] = sum over workgroups g of
 // ws[(g*S + s)*256 + k*16 + c], always in the same order: 16 contiguous groups of workgroups are
 // summed left to right by 16 threads each, then the 16 group sums are added left to right.
+// blockIdx.y numbers the (filter block, channel block) pairs of a batched launch (K, C: totals).
 __global__ __launch_bounds__(256) void smallc_wgrad_reduce_kernel(const float* __restrict__ ws, float* __restrict__ dw, int K, int C, int S, long dw_sk,
                                                                   long dw_sc, int nwg) {
     __shared__ float part[16][17];
+    {
+        const int ncbp = (C + 15) >> 4;
+        const int pair = blockIdx.y, kbi = pair / ncbp, cbi = pair - kbi * ncbp;
+        ws += static_cast<long>(pair) * nwg * S * 256;
+        dw += kbi * 16 * dw_sk + cbi * 16 * dw_sc;
+        K = min(16, K - 16 * kbi);
+        C = min(16, C - 16 * cbi);
+    }
     const int el = threadIdx.x & 15, grp = threadIdx.x >> 4;
     const int e = blockIdx.x * 16 + el;  // index into one workgroup's S*256 partial tile
     const int total = S * 256;
@@ -644,10 +658,12 @@ struct WgradF32Plan {
 constexpr int kWgradNT = 13, kWgradMaxS = 15;  // most taps per wave; staging slots per producer thread held in registers
 constexpr int kWgradNTs[] = {2, 3, 5, 9, 13};    // instantiated taps per wave: 4 * NT tap slots are multiplied whatever S is
 
-WgradF32Plan wgrad_f32_plan(const WgradProblem& p) {
+WgradF32Plan wgrad_f32_plan(const WgradProblem& p, bool blocks = false) {
     WgradF32Plan pl{};
     pl.ok = false;
-    if (p.bf16 || p.C > 16 || p.K > 16 || p.S > 4 * kWgradNT) return pl;
+    if (p.bf16 || p.S > 4 * kWgradNT) return pl;
+    if (!blocks && (p.C > 16 || p.K > 16)) return pl;
+    if (static_cast<long>(cdiv(p.C, 16)) * cdiv(p.K, 16) > 65535) return pl;
     if (static_cast<long>(p.C) * p.W >= (1L << 30) || static_cast<long>(p.K) * p.Q >= (1L << 30)) return pl;
     pl.NT = kWgradNT;
     for (int i = 4; i >= 0; --i)
@@ -684,7 +700,8 @@ hipError_t wgrad_f32_launch_nt(const WgradProblem& p, const WgradF32Plan& pl, hi
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        static_cast<int>(pl.lds_bytes));
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(pl.grid), dim3(512), pl.lds_bytes, st, p, pl.chunks_per_row, pl.nchunks, pl.QC, pl.LQS, pl.LXS,
+    const int pairs = cdiv(p.K, 16) * cdiv(p.C, 16);
+    hipLaunchKernelGGL(kern, dim3(pl.grid, pairs), dim3(512), pl.lds_bytes, st, p, pl.chunks_per_row, pl.nchunks, pl.QC, pl.LQS, pl.LXS,
                        pl.LX4);
     return hipGetLastError();
 }
@@ -693,7 +710,8 @@ hipError_t wgrad_f32_launch_nt(const WgradProblem& p, const WgradF32Plan& pl, hi
 
 hipError_t smallc_wgrad_reduce_launch(const float* ws, float* dw, int K, int C, int S, long dw_sk, long dw_sc, int nwg,
                                       hipStream_t st) {
-    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(cdiv(S * 256, 16)), dim3(256), 0, st, ws, dw, K, C, S, dw_sk, dw_sc, nwg);
+    const int pairs = cdiv(K, 16) * cdiv(C, 16);
+    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(cdiv(S * 256, 16), pairs), dim3(256), 0, st, ws, dw, K, C, S, dw_sk, dw_sc, nwg);
     return hipGetLastError();
 }
 
@@ -714,6 +732,8 @@ hipError_t smallc_corr_launch(const CorrProblem& p, hipStream_t st) {
     }
 }
 
+hipError_t smallc_wgrad_launch_impl(const WgradProblem& p, bool blocks, hipStream_t st);
+
 bool smallc_wgrad_supported(const WgradProblem& p) {
     if (p.bf16) return smallc_bf16_wgrad_supported(p);
     return wgrad_f32_plan(p).ok;
@@ -726,9 +746,22 @@ size_t smallc_wgrad_workspace(const WgradProblem& p) {
     return static_cast<size_t>(pl.grid) * p.S * 256 * sizeof(float);
 }
 
+// FP32 with any C, K: all 16 x 16 block pairs in one launch (grid.y) and one second stage
+size_t smallc_wgrad_f32_blocks_workspace(const WgradProblem& p) {
+    const WgradF32Plan pl = wgrad_f32_plan(p, true);
+    if (!pl.ok) return 0;
+    return static_cast<size_t>(cdiv(p.K, 16)) * cdiv(p.C, 16) * pl.grid * p.S * 256 * sizeof(float);
+}
+
+hipError_t smallc_wgrad_f32_blocks_launch(const WgradProblem& p, hipStream_t st) { return smallc_wgrad_launch_impl(p, true, st); }
+
 hipError_t smallc_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     if (p.bf16) return smallc_bf16_wgrad_launch(p, st);
-    const WgradF32Plan pl = wgrad_f32_plan(p);
+    return smallc_wgrad_launch_impl(p, false, st);
+}
+
+hipError_t smallc_wgrad_launch_impl(const WgradProblem& p, bool blocks, hipStream_t st) {
+    const WgradF32Plan pl = wgrad_f32_plan(p, blocks);
     if (!pl.ok) return hipErrorInvalidValue;
     hipError_t e;
     switch (pl.NT) {
