@@ -64,6 +64,24 @@ bool igemm_corr_supported(const CorrProblem& p) {
 hipError_t igemm_corr_launch(const CorrProblem& p, hipStream_t st) {
     if (!igemm_corr_supported(p)) return hipErrorInvalidValue;
     if (p.bf16 && igemm_bf16_corr_supported(p)) return igemm_bf16_corr_launch(p, st);
+    if (!p.bf16) {
+        // every filter block in one launch when the kernel can hold the weights of all channel blocks of a block
+        CorrProblem whole = p;
+        whole.w_contig = 0;
+        if (smallc_corr_f32_blocks_supported(whole)) return smallc_corr_f32_blocks_launch(whole, st);
+        // else one launch per channel block (all filter blocks each), accumulating into the output
+        CorrProblem cols = corr_block(p, 0, 0);
+        cols.M = p.M;
+        if (smallc_corr_f32_blocks_supported(cols)) {
+            for (int r0 = 0; r0 < p.R; r0 += kBlock) {
+                cols = corr_block(p, 0, r0);
+                cols.M = p.M;
+                const hipError_t e = smallc_corr_f32_blocks_launch(cols, st);
+                if (e != hipSuccess) return e;
+            }
+            return hipSuccess;
+        }
+    }
     for (int m0 = 0; m0 < p.M; m0 += kBlock) {
         // all channel blocks in one launch when the kernel can keep their weights in LDS ...
         CorrProblem rows = corr_block(p, m0, 0);

@@ -59,6 +59,11 @@ bool smallc_wgrad_supported(const WgradProblem& p);
 size_t smallc_wgrad_workspace(const WgradProblem& p);
 hipError_t smallc_wgrad_launch(const WgradProblem& p, hipStream_t st);
 
+// FP32 forward / backward-data with any R, M: filter blocks of 16 as rows of a single grid, channel blocks reduced
+// inside the kernel (needs the weights of all channel blocks of a filter block in LDS)
+bool smallc_corr_f32_blocks_supported(const CorrProblem& p);
+hipError_t smallc_corr_f32_blocks_launch(const CorrProblem& p, hipStream_t st);
+
 // FP32 backward-weight with any C, K: every 16 x 16 block pair as one row of a single grid, one second stage
 size_t smallc_wgrad_f32_blocks_workspace(const WgradProblem& p);  // 0: not supported
 hipError_t smallc_wgrad_f32_blocks_launch(const WgradProblem& p, hipStream_t st);

@@ -56,7 +56,10 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
     const int li = lane & 15;  // row of A / column of B and D
     const int kb = lane >> 4;  // k index of A/B; row block of D
     const float* __restrict__ in = static_cast<const float*>(p.in);
-    const float* __restrict__ wt = static_cast<const float*>(p.wt);
+    // More than 16 filters: blockIdx.y numbers the filter blocks of 16; a workgroup computes its block's rows.
+    const int mb = blockIdx.y;
+    const int Mb = min(16, p.M - 16 * mb);  // filters of this block
+    const float* __restrict__ wt = static_cast<const float*>(p.wt) + static_cast<long>(mb) * 16 * p.w_sm;
     const int nslots = 4 * RC * LP4;
     // window column 0 is the input position (tile start - P) rounded down to a multiple of 4, so that 16-byte
     // staging loads stay aligned for any padding; the consumers skip the psh extra columns
@@ -159,7 +162,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
     }
     {
         // coalesced copy of the raw tensor into LDS (aliasing the windows), then reorder into wfrag
-        const int nW = p.M * p.R * p.S;
+        const int nW = Mb * p.R * p.S;
         float* raw = win(0);
         if (raw_in_lds) {
             if ((reinterpret_cast<uintptr_t>(wt) & 15) == 0) {
@@ -187,7 +190,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
             const int cb = (e >> 6) / nsteps, step = (e >> 6) - cb * nsteps, l = e & 63;
             const int m = l & 15, r = 16 * cb + 4 * (step % RC) + (l >> 4), s = step / RC;
             float v = 0.f;
-            if (m < p.M && r < p.R) {
+            if (m < Mb && r < p.R) {
                 const long idx = m * p.w_sm + r * p.w_sr + p.w_s0 + s * p.w_ss;
                 v = raw_in_lds ? raw[idx] : wt[idx];
             }
@@ -277,8 +280,8 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
         // [position][filter]: lane (li, kb) holds filter li at the 4 adjacent columns 4 kb .. 4 kb + 3 of each
         // 16-column block, one 16-byte store per block when the row starts allow it.
         const int n = tile_n(t), O0 = tile_O0(t);
-        if (li < p.M) {
-            float* row = p.out + static_cast<long>(n) * p.out_sn + static_cast<long>(li) * p.Wout;
+        if (li < Mb) {
+            float* row = p.out + static_cast<long>(n) * p.out_sn + static_cast<long>(16 * mb + li) * p.Wout;
 #pragma unroll
             for (int j = 0; j < T; ++j) {
                 const int o = O0 + ob + j * 16 + 4 * kb;
@@ -335,10 +338,10 @@ struct CorrF32Plan {
 
 constexpr int kCorrT = 4, kCorrMaxS = 11;
 
-CorrF32Plan corr_f32_plan(const CorrProblem& p) {
+CorrF32Plan corr_f32_plan(const CorrProblem& p, bool blocks = false) {
     CorrF32Plan pl{};
     pl.ok = false;
-    if (p.bf16 || p.M > 16) return pl;
+    if (p.bf16 || (p.M > 16 && !blocks) || cdiv(p.M, 16) > 65535) return pl;
     if (static_cast<long>(p.R) * p.Win >= (1L << 30)) return pl;  // 32-bit element offsets within one sample
     constexpr int TQ = 4 * kCorrT * 16;
     // more than 16 channels: blocks of 16, reduced one after the other inside the kernel
@@ -364,7 +367,7 @@ CorrF32Plan corr_f32_plan(const CorrProblem& p) {
     // 16-byte window loads need every row start, the window origin and the base pointer aligned
     pl.fast = (p.Win % 4 == 0) && (p.in_sn % 4 == 0) && (reinterpret_cast<uintptr_t>(p.in) % 16 == 0) && p.Win >= 4;
     pl.vec_out = (p.Wout % 4 == 0) && (p.out_sn % 4 == 0) && (reinterpret_cast<uintptr_t>(p.out) % 16 == 0);
-    pl.raw_in_lds = p.w_contig && static_cast<long>(p.M) * p.R * p.S * 4 <= pl.nbuf * win_bytes;
+    pl.raw_in_lds = p.w_contig && p.M <= 16 && static_cast<long>(p.M) * p.R * p.S * 4 <= pl.nbuf * win_bytes;
     pl.ok = true;
     return pl;
 }
@@ -376,7 +379,7 @@ hipError_t corr_f32_launch_f(const CorrProblem& p, const CorrF32Plan& pl, hipStr
                                        static_cast<int>(pl.lds_bytes));
     if (e != hipSuccess) return e;
     const int grid = pl.ntiles < kNumCU ? pl.ntiles : kNumCU;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.LP4, pl.nbuf,
+    hipLaunchKernelGGL(kern, dim3(grid, cdiv(p.M, 16)), dim3(512), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.LP4, pl.nbuf,
                        pl.raw_in_lds, pl.ncb, pl.vec_out);
     return hipGetLastError();
 }
@@ -715,14 +718,25 @@ hipError_t smallc_wgrad_reduce_launch(const float* ws, float* dw, int K, int C, 
     return hipGetLastError();
 }
 
+hipError_t smallc_corr_launch_impl(const CorrProblem& p, bool blocks, hipStream_t st);
+
 bool smallc_corr_supported(const CorrProblem& p) {
     if (p.bf16) return smallc_bf16_corr_supported(p);
     return corr_f32_plan(p).ok;
 }
 
+// FP32 with any M: all filter blocks of 16 in one launch (grid.y), the channel blocks reduced inside the kernel
+bool smallc_corr_f32_blocks_supported(const CorrProblem& p) { return corr_f32_plan(p, true).ok; }
+
+hipError_t smallc_corr_f32_blocks_launch(const CorrProblem& p, hipStream_t st) { return smallc_corr_launch_impl(p, true, st); }
+
 hipError_t smallc_corr_launch(const CorrProblem& p, hipStream_t st) {
     if (p.bf16) return smallc_bf16_corr_launch(p, st);
-    const CorrF32Plan pl = corr_f32_plan(p);
+    return smallc_corr_launch_impl(p, false, st);
+}
+
+hipError_t smallc_corr_launch_impl(const CorrProblem& p, bool blocks, hipStream_t st) {
+    const CorrF32Plan pl = corr_f32_plan(p, blocks);
     if (!pl.ok) return hipErrorInvalidValue;
     switch (pl.RC) {
         case 1: return corr_f32_launch_rc<1>(p, pl, st);
