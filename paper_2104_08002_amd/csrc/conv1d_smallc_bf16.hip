@@ -288,10 +288,10 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
 #pragma unroll
         for (int j = 0; j < T; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
         const u32x4* bbase = wb + (kb & 1) * LPS + ob + li + (kb >> 1) * NP * d + psh;
-        auto park = [&](int j) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) dst[(4 * kb + i) * kOS + j * 16 + li] = acc[j][i];
-        };
+        // The input fragment is the A operand and the weight slice the B operand, so the accumulator tile is
+        // [position][filter]: lane (li, kb) holds filter li at the 4 adjacent columns 4 kb .. 4 kb + 3 of tile j,
+        // parked with one 16-byte LDS write.
+        auto park = [&](int j) { *reinterpret_cast<f32x4*>(dst + li * kOS + j * 16 + 4 * kb) = acc[j]; };
         if constexpr (G > 0) {
             // Operand m serves (tile j, slice m - G*j) for every j.  Operands are fetched PF steps ahead
             // of their MFMAs; tile j is complete after step G*j + NP - 1 and is parked two steps later.
@@ -313,7 +313,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
 #pragma unroll
                 for (int j = 0; j < T; ++j) {
                     const int pi = m - G * j;
-                    if (pi >= 0 && pi < NP) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[pi < 0 ? 0 : (pi >= NP ? 0 : pi)], fr[m % (PF + 2)], acc[j], 0, 0, 0);
+                    if (pi >= 0 && pi < NP) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fr[m % (PF + 2)], wreg[pi < 0 ? 0 : (pi >= NP ? 0 : pi)], acc[j], 0, 0, 0);
                 }
                 // issue order within the step: one MFMA, one LDS operation, one MFMA, ... so that the operand
                 // read and the parking writes go out in the shadow of the MFMAs instead of in front of them
@@ -334,7 +334,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
 #pragma unroll
                 for (int j = 0; j < T; ++j) {
                     const bf16x8 f = as_bf16x8(bbase[16 * j + pi * d]);
-                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[pi], f, acc[j], 0, 0, 0);
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f, wreg[pi], acc[j], 0, 0, 0);
                 }
             }
 #pragma unroll
