@@ -102,13 +102,14 @@ hipError_t igemm_corr_launch(const CorrProblem& p, hipStream_t st) {
 }
 
 bool igemm_wgrad_supported(const WgradProblem& p) {
-    if (p.bf16 && blocked_bf16_wgrad_supported(p)) return true;
+    if (p.bf16 && (toeplitz_bf16_wgrad_supported(p) || blocked_bf16_wgrad_supported(p))) return true;
     if (p.C <= kBlock && p.K <= kBlock) return false;
     return smallc_wgrad_supported(wgrad_block(p, 0, 0));
 }
 
 size_t igemm_wgrad_workspace(const WgradProblem& p) {
     if (!igemm_wgrad_supported(p)) return 0;
+    if (p.bf16 && toeplitz_bf16_wgrad_supported(p)) return toeplitz_bf16_wgrad_workspace(p);
     if (p.bf16 && blocked_bf16_wgrad_supported(p)) return blocked_bf16_wgrad_workspace(p);
     if (fp32_pairs_in_one_launch(p)) return smallc_wgrad_f32_blocks_workspace(p);
     return smallc_wgrad_workspace(wgrad_block(p, 0, 0));
@@ -116,6 +117,7 @@ size_t igemm_wgrad_workspace(const WgradProblem& p) {
 
 hipError_t igemm_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     if (!igemm_wgrad_supported(p)) return hipErrorInvalidValue;
+    if (p.bf16 && toeplitz_bf16_wgrad_supported(p)) return toeplitz_bf16_wgrad_launch(p, st);
     if (p.bf16 && blocked_bf16_wgrad_supported(p)) return blocked_bf16_wgrad_launch(p, st);
     if (fp32_pairs_in_one_launch(p)) return smallc_wgrad_f32_blocks_launch(p, st);
     for (int k0 = 0; k0 < p.K; k0 += kBlock) {

@@ -84,6 +84,12 @@ bool blocked_bf16_wgrad_supported(const WgradProblem& p);
 size_t blocked_bf16_wgrad_workspace(const WgradProblem& p);
 hipError_t blocked_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st);
 
+// bf16 backward-weight for dilations 1, 2, 4, 8, 16 and many taps: every consumer wave owns every fourth tap and
+// keeps the x operands that neighbouring taps and k-steps share in a register ring
+bool toeplitz_bf16_wgrad_supported(const WgradProblem& p);
+size_t toeplitz_bf16_wgrad_workspace(const WgradProblem& p);
+hipError_t toeplitz_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st);
+
 // bf16 forward / backward-data for many channels: implicit GEMM over (channel chunk, tap) with the weights
 // gathered into LDS stage by stage
 bool igemm_bf16_corr_supported(const CorrProblem& p);
