@@ -91,6 +91,13 @@ SMALL = [
     ("c64_k64_odd_P",     2, 64, 64, 1536, 9,  2,  7),     # odd padding: window origin one column early
     ("halo_gt_width",     2, 15, 15, 300,  51, 8,  200),   # halo (S-1)d = 400 exceeds W
     ("long_halo_short_W", 4, 4,  4,  64,   33, 16, 256),
+    # many taps at dilations 1, 2, 4, 8, 16: bf16 backward-weight keeps the shared x operands in a register ring
+    ("ring_two_tap_groups", 1, 20, 20, 3000, 100, 4, 13),  # S > 52: two tap groups
+    ("ring_S33_d1_c40",   3, 40, 24, 5000, 33, 1,  16),
+    ("ring_S33_d2_odd_P", 3, 40, 24, 5000, 33, 2,  31),
+    ("ring_S17_d8_odd_W", 2, 33, 17, 4001, 17, 8,  64),
+    ("ring_S27_d4_short", 1, 16, 16, 300,  27, 4,  0),     # a strip shorter than one unit of k-steps
+    ("ring_S70_d16",      1, 20, 20, 5000, 70, 16, 5),
 ]
 
 
