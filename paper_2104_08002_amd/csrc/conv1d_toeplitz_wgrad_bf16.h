@@ -186,7 +186,7 @@ __global__ __launch_bounds__(512, 1) void toeplitz_wgrad_bf16_kernel(TzArgs a) {
 
     // ---- first fill: the operands 0 .. SPAN-1 of the strip's first k-step ------------------------------------
     // Every thread helps: slot (copy, row, i) <-> x[c0 + row][qs + fl8p + phi + 8 i ..], staged in buffer 1.
-    {
+    auto first_fill = [&]() {
         const int ncopies = __builtin_popcount(a.phase_mask);
         const int total = ncopies * 16 * G::NXP;
         u32x4* pbuf = lds4 + a.stage_slots;
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(512, 1) void toeplitz_wgrad_bf16_kernel(TzArgs a) {
             }
             pbuf[ci * a.pcopy_slots + row * a.RSXP + i] = v;
         }
-    }
+    };
 
     if (consumer) {
         // ---- consumer side -----------------------------------------------------------------------
@@ -216,6 +216,7 @@ __global__ __launch_bounds__(512, 1) void toeplitz_wgrad_bf16_kernel(TzArgs a) {
         //   dy operand of filter block fb, k-step tt of a unit:  row 16 fb + li, slot 4 tt + kb
         //   x operand G = a t0 + Gc (t0: first k-step of the body):  copy of phase (E & 7), row li,
         //       slot hslot(Gc) + (E >> 3) + kb - (window origin >> 3),  E = E0 + v d + 4 q,  q = class of Gc
+        first_fill();
         unsigned ya[FB], xo[NQ], po[NQ];
         f32x4 acc[FB][NTW];
 #pragma unroll
@@ -426,6 +427,7 @@ __global__ __launch_bounds__(512, 1) void toeplitz_wgrad_bf16_kernel(TzArgs a) {
             Stage sb;
             prefetch(sa, 0);
             if (nunits > 1) prefetch(sb, 1);
+            first_fill();  // while the units' loads are on their way
             commit(sa, 0);
             if (nunits > 2) prefetch(sa, 2);
             __syncthreads();
@@ -446,6 +448,7 @@ __global__ __launch_bounds__(512, 1) void toeplitz_wgrad_bf16_kernel(TzArgs a) {
             }
         } else {
             prefetch(sa, 0);
+            first_fill();
             commit(sa, 0);
             if (nunits > 1) prefetch(sa, 1);
             __syncthreads();
