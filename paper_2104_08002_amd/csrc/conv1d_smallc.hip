@@ -378,7 +378,9 @@ hipError_t corr_f32_launch_f(const CorrProblem& p, const CorrF32Plan& pl, hipStr
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        static_cast<int>(pl.lds_bytes));
     if (e != hipSuccess) return e;
-    const int grid = pl.ntiles < kNumCU ? pl.ntiles : kNumCU;
+    // one workgroup per CU in total: the filter blocks (grid rows) share the strips of tiles between them
+    const int strips = cdiv(kNumCU, cdiv(p.M, 16));
+    const int grid = pl.ntiles < strips ? pl.ntiles : strips;
     hipLaunchKernelGGL(kern, dim3(grid, cdiv(p.M, 16)), dim3(512), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.LP4, pl.nbuf,
                        pl.raw_in_lds, pl.ncb, pl.vec_out);
     return hipGetLastError();
@@ -687,7 +689,9 @@ WgradF32Plan wgrad_f32_plan(const WgradProblem& p, bool blocks = false) {
         const long nc = static_cast<long>(p.N) * pl.chunks_per_row;
         if (nc > 0x7fffffffL) return pl;
         pl.nchunks = static_cast<int>(nc);
-        pl.grid = pl.nchunks < kNumCU ? pl.nchunks : kNumCU;
+        // one workgroup per CU in total: the block pairs (grid rows) share the strips of chunks between them
+        const int strips = blocks ? cdiv(kNumCU, cdiv(p.C, 16) * cdiv(p.K, 16)) : kNumCU;
+        pl.grid = pl.nchunks < strips ? pl.nchunks : strips;
         pl.lds_bytes = static_cast<size_t>(bytes);
         pl.fast = (p.W % 4 == 0) && (p.Q % 4 == 0) && (p.x_sn % 4 == 0) && (p.dy_sn % 4 == 0) && p.W >= 4 && p.Q >= 4 &&
                   (reinterpret_cast<uintptr_t>(p.x) % 16 == 0) && (reinterpret_cast<uintptr_t>(p.dy) % 16 == 0);

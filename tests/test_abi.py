@@ -105,8 +105,10 @@ def test_wide_layers_dispatch_to_blocked_mfma_kernels():
     # small channel counts at a dilation other than 8: bf16 backward-weight still runs on MFMA
     for d in (1, 2, 3, 4, 16):
         assert "mfma" in binding.conv1d_kernel_name(binding.PASS_BWD_WEIGHT, 4, 15, 15, 5000, 51, d, 25 * d, 1)
-    # fp32 backward-weight runs all 16 x 16 block pairs in one launch: one workspace slice per pair
+    # fp32 backward-weight runs all 16 x 16 block pairs in one launch, one workgroup per CU in total: the
+    # partial sums of all pairs together take what a single pair's 256 workgroups take
     wl = inputs.sweep_point(51, 8, "fp32")
     g = wl.geometry()
     small = (g[0], 16, 16) + tuple(g[3:])
-    assert binding.conv1d_bwd_weight_workspace_bytes(*g, 0) == 16 * binding.conv1d_bwd_weight_workspace_bytes(*small, 0)
+    assert binding.conv1d_bwd_weight_workspace_bytes(*g, 0) == binding.conv1d_bwd_weight_workspace_bytes(*small, 0)
+    assert binding.conv1d_bwd_weight_workspace_bytes(*g, 0) == 256 * 51 * 256 * 4
