@@ -393,37 +393,18 @@ constexpr Shape kShapes[] = {{1, 17}, {4, 9}};
 constexpr Shape kShapes[] = {{1, 5}, {1, 9}, {1, 17}, {1, 26}, {2, 9}, {2, 17}, {4, 5}, {4, 9}};
 #endif
 
-BlkPlan blk_plan(const WgradProblem& p) {
-    BlkPlan pl{};
-    pl.ok = false;
-    if (!p.bf16) return pl;
-    if (p.dw_sc != p.S || p.dw_sk != static_cast<long>(p.C) * p.S) return pl;  // writes the whole dw tensor
-    if (static_cast<long>(p.C) * p.W >= (1L << 30) || static_cast<long>(p.K) * p.Q >= (1L << 30)) return pl;
-    const long KCS = static_cast<long>(p.K) * p.C * p.S;
-    if (KCS >= (1L << 31)) return pl;
-    const int nfb = cdiv(p.K, 16);
+// Geometry of one candidate (shape, channel blocks per workgroup, chunk length); false if it does not fit.
+bool blk_geometry(const WgradProblem& p, int FB, int NT, int ncbw, int QC, BlkPlan& pl) {
     BlkArgs& a = pl.a;
-    // shapes in order of cost: MFMA slots, an LDS operand read counted as half an MFMA
-    constexpr int kNumShapes = sizeof(kShapes) / sizeof(kShapes[0]);
-    int order[kNumShapes];
-    double cost[kNumShapes];
-    for (int i = 0; i < kNumShapes; ++i) {
-        const Shape& sh = kShapes[i];
-        const double slots = static_cast<double>(cdiv(nfb, sh.FB)) * sh.FB * cdiv(p.S, sh.NT) * sh.NT;
-        cost[i] = slots * (1.0 + 0.5 * (sh.FB + sh.NT) / (sh.FB * sh.NT));
-        int j = i;
-        while (j > 0 && cost[order[j - 1]] > cost[i]) { order[j] = order[j - 1]; --j; }
-        order[j] = i;
-    }
-    for (int oi = 0; oi < kNumShapes; ++oi) {
-    pl.FB = kShapes[order[oi]].FB;
-    pl.NT = kShapes[order[oi]].NT;
-    a.ntg = cdiv(p.S, pl.NT);
-    a.nfg = cdiv(nfb, pl.FB);
+    const int nfb = cdiv(p.K, 16);
+    pl.FB = FB;
+    pl.NT = NT;
+    a.ntg = cdiv(p.S, NT);
+    a.nfg = cdiv(nfb, FB);
     // phases in use: delta = s*d - P - fl8(group) over all taps of all groups
     a.phase_mask = 0;
     for (int s = 0; s < p.S; ++s) {
-        const long s0 = s / pl.NT * pl.NT;
+        const long s0 = s / NT * NT;
         const long fl8 = ((s0 * p.d - p.P) >> 3) * 8;
         a.phase_mask |= 1u << ((static_cast<long>(s) * p.d - p.P - fl8) & 7);
     }
@@ -432,57 +413,91 @@ BlkPlan blk_plan(const WgradProblem& p) {
     for (int g = 0; g < 4; ++g)
         if ((a.phase_mask >> (2 * g)) & 3u) a.gmask |= 1u << g;
     const int ng = __builtin_popcount(a.gmask);
-    const long span = static_cast<long>(pl.NT - 1) * p.d + 7;  // largest delta
-    // as many channel blocks per workgroup as fit (every x row then serves FB filter blocks and every dy row
-    // ncbw channel blocks), then the longest chunk
-    for (int ncbw = p.C > 32 ? 4 : (p.C > 16 ? 2 : 1); ncbw >= 1; ncbw /= 2) {
-    for (int QC = 512; QC >= 128; QC /= 2) {
-        const int SY = QC / 8;
-        if (pl.FB * 16 * SY > 256 * kMaxY) continue;
-        const long NXS = SY + span / 8 + 1;
-        if ((16 * ncbw * NXS + 255) / 256 * ng > kMaxI) continue;
-        a.ncbw = ncbw;
-        a.ncb = cdiv(p.C, 16 * ncbw);
-        a.QC = QC;
-        a.nksw = QC / 32 * ncbw / 4;
-        a.RSY = SY + 1;
-        a.NXS = static_cast<int>(NXS);
-        a.RSX = a.NXS | 1;
-        a.xcopy_slots = 16 * ncbw * a.RSX;
-        a.ybuf_slots = pl.FB * 16 * a.RSY;
-        a.stage_slots = a.ybuf_slots + ncopies * a.xcopy_slots;
-        // + slack for the look-ahead reads of the last k-step (4 slots behind the last row)
-        size_t bytes = static_cast<size_t>(2 * a.stage_slots + 8) * 16;
-        const size_t red = static_cast<size_t>(4) * pl.FB * pl.NT * 1024;
-        if (bytes > static_cast<size_t>(kLdsBudget)) continue;
-        if (red > bytes) bytes = red;
-        pl.lds_bytes = bytes;
-        a.CPR = cdiv(p.Q, QC);
-        const long nc = static_cast<long>(p.N) * a.CPR;
-        if (nc > 0x7fffffffL) return pl;
-        a.nchunks = static_cast<int>(nc);
-        const int ncombos = a.nfg * a.ncb * a.ntg;
-        int nstrips = kNumCU / ncombos;
-        if (nstrips < 1) nstrips = 1;
-        if (nstrips > a.nchunks) nstrips = a.nchunks;
-        a.nstrips = nstrips;
-        const long grid = static_cast<long>(ncombos) * nstrips;
-        if (grid > 0x7fffffffL) return pl;
-        pl.grid = static_cast<int>(grid);
-        pl.tile = ncbw * pl.FB * pl.NT * 256;
-        a.x = static_cast<const unsigned short*>(p.x);
-        a.dy = static_cast<const unsigned short*>(p.dy);
-        a.ws = static_cast<float*>(p.ws);
-        a.C = p.C; a.K = p.K; a.W = p.W; a.Q = p.Q; a.S = p.S; a.d = p.d; a.P = p.P;
-        a.x_sn = p.x_sn; a.dy_sn = p.dy_sn;
-        pl.fast = (p.W % 2 == 0) && (p.Q % 2 == 0) && (p.x_sn % 2 == 0) && (p.dy_sn % 2 == 0) &&
-                  (reinterpret_cast<uintptr_t>(p.x) % 4 == 0) && (reinterpret_cast<uintptr_t>(p.dy) % 4 == 0);
-        pl.ok = true;
-        return pl;
-    }
-    }
-    }
-    return pl;
+    const long span = static_cast<long>(NT - 1) * p.d + 7;  // largest delta
+    const int SY = QC / 8;
+    if (FB * 16 * SY > 256 * kMaxY) return false;
+    const long NXS = SY + span / 8 + 1;
+    if ((16 * ncbw * NXS + 255) / 256 * ng > kMaxI) return false;
+    a.ncbw = ncbw;
+    a.ncb = cdiv(p.C, 16 * ncbw);
+    a.QC = QC;
+    a.nksw = QC / 32 * ncbw / 4;
+    a.RSY = SY + 1;
+    a.NXS = static_cast<int>(NXS);
+    a.RSX = a.NXS | 1;
+    a.xcopy_slots = 16 * ncbw * a.RSX;
+    a.ybuf_slots = FB * 16 * a.RSY;
+    a.stage_slots = a.ybuf_slots + ncopies * a.xcopy_slots;
+    // + slack for the look-ahead reads of the last k-step (4 slots behind the last row)
+    size_t bytes = static_cast<size_t>(2 * a.stage_slots + 8) * 16;
+    const size_t red = static_cast<size_t>(4) * FB * NT * 1024;
+    if (bytes > static_cast<size_t>(kLdsBudget)) return false;
+    if (red > bytes) bytes = red;
+    pl.lds_bytes = bytes;
+    a.CPR = cdiv(p.Q, QC);
+    const long nc = static_cast<long>(p.N) * a.CPR;
+    if (nc > 0x7fffffffL) return false;
+    a.nchunks = static_cast<int>(nc);
+    const int ncombos = a.nfg * a.ncb * a.ntg;
+    int nstrips = kNumCU / ncombos;
+    if (nstrips < 1) nstrips = 1;
+    if (nstrips > a.nchunks) nstrips = a.nchunks;
+    a.nstrips = nstrips;
+    const long grid = static_cast<long>(ncombos) * nstrips;
+    if (grid > 0x7fffffffL) return false;
+    pl.grid = static_cast<int>(grid);
+    pl.tile = ncbw * FB * NT * 256;
+    return true;
+}
+
+// Estimated time of a candidate in microseconds: MFMA slots (an LDS operand read counted as half an MFMA, the pipe
+// at 60 %), the bytes staged into LDS (served mostly by L2), and the partial tiles written and read once.
+double blk_cost(const WgradProblem& p, const BlkPlan& pl) {
+    const BlkArgs& a = pl.a;
+    const double ksteps = static_cast<double>(a.nchunks) * a.QC / 32;
+    const double slots = static_cast<double>(a.nfg) * pl.FB * a.ncb * a.ncbw * a.ntg * pl.NT;
+    const double reads = 1.0 + 0.5 * (pl.FB + pl.NT) / (pl.FB * pl.NT);
+    const int waves = pl.grid < kNumCU ? pl.grid : kNumCU;  // busy CUs
+    const double mfma_us = ksteps * slots * reads * 16 / (4.0 * waves) / 2400 / 0.6;
+    const int ncopies = __builtin_popcount(a.phase_mask);
+    const double staged = static_cast<double>(a.nchunks) * a.nfg * a.ncb * a.ntg * (pl.FB * 16 + ncopies * 16 * a.ncbw) * a.QC * 2;
+    const double stage_us = staged / 15e6;
+    const double ws_us = 2.0 * pl.grid * pl.tile * 4 / 4e6;
+    (void)p;
+    return mfma_us + stage_us + ws_us;
+}
+
+BlkPlan blk_plan(const WgradProblem& p) {
+    BlkPlan best{};
+    best.ok = false;
+    if (!p.bf16) return best;
+    if (p.dw_sc != p.S || p.dw_sk != static_cast<long>(p.C) * p.S) return best;  // writes the whole dw tensor
+    if (static_cast<long>(p.C) * p.W >= (1L << 30) || static_cast<long>(p.K) * p.Q >= (1L << 30)) return best;
+    if (static_cast<long>(p.K) * p.C * p.S >= (1L << 31)) return best;
+    double best_cost = 0;
+    for (const Shape& sh : kShapes)
+        for (int ncbw = p.C > 32 ? 4 : (p.C > 16 ? 2 : 1); ncbw >= 1; ncbw /= 2)
+            for (int QC = 512; QC >= 128; QC /= 2) {
+                BlkPlan pl{};
+                if (!blk_geometry(p, sh.FB, sh.NT, ncbw, QC, pl)) continue;
+                const double c = blk_cost(p, pl);
+                if (!best.ok || c < best_cost) {
+                    best = pl;
+                    best.ok = true;
+                    best_cost = c;
+                }
+                break;  // the longest chunk that fits
+            }
+    if (!best.ok) return best;
+    BlkArgs& a = best.a;
+    a.x = static_cast<const unsigned short*>(p.x);
+    a.dy = static_cast<const unsigned short*>(p.dy);
+    a.ws = static_cast<float*>(p.ws);
+    a.C = p.C; a.K = p.K; a.W = p.W; a.Q = p.Q; a.S = p.S; a.d = p.d; a.P = p.P;
+    a.x_sn = p.x_sn; a.dy_sn = p.dy_sn;
+    best.fast = (p.W % 2 == 0) && (p.Q % 2 == 0) && (p.x_sn % 2 == 0) && (p.dy_sn % 2 == 0) &&
+                (reinterpret_cast<uintptr_t>(p.x) % 4 == 0) && (reinterpret_cast<uintptr_t>(p.dy) % 4 == 0);
+    return best;
 }
 
 template <int FB, int NT>
