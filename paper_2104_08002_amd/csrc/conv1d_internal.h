@@ -95,6 +95,11 @@ hipError_t toeplitz_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st);
 bool igemm_bf16_corr_supported(const CorrProblem& p);
 hipError_t igemm_bf16_corr_launch(const CorrProblem& p, hipStream_t st);
 
+// the same for dilations 1, 2, 4, 8, 16 and 14 to 52 taps, while the weights of a filter group fit in LDS: resident
+// weight entries, input operands shared between taps and position blocks
+bool igemm_ring_bf16_corr_supported(const CorrProblem& p);
+hipError_t igemm_ring_bf16_corr_launch(const CorrProblem& p, hipStream_t st);
+
 // channel-blocked MFMA family
 bool igemm_corr_supported(const CorrProblem& p);
 hipError_t igemm_corr_launch(const CorrProblem& p, hipStream_t st);
