@@ -441,7 +441,7 @@ RgPlan rg_plan(const CorrProblem& p) {
 #else
     if (p.d != 1 && p.d != 2 && p.d != 4 && p.d != 8 && p.d != 16) return pl;
 #endif
-    if (p.S < 14 || p.S > 52) return pl;  // fewer taps: the staged kernel pads less
+    if (p.S < 5 || p.S > 52) return pl;
     if ((p.Win & 1) || (p.in_sn & 1) || (reinterpret_cast<uintptr_t>(p.in) & 3) || p.Win < 2) return pl;
     if (reinterpret_cast<uintptr_t>(p.wt) & 3) return pl;
     const bool fwd_mode = p.w_ss == 1 && p.w_sr == p.S && p.w_s0 == 0;
@@ -449,7 +449,7 @@ RgPlan rg_plan(const CorrProblem& p) {
     if (!fwd_mode && !bwd_mode) return pl;
     if (static_cast<long>(p.R) * p.Win >= (1L << 30)) return pl;
     if (static_cast<long>(p.M) * p.R * p.S >= (1L << 31) || p.M * p.w_sm >= (1L << 31) || p.R * p.w_sr >= (1L << 31)) return pl;
-    const int JT = p.S <= 20 ? 5 : (p.S <= 36 ? 9 : 13);
+    const int JT = p.S <= 8 ? 2 : (p.S <= 12 ? 3 : (p.S <= 20 ? 5 : (p.S <= 36 ? 9 : 13)));
 #ifdef CONV1D_DEV_FEW_KERNELS
     if (JT != 13) return pl;
 #endif
@@ -464,8 +464,11 @@ RgPlan rg_plan(const CorrProblem& p) {
     const long LP = (kTW + halo + a.delta + 1) / 2 * 2;
     const long LPS = LP + 8;
     const int planes = cdiv(p.R, 8);
-    for (int FB = p.M > 16 ? 2 : 1; FB >= 1; --FB)
-        for (int NG = 4; NG >= 1; NG /= 2) {
+    for (int FB = p.M > 16 ? 2 : 1; FB >= 1; --FB) {
+        // one filter block per workgroup pays off only with many taps per input operand (measured: C = K = 256,
+        // S = 9 ran 1.4 times slower than the staged kernel with its two filter blocks)
+        if (FB == 1 && p.M > 16 && JT < 5) break;
+        for (int NG = 8; NG >= 1; NG /= 2) {
             if (NG > 1 && NG / 2 >= planes) continue;
             const int ncc = cdiv(planes, NG);
             const long wres = static_cast<long>(ncc) * NG * JT * FB * kQS;
@@ -506,6 +509,7 @@ RgPlan rg_plan(const CorrProblem& p) {
             pl.ok = true;
             return pl;
         }
+    }
     return pl;
 }
 
@@ -529,6 +533,10 @@ hipError_t rg_launch_d(const RgPlan& pl, hipStream_t st) {
         case 209: return rg_launch<D, 2, 9>(pl, st);
         case 105: return rg_launch<D, 1, 5>(pl, st);
         case 205: return rg_launch<D, 2, 5>(pl, st);
+        case 103: return rg_launch<D, 1, 3>(pl, st);
+        case 203: return rg_launch<D, 2, 3>(pl, st);
+        case 102: return rg_launch<D, 1, 2>(pl, st);
+        case 202: return rg_launch<D, 2, 2>(pl, st);
 #endif
         default: return hipErrorInvalidValue;
     }

@@ -98,6 +98,10 @@ SMALL = [
     ("ring_S17_d8_odd_W", 2, 33, 17, 4001, 17, 8,  64),
     ("ring_S27_d4_short", 1, 16, 16, 300,  27, 4,  0),     # a strip shorter than one unit of k-steps
     ("ring_S70_d16",      1, 20, 20, 5000, 70, 16, 5),
+    # forward / backward-data with resident weights: few taps, odd padding, a filter count that is no multiple of 32
+    ("res_S12_d16",       3, 40, 24, 5000, 12, 16, 43),
+    ("res_S7_d4",         2, 72, 40, 1000, 7,  4,  12),
+    ("res_S45_d8_c128",   1, 128, 48, 2000, 45, 8, 77),
 ]
 
 
