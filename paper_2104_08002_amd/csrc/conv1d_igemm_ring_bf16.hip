@@ -55,6 +55,7 @@ struct RgArgs {
     long w_sm, w_sr, in_sn, out_sn;
     int tiles_per_row, nfg, nct, nteams;  // column blocks per row, filter groups, N * tiles_per_row, teams of nfg workgroups
     int NG, ncc;       // planes of 8 channels per stage, stages per tile
+    int NGW;           // planes per chunk of the weight prologue (divides NG * ncc)
     int LP, LPS;       // window positions staged (even), plane stride in slots
     int delta;         // (o0 - P) - window origin: 0 or 1
     int win_slots;     // NG * LPS
@@ -96,7 +97,6 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
     const int t_begin = static_cast<int>(static_cast<long>(team) * a.nct / a.nteams);
     const int t_end = static_cast<int>(static_cast<long>(team + 1) * a.nct / a.nteams);
     const int nstages = (t_end - t_begin) * a.ncc;
-    const int chunk_slots = a.NG * JT * FB * kQS;  // resident entries of one chunk (= the planes of one stage)
 
     const int wbase = a.wres_slots;  // the two window buffers follow the resident weights
 
@@ -184,14 +184,15 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
     }
 
     // ---- prologue: the workgroup's weight entries, gathered chunk by chunk (every thread helps) --------------
-    // The weights of a chunk are NU contiguous runs of the [K][C][S] tensor (forward: one run of 8 NG channels x
+    // The weights of a chunk (NGW planes of 8 channels) are NU contiguous runs of the [K][C][S] tensor (forward: one run of 8 NGW channels x
     // S taps per filter; backward-data: one run of 16 FB channels-of-dx x S taps per channel-of-dy).  The runs are
     // fetched as 16-byte pieces from 4-byte aligned addresses (two chunks ahead), parked raw in the LDS that
     // will later hold the windows, and the entries (8 channels of one tap per lane) are gathered with 2-byte LDS
     // reads.  Entries of padded taps, channels beyond R and filters beyond M stay zero.
     {
         for (int e = tid; e < a.wres_slots; e += 512) lds4[e] = u32x4{0u, 0u, 0u, 0u};
-        const int NWI = FB * 16 * a.NG * a.S;
+        const int NWI = FB * 16 * a.NGW * a.S;  // entries of one chunk (NGW planes)
+        const int nchunks = a.ncc * a.NG / a.NGW;
         const int NRP = a.NU * a.NPc;
         const int RSH = a.NPc * 8;  // halfwords per raw run
         const int cs = a.fwd_mode ? a.S : RSH;
@@ -207,7 +208,7 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
         for (int k = 0; k < kMaxWI; ++k) {
             const int e = min(tid + k * 512, NWI - 1);
             const int sx = e % a.S, mg = e / a.S;
-            const int g = mg % a.NG, ml = mg / a.NG;
+            const int g = mg % a.NGW, ml = mg / a.NGW;
             if (a.fwd_mode) {
                 wi_idx0[k] = ml * RSH + 8 * g * a.S + sx;
                 const int pm = static_cast<int>((ml * a.w_sm) & 1);
@@ -221,11 +222,11 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
             wi_ml[k] = ml;
         }
         const int m0 = fg * FB * 16;
-        auto chunk_base = [&](int cc) -> long { return static_cast<long>(m0) * a.w_sm + static_cast<long>(cc * a.NG * 8) * a.w_sr; };
+        auto chunk_base = [&](int cc) -> long { return static_cast<long>(m0) * a.w_sm + static_cast<long>(cc * a.NGW * 8) * a.w_sr; };
         constexpr int kDepth = 4;  // chunks whose raw pieces are in flight
         u32x4 rreg[kDepth][kMaxRP];
         auto raw_prefetch = [&](int cc, u32x4 (&rr)[kMaxRP]) {
-            const int r0 = cc * a.NG * 8;
+            const int r0 = cc * a.NGW * 8;
             const unsigned eb = static_cast<unsigned>(chunk_base(cc));  // the tensor has fewer than 2^31 elements
             const int umax = a.fwd_mode ? a.M - 1 - m0 : a.R - 1 - r0;
             const char* wb = reinterpret_cast<const char*>(a.wt);
@@ -252,9 +253,9 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
         };
         auto gather = [&](int cc) {
             const unsigned short* raw = reinterpret_cast<const unsigned short*>(lds4 + a.wres_slots + (cc & 1) * a.raw_slots);
-            u32x4* wgt = lds4 + cc * chunk_slots;
+            u32x4* wgt = lds4 + cc * (a.NGW * JT * FB * kQS);
             const int pb = static_cast<int>(chunk_base(cc) & 1);
-            const int r0 = cc * a.NG * 8;
+            const int r0 = cc * a.NGW * 8;
             unsigned v[kMaxWI][8];
 #pragma unroll
             for (int k = 0; k < kMaxWI; ++k)
@@ -277,17 +278,17 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
         // ahead, so that only the first chunks wait for memory
 #pragma unroll
         for (int i = 0; i < kDepth; ++i)
-            if (i < a.ncc) raw_prefetch(i, rreg[i]);
+            if (i < nchunks) raw_prefetch(i, rreg[i]);
         __syncthreads();  // the zeroes are in place
-        for (int c0 = 0; c0 < a.ncc; c0 += kDepth) {
+        for (int c0 = 0; c0 < nchunks; c0 += kDepth) {
 #pragma unroll
             for (int i = 0; i < kDepth; ++i) {
                 const int cc = c0 + i;
-                if (cc < a.ncc) {
+                if (cc < nchunks) {
                     raw_commit(cc & 1, rreg[i]);
                     __syncthreads();
                     gather(cc);
-                    if (cc + kDepth < a.ncc) raw_prefetch(cc + kDepth, rreg[i]);
+                    if (cc + kDepth < nchunks) raw_prefetch(cc + kDepth, rreg[i]);
                 }
             }
         }
@@ -474,17 +475,25 @@ RgPlan rg_plan(const CorrProblem& p) {
             const long wres = static_cast<long>(ncc) * NG * JT * FB * kQS;
             const long win = NG * LPS;
             if (cdiv(NG * (LP / 2), 256) > kMaxWT) continue;
-            if (cdiv(static_cast<long>(FB) * 16 * NG * p.S, 512) > kMaxWI) continue;
-            const int NU = fwd_mode ? FB * 16 : 8 * NG;
-            const long L = fwd_mode ? 8L * NG * p.S : static_cast<long>(FB) * 16 * p.S;
-            const long NPc = (2 * L + 2 + 15) / 16;
-            if (cdiv(NU * NPc, 512) > kMaxRP) continue;
+            // the prologue gathers the weights in chunks of NGW planes: as many as its per-thread task lists hold
+            int NGW = 0, NU = 0;
+            long NPc = 0;
+            for (int w = NG; w >= 1 && NGW == 0; w /= 2) {
+                if (cdiv(static_cast<long>(FB) * 16 * w * p.S, 512) > kMaxWI) continue;
+                NU = fwd_mode ? FB * 16 : 8 * w;
+                const long L = fwd_mode ? 8L * w * p.S : static_cast<long>(FB) * 16 * p.S;
+                NPc = (2 * L + 2 + 15) / 16;
+                if (cdiv(NU * NPc, 512) > kMaxRP) continue;
+                NGW = w;
+            }
+            if (NGW == 0) continue;
             // the two raw buffers of the prologue lie where the two window buffers will be
             const long behind = 2 * win > 2 * NU * NPc ? 2 * win : 2 * NU * NPc;
             const size_t bytes = static_cast<size_t>(wres + behind) * 16;
             if (bytes > static_cast<size_t>(kLdsBudget)) continue;
             pl.D = p.d; pl.FB = FB; pl.JT = JT;
             a.NG = NG;
+            a.NGW = NGW;
             a.ncc = ncc;
             a.LP = static_cast<int>(LP);
             a.LPS = static_cast<int>(LPS);
