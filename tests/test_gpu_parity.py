@@ -115,6 +115,49 @@ def test_small_geometries(binding, oracle, case, dtype, variant):
     _run_full(binding, oracle, wl, variant)
 
 
+# ---- base pointers that are only element-aligned: every kernel's unaligned path --------------------
+UNALIGNED = [
+    # name             N  C   K   W     S   d  P
+    ("una_genomics",   2, 15, 15, 3000, 51, 8, 200),
+    ("una_c64_S51",    1, 64, 64, 1536, 51, 8, 200),
+    ("una_c64_S9",     2, 64, 64, 1200, 9,  2, 8),
+    ("una_c40_S33_d4", 2, 40, 24, 2000, 33, 4, 64),
+]
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("case", UNALIGNED, ids=[c[0] for c in UNALIGNED])
+def test_element_aligned_pointers(binding, oracle, case, dtype):
+    """The ABI asks for element alignment only: shift every tensor by one element inside a larger allocation."""
+    import torch
+
+    name, N, C, K, W, S, d, P = case
+    wl = _mk(f"{name}_{dtype}", N, C, K, W, S, d, P, dtype, seed=inputs.BASE_SEED + 2000 + len(name))
+    data = inputs.make_inputs(wl)
+    dev = to_device(wl, data)
+
+    def shifted(t):
+        big = torch.empty(t.numel() + 1, dtype=t.dtype, device=t.device)
+        view = big[1:].view(t.shape)
+        view.copy_(t)
+        assert view.data_ptr() % 16 != 0 and view.is_contiguous()
+        return view
+
+    x, w, dy = shifted(dev["x"]), shifted(dev["w"]), shifted(dev["dy"])
+    y = shifted(torch.empty((N, K, wl.Q), dtype=torch.float32, device="cuda"))
+    dx = shifted(torch.empty((N, C, W), dtype=torch.float32, device="cuda"))
+    dw = shifted(torch.empty((K, C, S), dtype=torch.float32, device="cuda"))
+    binding.conv1d_fwd(x, w, d, P, out=y)
+    binding.conv1d_bwd_data(dy, w, W, d, P, out=dx)
+    binding.conv1d_bwd_weight(x, dy, S, d, P, out=dw)
+    torch.cuda.synchronize()
+    got = {"fwd": y.cpu().numpy(), "bwd_data": dx.cpu().numpy(), "bwd_weight": dw.cpu().numpy()}
+    errs = check_full(oracle, wl, data, got)
+    print(wl.name, errs, flush=True)
+    for p, e in errs.items():
+        assert e <= TOL[wl.dtype], (wl.name, p, e)
+
+
 # ---- genomics at full size, the configuration the benchmark times: whole-output comparison ------
 @pytest.mark.parametrize("wl", [inputs.GENOMICS_FP32, inputs.GENOMICS_BF16], ids=lambda w: w.name)
 def test_genomics_full_size(binding, oracle, wl):
