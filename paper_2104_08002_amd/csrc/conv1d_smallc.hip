@@ -623,7 +623,7 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
 // blockIdx.y numbers the (filter block, channel block) pairs of a batched launch (K, C: totals).
 __global__ __launch_bounds__(256) void smallc_wgrad_reduce_kernel(const float* __restrict__ ws, float* __restrict__ dw, int K, int C, int S, long dw_sk,
                                                                   long dw_sc, int nwg) {
-    __shared__ float part[16][17];
+    __shared__ f32x4 part[16][17];
     {
         const int ncbp = (C + 15) >> 4;
         const int pair = blockIdx.y, kbi = pair / ncbp, cbi = pair - kbi * ncbp;
@@ -632,25 +632,29 @@ __global__ __launch_bounds__(256) void smallc_wgrad_reduce_kernel(const float* _
         K = min(16, K - 16 * kbi);
         C = min(16, C - 16 * cbi);
     }
+    // a block of 16 x 16 threads handles 64 consecutive tile elements: thread (grp, el) adds its group's
+    // workgroups for the 4 elements 4 el .. 4 el + 3 with 16-byte loads (256-byte row segments per group)
     const int el = threadIdx.x & 15, grp = threadIdx.x >> 4;
-    const int e = blockIdx.x * 16 + el;  // index into one workgroup's S*256 partial tile
+    const int e = blockIdx.x * 64 + 4 * el;  // index into one workgroup's S*256 partial tile (a multiple of 64)
     const int total = S * 256;
     const int per = (nwg + 15) / 16;
     const int g0 = grp * per, g1 = min(nwg, g0 + per);
-    float t = 0.f;
-    if (e < total) {
+    f32x4 t = f32x4{0.f, 0.f, 0.f, 0.f};
+    {
         const float* src = ws + e;
 #pragma unroll 8
-        for (int g = g0; g < g1; ++g) t += src[static_cast<long>(g) * total];
+        for (int g = g0; g < g1; ++g) t += *reinterpret_cast<const f32x4*>(src + static_cast<long>(g) * total);
     }
     part[grp][el] = t;
     __syncthreads();
-    if (grp == 0 && e < total) {
-        float sum = part[0][el];
+    if (grp == 0) {
+        f32x4 sum = part[0][el];
 #pragma unroll
         for (int i = 1; i < 16; ++i) sum += part[i][el];
-        const int s = e >> 8, k = (e >> 4) & 15, c = e & 15;
-        if (k < K && c < C) dw[k * dw_sk + c * dw_sc + s] = sum;
+        const int s = e >> 8, k = (e >> 4) & 15, c0 = e & 15;  // the 4 elements are 4 adjacent channels
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (k < K && c0 + j < C) dw[k * dw_sk + (c0 + j) * dw_sc + s] = sum[j];
     }
 }
 
@@ -718,7 +722,7 @@ hipError_t wgrad_f32_launch_nt(const WgradProblem& p, const WgradF32Plan& pl, hi
 hipError_t smallc_wgrad_reduce_launch(const float* ws, float* dw, int K, int C, int S, long dw_sk, long dw_sc, int nwg,
                                       hipStream_t st) {
     const int pairs = cdiv(K, 16) * cdiv(C, 16);
-    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(cdiv(S * 256, 16), pairs), dim3(256), 0, st, ws, dw, K, C, S, dw_sk, dw_sc, nwg);
+    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(S * 4, pairs), dim3(256), 0, st, ws, dw, K, C, S, dw_sk, dw_sc, nwg);
     return hipGetLastError();
 }
 
