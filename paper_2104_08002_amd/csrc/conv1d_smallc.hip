@@ -493,25 +493,28 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
         dst[1] = f32x2{v[2], v[3]};
     };
     Slot slot[MAXS];
-    f32x4 pre[FAST ? MAXS : 1];
+    // Two prefetch sets: the loads of a chunk are issued two chunks before it is written to LDS (with few taps a
+    // chunk is shorter than the memory latency under load).  Set (chunk - c_begin) & 1 holds a chunk.
+    constexpr int NPRE = (FAST && NT <= 5) ? 2 : 1;  // long chunks (many taps) need one set only
+    f32x4 pre[NPRE][FAST ? MAXS : 1];
     if (!consumer) {
 #pragma unroll
         for (int k = 0; k < MAXS; ++k) slot[k] = make_slot(k, min(rtid + k * 256, nslots - 1));
     }
-    auto prefetch_chunk = [&](int chunk) {
+    auto prefetch_chunk = [&](int chunk, f32x4 (&pr)[FAST ? MAXS : 1]) {
         if constexpr (FAST) {
             const Origin o = origin(chunk);
 #pragma unroll
-            for (int k = 0; k < MAXS; ++k) pre[k] = fetch(o, k, slot[k]);
+            for (int k = 0; k < MAXS; ++k) pr[k] = fetch(o, k, slot[k]);
         }
     };
-    auto commit_chunk = [&](int b, int chunk) {
+    auto commit_chunk = [&](int b, int chunk, const f32x4 (&pr)[FAST ? MAXS : 1]) {
         const Origin o = origin(chunk);
 #pragma unroll
         for (int k = 0; k < MAXS; ++k) {
             if (rtid + k * 256 < nslots) {
                 if constexpr (FAST) {
-                    commit(b, o, k, slot[k], pre[k]);
+                    commit(b, o, k, slot[k], pr[k]);
                 } else {
                     commit(b, o, k, slot[k], fetch(o, k, slot[k]));
                 }
@@ -530,9 +533,15 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
 
     // prologue: producers stage the first chunk and start on the second
     if (!consumer && c_begin < c_end) {
-        prefetch_chunk(c_begin);
-        commit_chunk(0, c_begin);
-        if (c_begin + 1 < c_end) prefetch_chunk(c_begin + 1);
+        prefetch_chunk(c_begin, pre[0]);
+        if constexpr (NPRE == 2) {
+            if (c_begin + 1 < c_end) prefetch_chunk(c_begin + 1, pre[1]);
+            commit_chunk(0, c_begin, pre[0]);
+            if (c_begin + 2 < c_end) prefetch_chunk(c_begin + 2, pre[0]);
+        } else {
+            commit_chunk(0, c_begin, pre[0]);
+            if (c_begin + 1 < c_end) prefetch_chunk(c_begin + 1, pre[0]);
+        }
     }
     __syncthreads();
 
@@ -548,59 +557,74 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
             int bi[NT];
 #pragma unroll
             for (int i = 0; i < NT; ++i) bi[i] = b * stage_floats + 16 * LQS + li * LXS + kb + (cw + 4 * i) * p.d + psh;
-            // two k-steps per iteration with ping-pong operand registers: the LDS reads of the next k-step
-            // are issued between the MFMAs of the current one.  The reads of the last iteration run 4
-            // columns past the chunk (into row padding / the slack after the last row) and are discarded.
-            float a0 = lds[ai], b0[NT], a1, b1[NT];
+            // NS k-steps per iteration with a ring of NS operand register sets: the LDS reads of k-step t + NS - 1
+            // are issued between the MFMAs of k-step t.  With few taps per wave a k-step is only 2 - 3 MFMAs
+            // long, so the reads have to run three k-steps ahead to cover the LDS latency.  The reads of the
+            // last iteration run up to 4 (NS - 1) columns past the chunk (into row padding / the slack after the
+            // last row) and are discarded.
+            constexpr int NS = NT <= 3 ? 4 : 2;
+            float av[NS], bv[NS][NT];
 #pragma unroll
-            for (int i = 0; i < NT; ++i) b0[i] = lds[bi[i]];
-            for (int t = 0; t < QC; t += 8) {
-                a1 = lds[ai + 4];
+            for (int j = 0; j < NS - 1; ++j) {
+                av[j] = lds[ai + 4 * j];
 #pragma unroll
-                for (int i = 0; i < NT; ++i) {
-                    b1[i] = lds[bi[i] + 4];
-                    acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0[i], acc[i], 0, 0, 0);
+                for (int i = 0; i < NT; ++i) bv[j][i] = lds[bi[i] + 4 * j];
+            }
+            for (int t = 0; t < QC; t += 4 * NS) {
+#pragma unroll
+                for (int j = 0; j < NS; ++j) {
+                    constexpr int kAhead = NS - 1;
+                    const int nx = (j + kAhead) % NS;
+                    av[nx] = lds[ai + 4 * (j + kAhead)];
+#pragma unroll
+                    for (int i = 0; i < NT; ++i) {
+                        bv[nx][i] = lds[bi[i] + 4 * (j + kAhead)];
+                        acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[j], bv[j][i], acc[i], 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int i = 0; i < NT; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read ...
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // ... then one MFMA
+                    }
+                    // Keep the consumed operands live to the end of the k-step: otherwise the register of the
+                    // operand an MFMA has just been issued with is handed to the very next LDS read, and that
+                    // read cannot issue until the MFMA has finished fetching its sources.
+#pragma unroll
+                    for (int i = 0; i < NT; ++i) asm volatile("" ::"v"(bv[j][i]));
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+                ai += 4 * NS;
 #pragma unroll
-                for (int i = 0; i < NT; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read ...
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // ... then one MFMA
-                }
-                // Keep the consumed operands live to the end of the k-step: otherwise the register of the
-                // operand an MFMA has just been issued with is handed to the very next LDS read, and that
-                // read cannot issue until the MFMA has finished fetching its sources.
-#pragma unroll
-                for (int i = 0; i < NT; ++i) asm volatile("" ::"v"(b0[i]));
-                __builtin_amdgcn_sched_barrier(0);
-                a0 = lds[ai + 8];
-#pragma unroll
-                for (int i = 0; i < NT; ++i) {
-                    b0[i] = lds[bi[i] + 8];
-                    acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1[i], acc[i], 0, 0, 0);
-                }
-#pragma unroll
-                for (int i = 0; i < NT; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-                }
-#pragma unroll
-                for (int i = 0; i < NT; ++i) asm volatile("" ::"v"(b1[i]));
-                __builtin_amdgcn_sched_barrier(0);
-                ai += 8;
-#pragma unroll
-                for (int i = 0; i < NT; ++i) bi[i] += 8;
+                for (int i = 0; i < NT; ++i) bi[i] += 4 * NS;
             }
             __syncthreads();
         }
     } else {
-        int k = 0;
-        for (int chunk = c_begin; chunk < c_end; ++chunk, ++k) {
-            const int b = k & 1;
-            if (chunk + 1 < c_end) {
-                commit_chunk(b ^ 1, chunk + 1);
-                if (chunk + 2 < c_end) prefetch_chunk(chunk + 2);
+        if constexpr (NPRE == 2) {
+            for (int chunk = c_begin; chunk < c_end; chunk += 2) {
+                if (chunk + 1 < c_end) {
+                    commit_chunk(1, chunk + 1, pre[1]);
+                    if (chunk + 3 < c_end) prefetch_chunk(chunk + 3, pre[1]);
+                }
+                __syncthreads();
+                if (chunk + 1 < c_end) {
+                    if (chunk + 2 < c_end) {
+                        commit_chunk(0, chunk + 2, pre[0]);
+                        if (chunk + 4 < c_end) prefetch_chunk(chunk + 4, pre[0]);
+                    }
+                    __syncthreads();
+                }
             }
-            __syncthreads();
+        } else {
+            int k = 0;
+            for (int chunk = c_begin; chunk < c_end; ++chunk, ++k) {
+                const int b = k & 1;
+                if (chunk + 1 < c_end) {
+                    commit_chunk(b ^ 1, chunk + 1, pre[0]);
+                    if (chunk + 2 < c_end) prefetch_chunk(chunk + 2, pre[0]);
+                }
+                __syncthreads();
+            }
         }
     }
     if (consumer) {
@@ -683,7 +707,7 @@ WgradF32Plan wgrad_f32_plan(const WgradProblem& p, bool blocks = false) {
     auto pad = [](long v) { return (v + 31) / 32 * 32 + 2; };
     for (int QC = 256; QC >= 64; QC /= 2) {  // the largest chunk whose two stages fit in LDS
         const long LQS = pad(QC), LXS = pad(QC + halo);
-        const long bytes = 2 * 16 * (LQS + LXS) * 4 + 64;  // + slack for the discarded look-ahead reads
+        const long bytes = 2 * 16 * (LQS + LXS) * 4 + 128;  // + slack for the discarded look-ahead reads
         if (bytes > kLdsBudget) continue;
         pl.QC = QC;
         pl.LQS = static_cast<int>(LQS);
