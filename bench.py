@@ -4,8 +4,8 @@
 A "step" is one forward + one backward-data + one backward-weight pass of the layer on the
 genomics-shaped workload (N=16, C=K=15, W=60000, S=51, d=8, same padding), inputs resident in
 HBM.  Prints ONE JSON line:  metric/value = TFLOP/s over the whole step (3 passes x 2*N*C*K*S*Q
-nominal FLOPs), plus per-pass figures, a roofline object for the slowest kernel (timed with
-HIP events on the launch stream) and the FP64 oracle timed on the host cores.
+nominal FLOPs), plus per-pass figures, a roofline object for the kernel with the largest share of the step
+(timed with HIP events on the launch stream) and the FP64 oracle timed on the host cores.
 """
 from __future__ import annotations
 
@@ -186,17 +186,26 @@ def main() -> int:
             "tflops": round(tf, 2), "frac_mfma_peak": round(tf / PEAK[wl.dtype], 4),
             "algorithmic_GBps": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
         }
-    dom = max(run_passes, key=lambda p: per_pass[p]["avg_us"])
+    # The dominant kernel is the one with the largest share of the step.  fwd and bwd_data are launches of the same
+    # kernel (one launch per pass); bwd_weight is its own kernel plus the small second stage.
+    share = {}
+    for p in run_passes:
+        share.setdefault(per_pass[p]["kernel"], []).append(p)
+    dom_kernel = max(share, key=lambda k: sum(per_pass[p]["avg_us"] for p in share[k]))
+    dom_passes = share[dom_kernel]
+    dom = dom_passes[0]
+    avg_us = sum(per_pass[p]["avg_us"] for p in dom_passes) / len(dom_passes)
+    tf = wl.flops / (avg_us * 1e-6) / 1e12
+    alg_bytes = sum(algorithmic_bytes(wl, p) for p in dom_passes) / len(dom_passes)
+    gbs = alg_bytes / (avg_us * 1e-6) / 1e9
     # which roof bounds the dominant kernel: time at MFMA peak vs time at HBM peak for its algorithmic work
     t_mfma = wl.flops / (PEAK[wl.dtype] * 1e12)
-    t_hbm = algorithmic_bytes(wl, dom) / (HBM_PEAK_GBS * 1e9)
+    t_hbm = alg_bytes / (HBM_PEAK_GBS * 1e9)
     if t_hbm > t_mfma:
-        roof = {"bound": "hbm", "achieved": per_pass[dom]["algorithmic_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": per_pass[dom]["frac_hbm_peak"]}
+        roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)}
     else:
-        roof = {"bound": "mfma", "achieved": per_pass[dom]["tflops"], "peak": PEAK[wl.dtype], "unit": "TFLOP/s",
-                "frac": per_pass[dom]["frac_mfma_peak"]}
-    roof.update({"kernel": per_pass[dom]["kernel"], "pass": dom, "avg_us": per_pass[dom]["avg_us"],
+        roof = {"bound": "mfma", "achieved": round(tf, 2), "peak": PEAK[wl.dtype], "unit": "TFLOP/s", "frac": round(tf / PEAK[wl.dtype], 4)}
+    roof.update({"kernel": dom_kernel, "passes": dom_passes, "launches_per_step": len(dom_passes), "avg_us": round(avg_us, 2),
                  "traffic": stored_traffic(wl.name, dom)})
 
     cpu = None

@@ -30,7 +30,6 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int kLdsBudget = 160 * 1024;
 constexpr int kNumCU = 256;
-constexpr int kWaves = 4;
 constexpr unsigned kPermLo = 0x05040100u;  // {b.lo16, a.lo16} -> a.lo | b.lo << 16
 constexpr unsigned kPermHi = 0x07060302u;  // {b.hi16, a.hi16} -> a.hi | b.hi << 16
 
