@@ -187,6 +187,22 @@ def test_wide_full_size_sampled(binding, oracle):
     _run_sampled(binding, oracle, inputs.WIDE_BF16)
 
 
+# ---- long segments (the paper's 600000-wide inputs, Section 4.5.3): one sample, sampled outputs -----
+LONG = [
+    # name                N  C   K   W       S   d  P
+    ("long_genomics",     1, 15, 15, 600000, 51, 8, 200),
+    ("long_c64_S17_d4",   1, 64, 64, 300000, 17, 4, 32),
+]
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("case", LONG, ids=[c[0] for c in LONG])
+def test_long_segments_sampled(binding, oracle, case, dtype):
+    name, N, C, K, W, S, d, P = case
+    wl = _mk(f"{name}_{dtype}", N, C, K, W, S, d, P, dtype, seed=inputs.BASE_SEED + 3000 + len(name))
+    _run_sampled(binding, oracle, wl)
+
+
 # ---- the sweep and wide shapes at a width the oracle finishes whole ------------------------------
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 @pytest.mark.parametrize("S,d", [(5, 1), (9, 16), (17, 2), (33, 4), (51, 8), (51, 16)])
