@@ -1,438 +1,23 @@
-// Forward / backward-data passes (Eq. 2; Section 3.2) for bfloat16 inputs, many channels (R or M > 16) and
-// dilations 1, 2, 4, 8, 16: implicit GEMM with resident weights and shared input operands.
-//
-//   out[n][m][o] = sum_r sum_s in[n][r][o + s*d - P] * wt(m, r, s)
-//
-// One v_mfma_f32_16x16x32_bf16 contracts four k-blocks (8 channels of one tap each): lane (li, kb) holds filter li
-// (A operand) or output column li (B operand) of k-block kb = tap 4 jj + kb of tap group jj, for one plane of 8
-// channels.  Two things differ from the staged implicit GEMM of conv1d_igemm_bf16.hip:
-//
-// Resident weights.  A workgroup owns FB blocks of 16 filters and keeps their operand entries for ALL channels and
-// taps in LDS for its whole life (entry (plane, tap group, filter block, lane) = 16 bytes); they are gathered
-// once, in the prologue, from the [K][C][S] tensor as it is.  The producers then only stage input windows.
-//
-// Shared input operands.  The B operand of (position block t, tap group jj) starts at window position
-// 16 t + 4 d jj (+ li + kb d): with u = gcd(16, 4 d), alpha = 16 / u and beta = 4 d / u it is operand number
-// G = alpha t + beta jj.  A consumer wave owns 8 position blocks and walks G upwards: every operand is read from
-// LDS once and feeds all (t, jj) on its line, acc[t] += W[jj] * X[G]; the weight operands of a plane sit in
-// registers and are replaced by the next plane's as they fall out of use.  LDS operand reads per MFMA drop from
-// 0.62 to 0.2 - 0.4.
-//
-// Tile = 16 FB filters x 512 output columns of one sample; consumer wave v takes the columns [128 v, 128 v + 128).
-// The reduction runs in stages of NG planes; the window of a stage is double-buffered as [plane][position] 16-byte
-// slots (8 channels at one position).  Workgroup = 8 waves, persistent over a strip of tiles: waves 0-3 consume,
-// waves 4-7 stage the windows of the next stages; one workgroup barrier per stage.  Workgroups of the filter
-// groups of one strip form a team on one XCD (the window is fetched from HBM once).
-// Taps beyond S (the last tap group) have zero weights.
-#include "conv1d_internal.h"
+// Forward / backward-data, bfloat16, many channels, dilations 1, 2, 4, 8, 16: launch plan and dispatch of the
+// resident-weight kernels (the kernel template and its description are in the header; every dilation is
+// instantiated in a translation unit of its own).
+#include "conv1d_igemm_ring_bf16.h"
 
 namespace conv1d {
 
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+using rg::RgArgs;
+using rg::RgPlan;
+using rg::kLdsBudget;
+using rg::kNumCU;
+using rg::kMaxWT;
+using rg::kMaxWI;
+using rg::kMaxRP;
+using rg::kQS;
 
-constexpr int kLdsBudget = 160 * 1024;
-constexpr int kNumCU = 256;
-constexpr int kT = 8;             // position blocks of 16 per consumer wave
-constexpr int kTW = 4 * kT * 16;  // output columns per tile
-constexpr int kMaxWT = 5;         // window tasks per producer thread
-constexpr int kMaxWI = 4;         // weight entries per thread and chunk (prologue, 512 threads)
-constexpr int kMaxRP = 3;         // raw 16-byte pieces per thread and chunk
-constexpr int kQS = 68;           // slots per (plane, tap group, filter block): 4 k-blocks x 17
-constexpr unsigned kPermLo = 0x05040100u;  // {b.lo16, a.lo16} -> a.lo | b.lo << 16
-constexpr unsigned kPermHi = 0x07060302u;  // {b.hi16, a.hi16} -> a.hi | b.hi << 16
-
-__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
-
-struct RgArgs {
-    const unsigned short* in;
-    const unsigned short* wt;
-    float* out;
-    int N, R, M, Win, Wout, S, P;
-    long w_sm, w_sr, in_sn, out_sn;
-    int tiles_per_row, nfg, nct, nteams;  // column blocks per row, filter groups, N * tiles_per_row, teams of nfg workgroups
-    int NG, ncc;       // planes of 8 channels per stage, stages per tile
-    int NGW;           // planes per chunk of the weight prologue (divides NG * ncc)
-    int LP, LPS;       // window positions staged (even), plane stride in slots
-    int delta;         // (o0 - P) - window origin: 0 or 1
-    int win_slots;     // NG * LPS
-    int wres_slots;    // ncc * NG * JT * FB * kQS: the resident weight entries
-    int fwd_mode;      // weights are [m][r][s] (forward) or [r][m][S-1-s] (backward-data)
-    int NU, NPc;       // raw runs per chunk, 16-byte pieces per run
-    long su;           // elements between the starts of consecutive runs
-    long wbytes;       // size of the weight tensor
-    int raw_slots;     // NU * NPc
-    int vec_out;       // output rows and the base pointer are 16-byte aligned
-};
-
-// operand geometry of a dilation
-template <int D>
-struct Ring {
-    static constexpr int U = D == 1 ? 4 : (D == 2 ? 8 : 16);  // positions between consecutive operands
-    static constexpr int ALPHA = 16 / U;
-    static constexpr int BETA = 4 * D / U;
-    static constexpr int XD = 5;  // input operands in flight: the reads run 4 steps (8 - 32 MFMAs) ahead of their use
-};
-
-template <int D, int FB, int JT>
-__global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
-    using G_ = Ring<D>;
-    constexpr int ALPHA = G_::ALPHA, BETA = G_::BETA, XD = G_::XD;
-    constexpr int GMAX = ALPHA * (kT - 1) + BETA * (JT - 1);
-    extern __shared__ u32x4 lds4[];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const bool consumer = wave < 4;
-    const int cw = wave & 3;
-    const int rtid = tid & 255;
-    const int li = lane & 15;
-    const int kb = lane >> 4;
-
-    const int lid = xcd_logical_id(blockIdx.x, gridDim.x);
-    const int team = lid / a.nfg, fg = lid - team * a.nfg;
-    const int t_begin = static_cast<int>(static_cast<long>(team) * a.nct / a.nteams);
-    const int t_end = static_cast<int>(static_cast<long>(team + 1) * a.nct / a.nteams);
-    const int nstages = (t_end - t_begin) * a.ncc;
-
-    const int wbase = a.wres_slots;  // the two window buffers follow the resident weights
-
-    // ---- window staging (producer waves): tables, and the first two windows requested before the prologue ----
-    // Window task (plane g, pair i): positions G0 + 2i, G0 + 2i + 1 of the 8 channels of plane g; 8 dword
-    // loads (row starts, the window origin and Win are even) from clamped addresses, two slots out.
-    const int LP2 = a.LP >> 1;
-    const int NWT = a.NG * LP2;
-    int wt_plane8[kMaxWT], wt_pair[kMaxWT], wt_dst[kMaxWT];
-    unsigned wt_voff[kMaxWT];
-#pragma unroll
-    for (int k = 0; k < kMaxWT; ++k) {
-        const int e = min(rtid + k * 256, NWT - 1);
-        const int g = e / LP2;
-        wt_plane8[k] = 8 * g;
-        wt_pair[k] = e - g * LP2;
-        wt_voff[k] = 2u * (static_cast<unsigned>(wt_plane8[k]) * static_cast<unsigned>(a.Win) + 2u * static_cast<unsigned>(wt_pair[k]));
-        wt_dst[k] = g * a.LPS + 2 * wt_pair[k];
-    }
-    struct Geo {
-        int n, G0, r0;  // sample, window origin, first channel of the stage
-    };
-    auto geo = [&](int st) -> Geo {
-        const int ct = t_begin + st / a.ncc, cc = st - (st / a.ncc) * a.ncc;
-        Geo g;
-        g.n = ct / a.tiles_per_row;
-        g.G0 = (ct - g.n * a.tiles_per_row) * kTW - a.P - a.delta;
-        g.r0 = cc * a.NG * 8;
-        return g;
-    };
-    auto interior = [&](const Geo& g) { return g.G0 >= 0 && g.G0 + a.LP <= a.Win && g.r0 + 8 * a.NG <= a.R; };
-    unsigned wreg[2][kMaxWT][8];
-    auto window_prefetch = [&](const Geo& g, unsigned (&wr)[kMaxWT][8]) {
-        const char* ib = reinterpret_cast<const char*>(a.in + static_cast<long>(g.n) * a.in_sn);
-        const unsigned rowb = static_cast<unsigned>(a.Win) * 2u;
-        if (interior(g)) {
-            const char* rb = ib + 2 * (static_cast<long>(g.r0) * a.Win + g.G0);  // uniform
-#pragma unroll
-            for (int k = 0; k < kMaxWT; ++k)
-                if (k * 256 < NWT) {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) wr[k][j] = *reinterpret_cast<const unsigned*>(rb + j * static_cast<long>(rowb) + wt_voff[k]);
-                }
-        } else {
-#pragma unroll
-            for (int k = 0; k < kMaxWT; ++k)
-                if (k * 256 < NWT) {
-                    int pos = g.G0 + 2 * wt_pair[k];
-                    pos = pos < 0 ? 0 : (pos > a.Win - 2 ? a.Win - 2 : pos);
-                    const unsigned offmax = static_cast<unsigned>((a.R - 1) * a.Win + pos) * 2u;
-                    unsigned off = static_cast<unsigned>((g.r0 + wt_plane8[k]) * a.Win + pos) * 2u;
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        wr[k][j] = *reinterpret_cast<const unsigned*>(ib + min(off, offmax));
-                        off += rowb;
-                    }
-                }
-        }
-    };
-    auto window_commit = [&](const Geo& g, int b, unsigned (&wr)[kMaxWT][8]) {
-        u32x4* win = lds4 + wbase + b * a.win_slots;
-        const bool inner = interior(g);
-#pragma unroll
-        for (int k = 0; k < kMaxWT; ++k)
-            if (rtid + k * 256 < NWT) {
-                const int pos = g.G0 + 2 * wt_pair[k];
-                const bool ok = inner || (pos >= 0 && pos < a.Win);  // a pair is inside or outside the row as a whole
-                u32x4 ev, od;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const unsigned lo = ok ? wr[k][2 * q] : 0u, hi = ok ? wr[k][2 * q + 1] : 0u;
-                    ev[q] = __builtin_amdgcn_perm(hi, lo, kPermLo);
-                    od[q] = __builtin_amdgcn_perm(hi, lo, kPermHi);
-                }
-                u32x4* dst = win + wt_dst[k];
-                dst[0] = ev;
-                dst[1] = od;
-            }
-    };
-    Geo g0 = geo(0), g1 = geo(1 < nstages ? 1 : 0), g2 = g1;
-    if (!consumer) {
-        __builtin_amdgcn_s_setprio(3);
-        if (nstages > 0) window_prefetch(g0, wreg[0]);
-        if (nstages > 1) window_prefetch(g1, wreg[1]);
-    }
-
-    // ---- prologue: the workgroup's weight entries, gathered chunk by chunk (every thread helps) --------------
-    // The weights of a chunk (NGW planes of 8 channels) are NU contiguous runs of the [K][C][S] tensor (forward: one run of 8 NGW channels x
-    // S taps per filter; backward-data: one run of 16 FB channels-of-dx x S taps per channel-of-dy).  The runs are
-    // fetched as 16-byte pieces from 4-byte aligned addresses (two chunks ahead), parked raw in the LDS that
-    // will later hold the windows, and the entries (8 channels of one tap per lane) are gathered with 2-byte LDS
-    // reads.  Entries of padded taps, channels beyond R and filters beyond M stay zero.
-    {
-        for (int e = tid; e < a.wres_slots; e += 512) lds4[e] = u32x4{0u, 0u, 0u, 0u};
-        const int NWI = FB * 16 * a.NGW * a.S;  // entries of one chunk (NGW planes)
-        const int nchunks = a.ncc * a.NG / a.NGW;
-        const int NRP = a.NU * a.NPc;
-        const int RSH = a.NPc * 8;  // halfwords per raw run
-        const int cs = a.fwd_mode ? a.S : RSH;
-        int rp_u[kMaxRP], rp_q[kMaxRP];
-#pragma unroll
-        for (int k = 0; k < kMaxRP; ++k) {
-            const int e = min(tid + k * 512, NRP - 1);
-            rp_u[k] = e / a.NPc;
-            rp_q[k] = e - rp_u[k] * a.NPc;
-        }
-        int wi_idx0[kMaxWI], wi_lds[kMaxWI], wi_g8[kMaxWI], wi_par[kMaxWI], wi_ml[kMaxWI];
-#pragma unroll
-        for (int k = 0; k < kMaxWI; ++k) {
-            const int e = min(tid + k * 512, NWI - 1);
-            const int sx = e % a.S, mg = e / a.S;
-            const int g = mg % a.NGW, ml = mg / a.NGW;
-            if (a.fwd_mode) {
-                wi_idx0[k] = ml * RSH + 8 * g * a.S + sx;
-                const int pm = static_cast<int>((ml * a.w_sm) & 1);
-                wi_par[k] = pm | (pm << 1);
-            } else {
-                wi_idx0[k] = 8 * g * RSH + ml * a.S + (a.S - 1 - sx);
-                wi_par[k] = static_cast<int>(a.w_sr & 1) << 1;  // runs of odd channels start at the other parity
-            }
-            wi_lds[k] = ((g * JT + (sx >> 2)) * FB + (ml >> 4)) * kQS + 17 * (sx & 3) + (ml & 15);
-            wi_g8[k] = 8 * g;
-            wi_ml[k] = ml;
-        }
-        const int m0 = fg * FB * 16;
-        auto chunk_base = [&](int cc) -> long { return static_cast<long>(m0) * a.w_sm + static_cast<long>(cc * a.NGW * 8) * a.w_sr; };
-        constexpr int kDepth = 4;  // chunks whose raw pieces are in flight
-        u32x4 rreg[kDepth][kMaxRP];
-        auto raw_prefetch = [&](int cc, u32x4 (&rr)[kMaxRP]) {
-            const int r0 = cc * a.NGW * 8;
-            const unsigned eb = static_cast<unsigned>(chunk_base(cc));  // the tensor has fewer than 2^31 elements
-            const int umax = a.fwd_mode ? a.M - 1 - m0 : a.R - 1 - r0;
-            const char* wb = reinterpret_cast<const char*>(a.wt);
-            const unsigned su = static_cast<unsigned>(a.su);
-            const unsigned last_dw = static_cast<unsigned>(a.wbytes - 2) & ~3u;  // the last dword that holds an element
-#pragma unroll
-            for (int k = 0; k < kMaxRP; ++k)
-                if (k * 512 < NRP) {
-                    const unsigned eu = eb + static_cast<unsigned>(max(0, min(rp_u[k], umax))) * su;
-                    const unsigned B = ((eu * 2u) & ~3u) + 16u * static_cast<unsigned>(rp_q[k]);
-                    if (B + 12u <= last_dw) {
-                        rr[k] = *reinterpret_cast<const u32x4*>(wb + B);
-                    } else {  // the last pieces of the tensor
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) rr[k][i] = *reinterpret_cast<const unsigned*>(wb + min(B + 4u * i, last_dw));
-                    }
-                }
-        };
-        auto raw_commit = [&](int rb, const u32x4 (&rr)[kMaxRP]) {
-            u32x4* raw = lds4 + a.wres_slots + rb * a.raw_slots;
-#pragma unroll
-            for (int k = 0; k < kMaxRP; ++k)
-                if (tid + k * 512 < NRP) raw[rp_u[k] * a.NPc + rp_q[k]] = rr[k];
-        };
-        auto gather = [&](int cc) {
-            const unsigned short* raw = reinterpret_cast<const unsigned short*>(lds4 + a.wres_slots + (cc & 1) * a.raw_slots);
-            u32x4* wgt = lds4 + cc * (a.NGW * JT * FB * kQS);
-            const int pb = static_cast<int>(chunk_base(cc) & 1);
-            const int r0 = cc * a.NGW * 8;
-            unsigned v[kMaxWI][8];
-#pragma unroll
-            for (int k = 0; k < kMaxWI; ++k)
-                if (k * 512 < NWI) {
-                    const int ie = wi_idx0[k] + (pb ^ (wi_par[k] & 1)), io = wi_idx0[k] + (pb ^ (wi_par[k] >> 1));
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) v[k][j] = raw[((j & 1) ? io : ie) + j * cs];
-                }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int k = 0; k < kMaxWI; ++k)
-                if (tid + k * 512 < NWI) {
-                    const int nv = m0 + wi_ml[k] < a.M ? a.R - r0 - wi_g8[k] : 0;  // channels that exist
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) v[k][j] = j < nv ? v[k][j] : 0u;
-                    wgt[wi_lds[k]] = u32x4{v[k][0] | (v[k][1] << 16), v[k][2] | (v[k][3] << 16), v[k][4] | (v[k][5] << 16), v[k][6] | (v[k][7] << 16)};
-                }
-        };
-        // chunk cc travels in register set cc % kDepth and raw buffer cc & 1; its loads are issued kDepth chunks
-        // ahead, so that only the first chunks wait for memory
-#pragma unroll
-        for (int i = 0; i < kDepth; ++i)
-            if (i < nchunks) raw_prefetch(i, rreg[i]);
-        __syncthreads();  // the zeroes are in place
-        for (int c0 = 0; c0 < nchunks; c0 += kDepth) {
-#pragma unroll
-            for (int i = 0; i < kDepth; ++i) {
-                const int cc = c0 + i;
-                if (cc < nchunks) {
-                    raw_commit(cc & 1, rreg[i]);
-                    __syncthreads();
-                    gather(cc);
-                    if (cc + kDepth < nchunks) raw_prefetch(cc + kDepth, rreg[i]);
-                }
-            }
-        }
-        __syncthreads();
-    }
-
-    if (consumer) {
-        // ---- consumer side -----------------------------------------------------------------------
-        //   weight operand (plane gp, tap group jj, filter block fb): slot ((gp * JT + jj) * FB + fb) * 68 + 17 kb + li
-        //   input operand G of plane g of the stage:  slot g * LPS + 128 cw + li + kb d + delta + U G
-        const unsigned wlane = 16u * static_cast<unsigned>(17 * kb + li);
-        const unsigned plane_bytes = 16u * static_cast<unsigned>(JT * FB * kQS);
-        const unsigned wres_bytes = 16u * static_cast<unsigned>(a.wres_slots);
-        const unsigned xlane = 16u * static_cast<unsigned>(wbase + cw * (kT * 16) + li + kb * D + a.delta);
-        const char* ldsb = reinterpret_cast<const char*>(lds4);
-        auto ld = [&](unsigned off) { return as_bf16x8(*reinterpret_cast<const u32x4*>(ldsb + off)); };
-        f32x4 acc[FB][kT];
-        bf16x8 W[FB][JT];
-#pragma unroll
-        for (int fb = 0; fb < FB; ++fb) {
-#pragma unroll
-            for (int t = 0; t < kT; ++t) acc[fb][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int jj = 0; jj < JT; ++jj) W[fb][jj] = ld(wlane + 16u * static_cast<unsigned>((jj * FB + fb) * kQS));
-        }
-        unsigned wnext = wlane + plane_bytes;  // entries of the plane after the current one
-        if (wnext >= wlane + wres_bytes) wnext = wlane;
-
-        int tile = t_begin, cc = 0;
-        __syncthreads();  // stage 0 is in LDS
-        for (int st = 0; st < nstages; ++st) {
-            const unsigned sb = xlane + 16u * static_cast<unsigned>((st & 1) * a.win_slots);
-            for (int g = 0; g < a.NG; ++g) {
-                const unsigned xo = sb + 16u * static_cast<unsigned>(g * a.LPS);
-                bf16x8 X[XD];
-#pragma unroll
-                for (int i = 0; i < XD - 1; ++i)
-                    if (i <= GMAX) X[i] = ld(xo + 16u * G_::U * i);
-#pragma unroll
-                for (int G = 0; G <= GMAX; ++G) {
-                    // reads of this step: the operand XD - 1 steps ahead, and the next plane's weights for the tap
-                    // groups whose last MFMA was in the step before
-                    if (G + XD - 1 <= GMAX) X[(G + XD - 1) % XD] = ld(xo + 16u * G_::U * (G + XD - 1));
-#pragma unroll
-                    for (int jj = 0; jj < JT; ++jj)
-                        if (BETA * jj + ALPHA * (kT - 1) == G - 1) {
-#pragma unroll
-                            for (int fb = 0; fb < FB; ++fb) W[fb][jj] = ld(wnext + 16u * static_cast<unsigned>((jj * FB + fb) * kQS));
-                        }
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int t = 0; t < kT; ++t) {
-                        const int r = G - ALPHA * t;
-                        if (r >= 0 && r % BETA == 0 && r / BETA < JT) {
-#pragma unroll
-                            for (int fb = 0; fb < FB; ++fb)
-                                acc[fb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(X[G % XD], W[fb][r / BETA], acc[fb][t], 0, 0, 0);
-                        }
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                // the last tap group's weights
-#pragma unroll
-                for (int fb = 0; fb < FB; ++fb) W[fb][JT - 1] = ld(wnext + 16u * static_cast<unsigned>(((JT - 1) * FB + fb) * kQS));
-                wnext += plane_bytes;
-                if (wnext >= wlane + wres_bytes) wnext = wlane;
-            }
-            if (++cc == a.ncc) {
-                // the tile is complete.  The MFMA operands are swapped (A = input slots, B = weights), so lane
-                // (li, kb) holds filter li of each block at the 4 adjacent columns 4 kb .. 4 kb + 3 of each position block
-                const int ct = tile;
-                const int n = ct / a.tiles_per_row;
-                const int o = (ct - n * a.tiles_per_row) * kTW + cw * (kT * 16) + 4 * kb;
-                float* base = a.out + static_cast<long>(n) * a.out_sn;
-#pragma unroll
-                for (int fb = 0; fb < FB; ++fb) {
-                    const int m = (fg * FB + fb) * 16 + li;
-                    if (m < a.M) {
-                        float* row = base + static_cast<long>(m) * a.Wout + o;
-#pragma unroll
-                        for (int t = 0; t < kT; ++t) {
-                            if (a.vec_out && o + 16 * t + 3 < a.Wout) {
-                                *reinterpret_cast<f32x4*>(row + 16 * t) = acc[fb][t];
-                            } else {
-#pragma unroll
-                                for (int i = 0; i < 4; ++i)
-                                    if (o + 16 * t + i < a.Wout) row[16 * t + i] = acc[fb][t][i];
-                            }
-                        }
-                    }
-                }
-#pragma unroll
-                for (int fb = 0; fb < FB; ++fb)
-#pragma unroll
-                    for (int t = 0; t < kT; ++t) acc[fb][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-                cc = 0;
-                ++tile;
-            }
-            __syncthreads();
-        }
-    } else {
-        // ---- producer side -----------------------------------------------------------------------
-        // Two register sets: the window of stage st + 2 is requested while stage st + 1 is written (a stage is
-        // shorter than the memory latency under load).  Set st & 1 holds stage st.
-        if (nstages > 0) {
-            window_commit(g0, 0, wreg[0]);
-            if (nstages > 2) {
-                g2 = geo(2);
-                window_prefetch(g2, wreg[0]);
-            }
-        }
-        __syncthreads();
-        // invariant at the top of iteration st: g1 = stage st + 1 (in set (st + 1) & 1), g2 = stage st + 2 (in set st & 1)
-        for (int st = 0; st < nstages; st += 2) {
-            if (st + 1 < nstages) {
-                window_commit(g1, 1, wreg[1]);
-                if (st + 3 < nstages) {
-                    g1 = geo(st + 3);
-                    window_prefetch(g1, wreg[1]);
-                }
-            }
-            __syncthreads();
-            if (st + 1 < nstages) {
-                if (st + 2 < nstages) {
-                    window_commit(g2, 0, wreg[0]);
-                    if (st + 4 < nstages) {
-                        g2 = geo(st + 4);
-                        window_prefetch(g2, wreg[0]);
-                    }
-                }
-                __syncthreads();
-            }
-        }
-    }
-}
-
-struct RgPlan {
-    bool ok;
-    int D, FB, JT, grid;
-    size_t lds_bytes;
-    RgArgs a;
-};
-
-RgPlan rg_plan(const CorrProblem& p) {
+RgPlan rg_plan_kt(const CorrProblem& p, int kT) {
+    const int kTW = 64 * kT;
     RgPlan pl{};
     pl.ok = false;
     if (!p.bf16 || p.accumulate) return pl;
@@ -491,7 +76,7 @@ RgPlan rg_plan(const CorrProblem& p) {
             const long behind = 2 * win > 2 * NU * NPc ? 2 * win : 2 * NU * NPc;
             const size_t bytes = static_cast<size_t>(wres + behind) * 16;
             if (bytes > static_cast<size_t>(kLdsBudget)) continue;
-            pl.D = p.d; pl.FB = FB; pl.JT = JT;
+            pl.D = p.d; pl.FB = FB; pl.JT = JT; pl.KT = kT;
             a.NG = NG;
             a.NGW = NGW;
             a.ncc = ncc;
@@ -522,33 +107,18 @@ RgPlan rg_plan(const CorrProblem& p) {
     return pl;
 }
 
-template <int D, int FB, int JT>
-hipError_t rg_launch(const RgPlan& pl, hipStream_t st) {
-    auto kern = igemm_ring_bf16_kernel<D, FB, JT>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(pl.lds_bytes));
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(pl.grid), dim3(512), pl.lds_bytes, st, pl.a);
-    return hipGetLastError();
-}
-
-template <int D>
-hipError_t rg_launch_d(const RgPlan& pl, hipStream_t st) {
-    switch (pl.FB * 100 + pl.JT) {
-        case 113: return rg_launch<D, 1, 13>(pl, st);
-        case 213: return rg_launch<D, 2, 13>(pl, st);
+// Tile width: 8 position blocks per wave, or 5 when that spreads the tiles more evenly over the workgroups (a
+// workgroup walks whole tiles; 2.5 tiles per workgroup cost as much as 3).
+RgPlan rg_plan(const CorrProblem& p) {
+    RgPlan best = rg_plan_kt(p, 8);
 #ifndef CONV1D_DEV_FEW_KERNELS
-        case 109: return rg_launch<D, 1, 9>(pl, st);
-        case 209: return rg_launch<D, 2, 9>(pl, st);
-        case 105: return rg_launch<D, 1, 5>(pl, st);
-        case 205: return rg_launch<D, 2, 5>(pl, st);
-        case 103: return rg_launch<D, 1, 3>(pl, st);
-        case 203: return rg_launch<D, 2, 3>(pl, st);
-        case 102: return rg_launch<D, 1, 2>(pl, st);
-        case 202: return rg_launch<D, 2, 2>(pl, st);
-#endif
-        default: return hipErrorInvalidValue;
+    if (best.ok) {
+        const RgPlan alt = rg_plan_kt(p, 5);
+        auto makespan = [](const RgPlan& pl) { return static_cast<long>(cdiv(pl.a.nct, pl.a.nteams)) * (2 * pl.KT + 1); };
+        if (alt.ok && alt.FB == best.FB && makespan(alt) * 10 < makespan(best) * 9) best = alt;
     }
+#endif
+    return best;
 }
 
 }  // namespace
@@ -559,13 +129,11 @@ hipError_t igemm_ring_bf16_corr_launch(const CorrProblem& p, hipStream_t st) {
     const RgPlan pl = rg_plan(p);
     if (!pl.ok) return hipErrorInvalidValue;
     switch (pl.D) {
-#ifndef CONV1D_DEV_FEW_KERNELS
-        case 1: return rg_launch_d<1>(pl, st);
-        case 2: return rg_launch_d<2>(pl, st);
-        case 4: return rg_launch_d<4>(pl, st);
-        case 16: return rg_launch_d<16>(pl, st);
-#endif
-        case 8: return rg_launch_d<8>(pl, st);
+        case 1: return rg::launch_d1(pl, st);
+        case 2: return rg::launch_d2(pl, st);
+        case 4: return rg::launch_d4(pl, st);
+        case 8: return rg::launch_d8(pl, st);
+        case 16: return rg::launch_d16(pl, st);
         default: return hipErrorInvalidValue;
     }
 }

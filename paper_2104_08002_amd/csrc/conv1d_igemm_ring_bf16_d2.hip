@@ -1,0 +1,14 @@
+// Forward / backward-data, bfloat16, many channels, dilation 2: the resident-weight kernels of this dilation.
+#include "conv1d_igemm_ring_bf16.h"
+
+namespace conv1d {
+namespace rg {
+
+#ifdef CONV1D_DEV_FEW_KERNELS
+hipError_t launch_d2(const RgPlan&, hipStream_t) { return hipErrorInvalidValue; }
+#else
+hipError_t launch_d2(const RgPlan& pl, hipStream_t st) { return rg_launch_d<2>(pl, st); }
+#endif
+
+}  // namespace rg
+}  // namespace conv1d

@@ -1,0 +1,10 @@
+// Forward / backward-data, bfloat16, many channels, dilation 8: the resident-weight kernels of this dilation.
+#include "conv1d_igemm_ring_bf16.h"
+
+namespace conv1d {
+namespace rg {
+
+hipError_t launch_d8(const RgPlan& pl, hipStream_t st) { return rg_launch_d<8>(pl, st); }
+
+}  // namespace rg
+}  // namespace conv1d
