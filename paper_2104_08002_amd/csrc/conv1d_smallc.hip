@@ -642,12 +642,13 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
 }
 
 // Second stage of the backward-weight pass: dw[k][c][s] = sum over workgroups g of
-// ws[(g*S + s)*256 + k*16 + c], always in the same order: 16 contiguous groups of workgroups are
-// summed left to right by 16 threads each, then the 16 group sums are added left to right.
+// ws[(g*S + s)*256 + k*16 + c], always in the same order: 32 contiguous groups of workgroups are
+// summed left to right by 16 threads each, then the 32 group sums are added left to right.
 // blockIdx.y numbers the (filter block, channel block) pairs of a batched launch (K, C: totals).
-__global__ __launch_bounds__(256) void smallc_wgrad_reduce_kernel(const float* __restrict__ ws, float* __restrict__ dw, int K, int C, int S, long dw_sk,
+__global__ __launch_bounds__(512) void smallc_wgrad_reduce_kernel(const float* __restrict__ ws, float* __restrict__ dw, int K, int C, int S, long dw_sk,
                                                                   long dw_sc, int nwg) {
-    __shared__ f32x4 part[16][17];
+    constexpr int kGroups = 32;
+    __shared__ f32x4 part[kGroups][17];
     {
         const int ncbp = (C + 15) >> 4;
         const int pair = blockIdx.y, kbi = pair / ncbp, cbi = pair - kbi * ncbp;
@@ -656,12 +657,12 @@ __global__ __launch_bounds__(256) void smallc_wgrad_reduce_kernel(const float* _
         K = min(16, K - 16 * kbi);
         C = min(16, C - 16 * cbi);
     }
-    // a block of 16 x 16 threads handles 64 consecutive tile elements: thread (grp, el) adds its group's
+    // a block of 32 x 16 threads handles 64 consecutive tile elements: thread (grp, el) adds its group's
     // workgroups for the 4 elements 4 el .. 4 el + 3 with 16-byte loads (256-byte row segments per group)
     const int el = threadIdx.x & 15, grp = threadIdx.x >> 4;
     const int e = blockIdx.x * 64 + 4 * el;  // index into one workgroup's S*256 partial tile (a multiple of 64)
     const int total = S * 256;
-    const int per = (nwg + 15) / 16;
+    const int per = (nwg + kGroups - 1) / kGroups;
     const int g0 = grp * per, g1 = min(nwg, g0 + per);
     f32x4 t = f32x4{0.f, 0.f, 0.f, 0.f};
     {
@@ -674,7 +675,7 @@ __global__ __launch_bounds__(256) void smallc_wgrad_reduce_kernel(const float* _
     if (grp == 0) {
         f32x4 sum = part[0][el];
 #pragma unroll
-        for (int i = 1; i < 16; ++i) sum += part[i][el];
+        for (int i = 1; i < kGroups; ++i) sum += part[i][el];
         const int s = e >> 8, k = (e >> 4) & 15, c0 = e & 15;  // the 4 elements are 4 adjacent channels
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -746,7 +747,7 @@ hipError_t wgrad_f32_launch_nt(const WgradProblem& p, const WgradF32Plan& pl, hi
 hipError_t smallc_wgrad_reduce_launch(const float* ws, float* dw, int K, int C, int S, long dw_sk, long dw_sc, int nwg,
                                       hipStream_t st) {
     const int pairs = cdiv(K, 16) * cdiv(C, 16);
-    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(S * 4, pairs), dim3(256), 0, st, ws, dw, K, C, S, dw_sk, dw_sc, nwg);
+    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(S * 4, pairs), dim3(512), 0, st, ws, dw, K, C, S, dw_sk, dw_sc, nwg);
     return hipGetLastError();
 }
 
