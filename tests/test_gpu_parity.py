@@ -102,6 +102,8 @@ SMALL = [
     ("res_S12_d16",       3, 40, 24, 5000, 12, 16, 43),
     ("res_S7_d4",         2, 72, 40, 1000, 7,  4,  12),
     ("res_S45_d8_c128",   1, 128, 48, 2000, 45, 8, 77),
+    ("c40_halo_gt_width", 2, 40, 24, 200,  51, 8,  200),   # many channels, halo (S-1)d = 400 exceeds W
+    ("c40_tiny_Q",        3, 40, 24, 420,  51, 8,  0),     # Q = 20: less than one k-step / one position block pair
 ]
 
 
