@@ -472,7 +472,7 @@ struct TzPlan {
     TzArgs a;
 };
 
-constexpr int kNTWs[] = {13, 9, 5};  // taps per consumer wave (a tap group has 4 times as many)
+constexpr int kNTWs[] = {13, 9, 5, 3, 2};  // taps per consumer wave (a tap group has 4 times as many)
 
 template <int D, int FB, int NTW>
 hipError_t launch(const TzPlan& pl, hipStream_t st) {
@@ -495,6 +495,10 @@ hipError_t launch_dilation(const TzPlan& pl, hipStream_t st) {
         case 209: return launch<D, 2, 9>(pl, st);
         case 105: return launch<D, 1, 5>(pl, st);
         case 205: return launch<D, 2, 5>(pl, st);
+        case 103: return launch<D, 1, 3>(pl, st);
+        case 203: return launch<D, 2, 3>(pl, st);
+        case 102: return launch<D, 1, 2>(pl, st);
+        case 202: return launch<D, 2, 2>(pl, st);
 #endif
         default: return hipErrorInvalidValue;
     }

@@ -129,7 +129,13 @@ TzPlan tz_plan(const WgradProblem& p) {
         const int slots = cdiv(p.S, 4 * ntw) * 4 * ntw;
         if (best == 0 || slots < best_slots) { best = ntw; best_slots = slots; }
     }
-    if (best == 0 || 20 * best_slots > 29 * p.S) return pl;
+    // Few taps: small layers are bound by memory latency, not by MFMA slots, and this kernel's deeper request
+    // queue wins; layers with many channel and filter blocks are bound by the bytes staged per MFMA, where the
+    // blocked kernel's larger tiles win (measured on C = K = 256, S = 9: 623 us against 465 us).
+    if (best == 0) return pl;
+    if (20 * best_slots > 29 * p.S && (best_slots > 12 || cdiv(p.C, 16) * cdiv(p.K, 16) > 16)) return pl;
+    if (best < 5 && cdiv(p.C, 16) * cdiv(p.K, 16) > 16) return pl;
+    if (best == 2 && p.d == 1) return pl;  // 8 phase copies for 2 taps per wave: the blocked kernel is faster (53 us against 61 us)
     pl.D = p.d;
     pl.NTW = best;
     bool ok = false;
@@ -138,7 +144,10 @@ TzPlan tz_plan(const WgradProblem& p) {
         switch (best) {
             case 13: return tz_geometry_d<13>(p, FB, pl);
             case 9: return tz_geometry_d<9>(p, FB, pl);
-            default: return tz_geometry_d<5>(p, FB, pl);
+            case 5: return tz_geometry_d<5>(p, FB, pl);
+            case 3: return tz_geometry_d<3>(p, FB, pl);
+            case 2: return tz_geometry_d<2>(p, FB, pl);
+            default: return false;
         }
     };
     for (int FB = p.K > 16 ? 2 : 1; FB >= 1 && !ok; --FB) ok = geometry(FB);
