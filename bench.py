@@ -105,7 +105,8 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the path shards over the batch axis; see DESIGN.md)", file=sys.stderr)
+              "(the path would shard over the batch axis: forward and backward-data need no communication, "
+              "backward-weight one all-reduce of the weight gradient)", file=sys.stderr)
         return 2
 
     import numpy as np
