@@ -71,7 +71,7 @@ typedef enum {
     CONV1D_VARIANT_AUTO = 0,
     CONV1D_VARIANT_GENERIC = 1, /* plain FMA, any geometry */
     CONV1D_VARIANT_SMALLC = 2,  /* MFMA, C and K <= 16, taps held in registers */
-    CONV1D_VARIANT_IGEMM = 3    /* MFMA, C or K > 16: blocks of 16 channels x 16 filters, channel blocks accumulated */
+    CONV1D_VARIANT_IGEMM = 3    /* MFMA, any C and K in blocks of 16 channels x 16 filters (implicit GEMM over channel blocks and taps) */
 } conv1d_variant_t;
 
 typedef enum { CONV1D_PASS_FWD = 0, CONV1D_PASS_BWD_DATA = 1, CONV1D_PASS_BWD_WEIGHT = 2 } conv1d_pass_t;
