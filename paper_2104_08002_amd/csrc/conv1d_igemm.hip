@@ -56,7 +56,7 @@ bool fp32_pairs_in_one_launch(const WgradProblem& p) {
 
 // The first block pair is the largest one; the others differ from it only by having fewer rows.
 bool igemm_corr_supported(const CorrProblem& p) {
-    if (p.bf16 && (igemm_ring_bf16_corr_supported(p) || igemm_bf16_corr_supported(p))) return true;
+    if (p.bf16 && (igemm_ring_bf16_corr_supported(p) || igemm_stream_bf16_corr_supported(p) || igemm_bf16_corr_supported(p))) return true;
     if (p.R <= kBlock && p.M <= kBlock) return false;  // one block: that is the small-channel family itself
     return smallc_corr_supported(corr_block(p, 0, 0));
 }
@@ -64,6 +64,7 @@ bool igemm_corr_supported(const CorrProblem& p) {
 hipError_t igemm_corr_launch(const CorrProblem& p, hipStream_t st) {
     if (!igemm_corr_supported(p)) return hipErrorInvalidValue;
     if (p.bf16 && igemm_ring_bf16_corr_supported(p)) return igemm_ring_bf16_corr_launch(p, st);
+    if (p.bf16 && igemm_stream_bf16_corr_supported(p)) return igemm_stream_bf16_corr_launch(p, st);
     if (p.bf16 && igemm_bf16_corr_supported(p)) return igemm_bf16_corr_launch(p, st);
     if (!p.bf16) {
         // every filter block in one launch when the kernel can hold the weights of all channel blocks of a block

@@ -25,6 +25,8 @@
 // groups of one strip form a team on one XCD (the window is fetched from HBM once).
 // Taps beyond S (the last tap group) have zero weights.
 #pragma once
+#include <type_traits>
+
 #include "conv1d_internal.h"
 
 namespace conv1d {
@@ -98,10 +100,11 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
     const int t_begin = static_cast<int>(static_cast<long>(team) * a.nct / a.nteams);
     const int t_end = static_cast<int>(static_cast<long>(team + 1) * a.nct / a.nteams);
     const int nstages = (t_end - t_begin) * a.ncc;
+    if (nstages <= 0) return;  // the whole workgroup (the plan gives every team at least one tile)
 
     const int wbase = a.wres_slots;  // the two window buffers follow the resident weights
 
-    // ---- window staging (producer waves): tables, and the first two windows requested before the prologue ----
+    // ---- window staging (producer waves): tables, and the first window requested before the prologue ----
     // Window task (plane g, pair i): positions G0 + 2i, G0 + 2i + 1 of the 8 channels of plane g; 8 dword
     // loads (row starts, the window origin and Win are even) from clamped addresses, two slots out.
     const int LP2 = a.LP >> 1;
@@ -130,31 +133,34 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
     };
     auto interior = [&](const Geo& g) { return g.G0 >= 0 && g.G0 + a.LP <= a.Win && g.r0 + 8 * a.NG <= a.R; };
     unsigned wreg[2][kMaxWT][8];
-    auto window_prefetch = [&](const Geo& g, unsigned (&wr)[kMaxWT][8]) {
+    // The task count is a compile-time number and every path issues the same loads (tasks and stages past the end
+    // repeat the last one, edge addresses are clamped instead of branched around): only then does the compiler
+    // count the loads that may still be in flight when a register set is used, instead of waiting for all of
+    // them, and only then do two register sets buy two stages of memory latency.
+    auto window_prefetch = [&](auto nt_, const Geo& g, unsigned (&wr)[kMaxWT][8]) {
+        constexpr int NT = decltype(nt_)::value;
         const char* ib = reinterpret_cast<const char*>(a.in + static_cast<long>(g.n) * a.in_sn);
         const unsigned rowb = static_cast<unsigned>(a.Win) * 2u;
         if (interior(g)) {
             const char* rb = ib + 2 * (static_cast<long>(g.r0) * a.Win + g.G0);  // uniform
 #pragma unroll
-            for (int k = 0; k < kMaxWT; ++k)
-                if (k * 256 < NWT) {
+            for (int k = 0; k < NT; ++k) {
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) wr[k][j] = *reinterpret_cast<const unsigned*>(rb + j * static_cast<long>(rowb) + wt_voff[k]);
-                }
+                for (int j = 0; j < 8; ++j) wr[k][j] = *reinterpret_cast<const unsigned*>(rb + j * static_cast<long>(rowb) + wt_voff[k]);
+            }
         } else {
 #pragma unroll
-            for (int k = 0; k < kMaxWT; ++k)
-                if (k * 256 < NWT) {
-                    int pos = g.G0 + 2 * wt_pair[k];
-                    pos = pos < 0 ? 0 : (pos > a.Win - 2 ? a.Win - 2 : pos);
-                    const unsigned offmax = static_cast<unsigned>((a.R - 1) * a.Win + pos) * 2u;
-                    unsigned off = static_cast<unsigned>((g.r0 + wt_plane8[k]) * a.Win + pos) * 2u;
+            for (int k = 0; k < NT; ++k) {
+                int pos = g.G0 + 2 * wt_pair[k];
+                pos = pos < 0 ? 0 : (pos > a.Win - 2 ? a.Win - 2 : pos);
+                const unsigned offmax = static_cast<unsigned>((a.R - 1) * a.Win + pos) * 2u;
+                unsigned off = static_cast<unsigned>((g.r0 + wt_plane8[k]) * a.Win + pos) * 2u;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        wr[k][j] = *reinterpret_cast<const unsigned*>(ib + min(off, offmax));
-                        off += rowb;
-                    }
+                for (int j = 0; j < 8; ++j) {
+                    wr[k][j] = *reinterpret_cast<const unsigned*>(ib + min(off, offmax));
+                    off += rowb;
                 }
+            }
         }
     };
     auto window_commit = [&](const Geo& g, int b, unsigned (&wr)[kMaxWT][8]) {
@@ -180,8 +186,7 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
     Geo g0 = geo(0), g1 = geo(1 < nstages ? 1 : 0), g2 = g1;
     if (!consumer) {
         __builtin_amdgcn_s_setprio(3);
-        if (nstages > 0) window_prefetch(g0, wreg[0]);
-        if (nstages > 1) window_prefetch(g1, wreg[1]);
+        window_prefetch(std::integral_constant<int, kMaxWT>{}, g0, wreg[0]);  // in flight during the prologue
     }
 
     // ---- prologue: the workgroup's weight entries, gathered chunk by chunk (every thread helps) --------------
@@ -226,31 +231,38 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
         auto chunk_base = [&](int cc) -> long { return static_cast<long>(m0) * a.w_sm + static_cast<long>(cc * a.NGW * 8) * a.w_sr; };
         constexpr int kDepth = 4;  // chunks whose raw pieces are in flight
         u32x4 rreg[kDepth][kMaxRP];
-        auto raw_prefetch = [&](int cc, u32x4 (&rr)[kMaxRP]) {
+        // byte offset of piece k of chunk cc (4-byte aligned), and the last offset a 16-byte load may start at
+        const unsigned last_dw = static_cast<unsigned>(a.wbytes - 2) & ~3u;  // the last dword that holds an element
+        const unsigned last_piece = last_dw - 12u;
+        auto piece_offset = [&](int cc, int k) -> unsigned {
             const int r0 = cc * a.NGW * 8;
             const unsigned eb = static_cast<unsigned>(chunk_base(cc));  // the tensor has fewer than 2^31 elements
             const int umax = a.fwd_mode ? a.M - 1 - m0 : a.R - 1 - r0;
-            const char* wb = reinterpret_cast<const char*>(a.wt);
-            const unsigned su = static_cast<unsigned>(a.su);
-            const unsigned last_dw = static_cast<unsigned>(a.wbytes - 2) & ~3u;  // the last dword that holds an element
-#pragma unroll
-            for (int k = 0; k < kMaxRP; ++k)
-                if (k * 512 < NRP) {
-                    const unsigned eu = eb + static_cast<unsigned>(max(0, min(rp_u[k], umax))) * su;
-                    const unsigned B = ((eu * 2u) & ~3u) + 16u * static_cast<unsigned>(rp_q[k]);
-                    if (B + 12u <= last_dw) {
-                        rr[k] = *reinterpret_cast<const u32x4*>(wb + B);
-                    } else {  // the last pieces of the tensor
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) rr[k][i] = *reinterpret_cast<const unsigned*>(wb + min(B + 4u * i, last_dw));
-                    }
-                }
+            const unsigned eu = eb + static_cast<unsigned>(max(0, min(rp_u[k], umax))) * static_cast<unsigned>(a.su);
+            return ((eu * 2u) & ~3u) + 16u * static_cast<unsigned>(rp_q[k]);
         };
-        auto raw_commit = [&](int rb, const u32x4 (&rr)[kMaxRP]) {
-            u32x4* raw = lds4 + a.wres_slots + rb * a.raw_slots;
+        // Every path issues the same loads (chunks past the end repeat the last one, the last pieces of the tensor
+        // are loaded from a clamped address and shifted when they are parked), so that the compiler can count the
+        // loads in flight instead of waiting for all of them.
+        auto raw_prefetch = [&](int cc_, u32x4 (&rr)[kMaxRP]) {
+            const int cc = min(cc_, nchunks - 1);
+            const char* wb = reinterpret_cast<const char*>(a.wt);
+#pragma unroll
+            for (int k = 0; k < kMaxRP; ++k) rr[k] = *reinterpret_cast<const u32x4*>(wb + min(piece_offset(cc, k), last_piece));
+        };
+        auto raw_commit = [&](int cc, const u32x4 (&rr)[kMaxRP]) {
+            u32x4* raw = lds4 + a.wres_slots + (cc & 1) * a.raw_slots;
 #pragma unroll
             for (int k = 0; k < kMaxRP; ++k)
-                if (tid + k * 512 < NRP) raw[rp_u[k] * a.NPc + rp_q[k]] = rr[k];
+                if (tid + k * 512 < NRP) {
+                    const unsigned B = piece_offset(cc, k);
+                    const unsigned sh = B > last_piece ? (B - last_piece) >> 2 : 0u;  // dwords the clamped load started early
+                    u32x4 v = rr[k];
+                    v[0] = sh == 0 ? v[0] : (sh == 1 ? v[1] : (sh == 2 ? v[2] : v[3]));
+                    v[1] = sh == 0 ? v[1] : (sh == 1 ? v[2] : v[3]);
+                    v[2] = sh == 0 ? v[2] : v[3];
+                    raw[rp_u[k] * a.NPc + rp_q[k]] = v;
+                }
         };
         auto gather = [&](int cc) {
             const unsigned short* raw = reinterpret_cast<const unsigned short*>(lds4 + a.wres_slots + (cc & 1) * a.raw_slots);
@@ -278,19 +290,16 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
         // chunk cc travels in register set cc % kDepth and raw buffer cc & 1; its loads are issued kDepth chunks
         // ahead, so that only the first chunks wait for memory
 #pragma unroll
-        for (int i = 0; i < kDepth; ++i)
-            if (i < nchunks) raw_prefetch(i, rreg[i]);
+        for (int i = 0; i < kDepth; ++i) raw_prefetch(i, rreg[i]);
         __syncthreads();  // the zeroes are in place
         for (int c0 = 0; c0 < nchunks; c0 += kDepth) {
 #pragma unroll
             for (int i = 0; i < kDepth; ++i) {
                 const int cc = c0 + i;
-                if (cc < nchunks) {
-                    raw_commit(cc & 1, rreg[i]);
-                    __syncthreads();
-                    gather(cc);
-                    if (cc + kDepth < nchunks) raw_prefetch(cc + kDepth, rreg[i]);
-                }
+                if (cc < nchunks) raw_commit(cc, rreg[i]);
+                __syncthreads();
+                if (cc < nchunks) gather(cc);
+                raw_prefetch(cc + kDepth, rreg[i]);
             }
         }
         __syncthreads();
@@ -390,38 +399,49 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
             }
             __syncthreads();
         }
+        if (nstages & 1) __syncthreads();  // the producers' loop takes the stages in pairs
     } else {
         // ---- producer side -----------------------------------------------------------------------
         // Two register sets: the window of stage st + 2 is requested while stage st + 1 is written (a stage is
-        // shorter than the memory latency under load).  Set st & 1 holds stage st.
-        if (nstages > 0) {
+        // shorter than the memory latency under load).  Set st & 1 holds stage st.  The loop exists once per task
+        // count.
+        auto run = [&](auto nt_) {
+            const int last = nstages - 1;
+            window_prefetch(nt_, g1, wreg[1]);
             window_commit(g0, 0, wreg[0]);
-            if (nstages > 2) {
-                g2 = geo(2);
-                window_prefetch(g2, wreg[0]);
-            }
-        }
-        __syncthreads();
-        // invariant at the top of iteration st: g1 = stage st + 1 (in set (st + 1) & 1), g2 = stage st + 2 (in set st & 1)
-        for (int st = 0; st < nstages; st += 2) {
-            if (st + 1 < nstages) {
-                window_commit(g1, 1, wreg[1]);
-                if (st + 3 < nstages) {
-                    g1 = geo(st + 3);
-                    window_prefetch(g1, wreg[1]);
-                }
-            }
+            g2 = geo(min(2, last));
+            window_prefetch(nt_, g2, wreg[0]);
             __syncthreads();
-            if (st + 1 < nstages) {
-                if (st + 2 < nstages) {
-                    window_commit(g2, 0, wreg[0]);
-                    if (st + 4 < nstages) {
-                        g2 = geo(st + 4);
-                        window_prefetch(g2, wreg[0]);
-                    }
-                }
+            // invariant at the top of iteration st: g1 = stage st + 1 (in set 1), g2 = stage st + 2 (in set 0)
+            int st = 0;
+            for (; st + 4 <= last; st += 2) {  // the steady state: no branch around a load
+                window_commit(g1, 1, wreg[1]);
+                g1 = geo(st + 3);
+                window_prefetch(nt_, g1, wreg[1]);
+                __syncthreads();
+                window_commit(g2, 0, wreg[0]);
+                g2 = geo(st + 4);
+                window_prefetch(nt_, g2, wreg[0]);
                 __syncthreads();
             }
+            // the last stages; with an odd number of them the consumers meet the second barrier after their loop
+            for (; st <= last; st += 2) {
+                if (st + 1 <= last) window_commit(g1, 1, wreg[1]);
+                if (st + 3 <= last) {
+                    g1 = geo(st + 3);
+                    window_prefetch(nt_, g1, wreg[1]);
+                }
+                __syncthreads();
+                if (st + 2 <= last) window_commit(g2, 0, wreg[0]);
+                __syncthreads();
+            }
+        };
+        switch ((NWT + 255) / 256) {
+            case 1: run(std::integral_constant<int, 1>{}); break;
+            case 2: run(std::integral_constant<int, 2>{}); break;
+            case 3: run(std::integral_constant<int, 3>{}); break;
+            case 4: run(std::integral_constant<int, 4>{}); break;
+            default: run(std::integral_constant<int, kMaxWT>{}); break;
         }
     }
 }

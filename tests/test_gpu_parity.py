@@ -102,6 +102,11 @@ SMALL = [
     ("res_S12_d16",       3, 40, 24, 5000, 12, 16, 43),
     ("res_S7_d4",         2, 72, 40, 1000, 7,  4,  12),
     ("res_S45_d8_c128",   1, 128, 48, 2000, 45, 8, 77),
+    # forward / backward-data with streamed weights: many filters and channels, 5 to 12 taps
+    ("str_S7_d8",         1, 128, 200, 3000, 7, 8,  21),    # filter count no multiple of 32
+    ("str_S12_d2",        2, 136, 72, 2500, 12, 2,  11),    # odd padding, channel count no multiple of 16
+    ("str_S5_d16",        1, 256, 256, 1024, 5, 16, 32),    # one column tile per sample
+    ("str_S9_d1_odd",     3, 160, 96, 2100, 9,  1,  4),     # an odd number of stages per workgroup
     ("c40_halo_gt_width", 2, 40, 24, 200,  51, 8,  200),   # many channels, halo (S-1)d = 400 exceeds W
     ("c40_tiny_Q",        3, 40, 24, 420,  51, 8,  0),     # Q = 20: less than one k-step / one position block pair
 ]
