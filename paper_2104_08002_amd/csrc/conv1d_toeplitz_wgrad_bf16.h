@@ -26,6 +26,8 @@
 // taps), waves 4-7 ("producers") load the next unit from global memory, build the phase copies and write them
 // into the other half of the double-buffered LDS.  One workgroup barrier per unit.
 #pragma once
+#include <type_traits>
+
 #include "conv1d_internal.h"
 
 namespace conv1d {
@@ -348,31 +350,34 @@ __global__ __launch_bounds__(512, 1) void toeplitz_wgrad_bf16_kernel(TzArgs a) {
         auto has_odd = [&](int it) { return (a.phase_mask >> (item_base(it) + 1)) & 1u; };
         // FAST: every unit is fetched one unit ahead with 16-byte loads; where the window leaves the rows the
         // loads are clamped into them and the slots are put right when they are written to LDS.
-        auto prefetch = [&](Stage& st, int u) {
+        // Whether the dwords behind the slots are loaded at all (some phase in use is odd) is a compile-time
+        // choice of the caller, and both paths issue the same loads: the compiler can then count the loads that may
+        // still be in flight when a register set is used instead of waiting for all of them.
+        auto prefetch = [&](auto odd_, Stage& st, int u) {
+            constexpr bool ODD = decltype(odd_)::value;
             if (!FAST) return;
             const int q0 = qs + u * 32 * LU;
             if (interior(q0)) {
                 const unsigned short* yb = dyn + q0;
                 const unsigned short* xb = xn + (q0 + fl8);
 #pragma unroll
-                for (int k = 0; k < kMaxY; ++k)
-                    if (k * 256 < NY) st.y[k] = *reinterpret_cast<const u32x4*>(yb + (yrow[k] + static_cast<unsigned>(ycol[k])));
+                for (int k = 0; k < kMaxY; ++k) st.y[k] = *reinterpret_cast<const u32x4*>(yb + (yrow[k] + static_cast<unsigned>(ycol[k])));
 #pragma unroll
                 for (int it = 0; it < kMaxI; ++it) {
-                        const unsigned short* src = xb + (xrow[it] + static_cast<unsigned>(xcol[it]));
-                        st.x[it] = *reinterpret_cast<const u32x4*>(src);
-                        if (has_odd(it)) st.xd[it] = *reinterpret_cast<const unsigned*>(src + 8);
-                    }
+                    const unsigned short* src = xb + (xrow[it] + static_cast<unsigned>(xcol[it]));
+                    st.x[it] = *reinterpret_cast<const u32x4*>(src);
+                    if (ODD) st.xd[it] = *reinterpret_cast<const unsigned*>(src + 8);
+                }
             } else {
 #pragma unroll
-                for (int k = 0; k < kMaxY; ++k)
-                    if (k * 256 < NY) st.y[k] = load128_clamped(dyn + yrow[k], q0 + ycol[k], a.Q);
+                for (int k = 0; k < kMaxY; ++k) st.y[k] = load128_clamped(dyn + yrow[k], q0 + ycol[k], a.Q);
 #pragma unroll
                 for (int it = 0; it < kMaxI; ++it) {
-                        const int c = q0 + fl8 + xcol[it];
-                        st.x[it] = load128_clamped(xn + xrow[it], c, a.W);
-                        if (has_odd(it)) st.xd[it] = load_pair(xn + xrow[it], c + 8, a.W);
-                    }
+                    const int c = q0 + fl8 + xcol[it];
+                    st.x[it] = load128_clamped(xn + xrow[it], c, a.W);
+                    // clamped like the slot itself; put right (zero outside the row) when it is written to LDS
+                    if (ODD) st.xd[it] = *reinterpret_cast<const unsigned*>(xn + xrow[it] + clampi(c + 8, 0, a.W - 2));
+                }
             }
         };
         auto commit = [&](Stage& st, int u) {
@@ -383,8 +388,11 @@ __global__ __launch_bounds__(512, 1) void toeplitz_wgrad_bf16_kernel(TzArgs a) {
                     for (int k = 0; k < kMaxY; ++k)
                         if (k * 256 < NY) st.y[k] = fix128(st.y[k], q0 + ycol[k], a.Q);
 #pragma unroll
-                    for (int it = 0; it < kMaxI; ++it)
-                        st.x[it] = fix128(st.x[it], q0 + fl8 + xcol[it], a.W);
+                    for (int it = 0; it < kMaxI; ++it) {
+                        const int c = q0 + fl8 + xcol[it];
+                        st.x[it] = fix128(st.x[it], c, a.W);
+                        if (has_odd(it)) st.xd[it] = (c + 8 >= 0 && c + 8 < a.W) ? st.xd[it] : 0u;
+                    }
                 }
             } else {
 #pragma unroll
@@ -422,45 +430,56 @@ __global__ __launch_bounds__(512, 1) void toeplitz_wgrad_bf16_kernel(TzArgs a) {
         // to LDS (the memory latency under load exceeds the MFMA time of one unit).  Set A holds the even units,
         // set B the odd ones.
         constexpr bool kTwoSets = FAST && !(FB == 2 && (D == 2 || D == 4));
-        Stage sa;
-        if constexpr (kTwoSets) {
-            Stage sb;
-            prefetch(sa, 0);
-            if (nunits > 1) prefetch(sb, 1);
-            first_fill();  // while the units' loads are on their way
-            commit(sa, 0);
-            if (nunits > 2) prefetch(sa, 2);
-            __syncthreads();
-            __syncthreads();
-            for (int u = 0; u < nunits; u += 2) {
-                if (u + 1 < nunits) {
-                    commit(sb, u + 1);
-                    if (u + 3 < nunits) prefetch(sb, u + 3);
-                }
+        auto run = [&](auto odd_) {
+            const int last = nunits - 1;
+            Stage sa;
+            if constexpr (kTwoSets) {
+                Stage sb;
+                prefetch(odd_, sa, 0);
+                prefetch(odd_, sb, min(1, last));
+                first_fill();  // while the units' loads are on their way
+                commit(sa, 0);
+                prefetch(odd_, sa, min(2, last));
                 __syncthreads();
-                if (u + 1 < nunits) {
-                    if (u + 2 < nunits) {
-                        commit(sa, u + 2);
-                        if (u + 4 < nunits) prefetch(sa, u + 4);
+                __syncthreads();
+                int u = 0;
+                for (; u + 4 <= last; u += 2) {  // the steady state: no branch around a load
+                    commit(sb, u + 1);
+                    prefetch(odd_, sb, u + 3);
+                    __syncthreads();
+                    commit(sa, u + 2);
+                    prefetch(odd_, sa, u + 4);
+                    __syncthreads();
+                }
+                for (; u <= last; u += 2) {  // the last units
+                    if (u + 1 <= last) {
+                        commit(sb, u + 1);
+                        if (u + 3 <= last) prefetch(odd_, sb, u + 3);
+                    }
+                    __syncthreads();
+                    if (u + 1 <= last) {
+                        if (u + 2 <= last) commit(sa, u + 2);
+                        __syncthreads();
+                    }
+                }
+            } else {
+                prefetch(odd_, sa, 0);
+                first_fill();
+                commit(sa, 0);
+                if (nunits > 1) prefetch(odd_, sa, 1);
+                __syncthreads();
+                __syncthreads();
+                for (int u = 0; u < nunits; ++u) {
+                    if (u + 1 < nunits) {
+                        commit(sa, u + 1);
+                        if (u + 2 < nunits) prefetch(odd_, sa, u + 2);
                     }
                     __syncthreads();
                 }
             }
-        } else {
-            prefetch(sa, 0);
-            first_fill();
-            commit(sa, 0);
-            if (nunits > 1) prefetch(sa, 1);
-            __syncthreads();
-            __syncthreads();
-            for (int u = 0; u < nunits; ++u) {
-                if (u + 1 < nunits) {
-                    commit(sa, u + 1);
-                    if (u + 2 < nunits) prefetch(sa, u + 2);
-                }
-                __syncthreads();
-            }
-        }
+        };
+        if (a.phase_mask & 0xaau) run(std::true_type{});
+        else run(std::false_type{});
     }
 }
 
