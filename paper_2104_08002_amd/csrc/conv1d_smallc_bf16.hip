@@ -573,7 +573,7 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_bf16_d8_kernel(WgradProbl
         }
         if (!consumer) {
             prefetch_stage(preA, j0);
-            if (j0 + 1 < j1) prefetch_stage(preB, j0 + 1);
+            prefetch_stage(preB, min(j0 + 1, j1 - 1));
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -592,13 +592,13 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_bf16_d8_kernel(WgradProbl
         }
     } else {
         commit_stage(preA, 0, j0);
-        if (j0 + 2 < j1) prefetch_stage(preA, j0 + 2);
+        prefetch_stage(preA, min(j0 + 2, j1 - 1));
     }
     __syncthreads();
 
-    for (int j = j0; j < j1; ++j) {
-        const int b = (j - j0) & 1;
-        if (consumer) {
+    if (consumer) {
+        for (int j = j0; j < j1; ++j) {
+            const int b = (j - j0) & 1;
             const u32x4* xp = xbuf[b] + li * kXR + cw + kb;
             const u32x4* ap = dybuf[b] + li * kDR + kb;
             bf16x8 a = as_bf16x8(ap[0]);
@@ -615,17 +615,33 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_bf16_d8_kernel(WgradProbl
                 __builtin_amdgcn_sched_barrier(0);
                 a = a_nxt;
             }
-        } else if (j + 1 < j1) {
-            // stage j+1 sits in preB when b == 0 and in preA when b == 1; its registers then take stage j+3
-            if (b == 0) {
+            __syncthreads();
+        }
+    } else {
+        // Stage j + 1 sits in preB while an even stage (counted from j0) is consumed and in preA otherwise; its
+        // registers then take stage j + 3.  The steady loop has no branch around a load, so the compiler can tell
+        // that a set's first use has to wait for that set only, not for the requests made since.
+        const int last = j1 - 1;
+        int j = j0;
+        for (; j + 4 <= last; j += 2) {
+            commit_stage(preB, 1, j + 1);
+            prefetch_stage(preB, j + 3);
+            __syncthreads();
+            commit_stage(preA, 0, j + 2);
+            prefetch_stage(preA, j + 4);
+            __syncthreads();
+        }
+        for (; j <= last; j += 2) {  // the last stages
+            if (j + 1 <= last) {
                 commit_stage(preB, 1, j + 1);
-                if (j + 3 < j1) prefetch_stage(preB, j + 3);
-            } else {
-                commit_stage(preA, 0, j + 1);
-                if (j + 3 < j1) prefetch_stage(preA, j + 3);
+                if (j + 3 <= last) prefetch_stage(preB, j + 3);
+            }
+            __syncthreads();
+            if (j + 1 <= last) {
+                if (j + 2 <= last) commit_stage(preA, 0, j + 2);
+                __syncthreads();
             }
         }
-        __syncthreads();
     }
     if (consumer) {
         const int nt = (p.S - cw + 3) / 4;  // real taps of this wave; the remaining slots hold unused sums
