@@ -304,10 +304,10 @@ __global__ __launch_bounds__(512, 1) void toeplitz_wgrad_bf16_kernel(TzArgs a) {
         // an odd phase phi = e + 1 is made from the load of the even phase e and the dword behind it, shifted
         // by one element.  A load item is (slot, even base e); every thread owns kMaxI of them.
         // Rows beyond C or K re-read the last row: their sums are never stored and no other sum depends on them.
-        // FAST (widths, sample strides and pointers multiples of 2 elements): units are fetched one unit ahead;
-        // a unit whose whole window lies inside the rows ("interior") from scalar base + per-thread constant
-        // offsets.  Otherwise every unit is loaded element by element, zero outside the row, when it is written
-        // to LDS.
+        // FAST (widths, sample strides and pointers multiples of 2 elements): units are fetched one or two units
+        // ahead with 16-byte loads from addresses clamped into the rows; a unit whose window leaves the rows (not
+        // "interior") is put right when it is written to LDS.  Otherwise every unit is loaded element by element,
+        // zero outside the row, when it is written to LDS.
         constexpr int SY = 4 * LU;
         constexpr int NY = FB * 16 * SY, NXT = 16 * G::NXS;
         constexpr int ng = G::NG;
@@ -351,33 +351,22 @@ __global__ __launch_bounds__(512, 1) void toeplitz_wgrad_bf16_kernel(TzArgs a) {
         // FAST: every unit is fetched one unit ahead with 16-byte loads; where the window leaves the rows the
         // loads are clamped into them and the slots are put right when they are written to LDS.
         // Whether the dwords behind the slots are loaded at all (some phase in use is odd) is a compile-time
-        // choice of the caller, and both paths issue the same loads: the compiler can then count the loads that may
+        // choice of the caller, so no branch surrounds a load: the compiler can then count the loads that may
         // still be in flight when a register set is used instead of waiting for all of them.
         auto prefetch = [&](auto odd_, Stage& st, int u) {
             constexpr bool ODD = decltype(odd_)::value;
             if (!FAST) return;
             const int q0 = qs + u * 32 * LU;
-            if (interior(q0)) {
-                const unsigned short* yb = dyn + q0;
-                const unsigned short* xb = xn + (q0 + fl8);
+            // (one path for interior and edge units: clamping on the vector ALU measured as fast as a second path
+            // with scalar bases)
 #pragma unroll
-                for (int k = 0; k < kMaxY; ++k) st.y[k] = *reinterpret_cast<const u32x4*>(yb + (yrow[k] + static_cast<unsigned>(ycol[k])));
+            for (int k = 0; k < kMaxY; ++k) st.y[k] = load128_clamped(dyn + yrow[k], q0 + ycol[k], a.Q);
 #pragma unroll
-                for (int it = 0; it < kMaxI; ++it) {
-                    const unsigned short* src = xb + (xrow[it] + static_cast<unsigned>(xcol[it]));
-                    st.x[it] = *reinterpret_cast<const u32x4*>(src);
-                    if (ODD) st.xd[it] = *reinterpret_cast<const unsigned*>(src + 8);
-                }
-            } else {
-#pragma unroll
-                for (int k = 0; k < kMaxY; ++k) st.y[k] = load128_clamped(dyn + yrow[k], q0 + ycol[k], a.Q);
-#pragma unroll
-                for (int it = 0; it < kMaxI; ++it) {
-                    const int c = q0 + fl8 + xcol[it];
-                    st.x[it] = load128_clamped(xn + xrow[it], c, a.W);
-                    // clamped like the slot itself; put right (zero outside the row) when it is written to LDS
-                    if (ODD) st.xd[it] = *reinterpret_cast<const unsigned*>(xn + xrow[it] + clampi(c + 8, 0, a.W - 2));
-                }
+            for (int it = 0; it < kMaxI; ++it) {
+                const int c = q0 + fl8 + xcol[it];
+                st.x[it] = load128_clamped(xn + xrow[it], c, a.W);
+                // clamped like the slot itself; put right (zero outside the row) when it is written to LDS
+                if (ODD) st.xd[it] = *reinterpret_cast<const unsigned*>(xn + xrow[it] + clampi(c + 8, 0, a.W - 2));
             }
         };
         auto commit = [&](Stage& st, int u) {
