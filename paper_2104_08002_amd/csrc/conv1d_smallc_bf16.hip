@@ -158,12 +158,38 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
         wb[h * LPS + 2 * pp] = ev;
         wb[h * LPS + 2 * pp + 1] = od;
     };
-    auto tile_n = [&](int t) { return t / tiles_per_row; };
-    auto tile_O0 = [&](int t) { return (t - (t / tiles_per_row) * tiles_per_row) * TQ; };
+    // (sample, first column) of a tile near the one the loop is at, by counting from it: a uniform integer division
+    // is ~25 vector instructions, and the producers would do three per tile next to the MFMA wave of their SIMD
+    const int row_w = tiles_per_row * TQ;
+    int cur_t = t_begin, cur_n = t_begin / tiles_per_row, cur_O0 = (t_begin - cur_n * tiles_per_row) * TQ;
+    struct TilePos {
+        int n, O0;
+    };
+    auto tile_pos = [&](int t) -> TilePos {
+        TilePos tp{cur_n, cur_O0 + (t - cur_t) * TQ};
+        while (tp.O0 >= row_w) {
+            tp.O0 -= row_w;
+            ++tp.n;
+        }
+        while (tp.O0 < 0) {
+            tp.O0 += row_w;
+            --tp.n;
+        }
+        return tp;
+    };
+    auto tile_advance = [&]() {
+        ++cur_t;
+        cur_O0 += TQ;
+        if (cur_O0 >= row_w) {
+            cur_O0 = 0;
+            ++cur_n;
+        }
+    };
     Task pre[FAST ? MAXT : 1];
     auto prefetch = [&](int t) {  // producers: window of tile t -> registers
         if constexpr (FAST) {
-            const int n = tile_n(t), G0 = tile_O0(t) - p.P - psh;
+            const TilePos tp = tile_pos(t);
+            const int n = tp.n, G0 = tp.O0 - p.P - psh;
 #pragma unroll
             for (int k = 0; k < MAXT; ++k) {
                 const int task = rtid + k * 256;
@@ -172,7 +198,8 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
         }
     };
     auto commit = [&](int t, u32x4* wb) {  // producers: registers (or memory) -> LDS window of tile t
-        const int n = tile_n(t), G0 = tile_O0(t) - p.P - psh;
+        const TilePos tp = tile_pos(t);
+        const int n = tp.n, G0 = tp.O0 - p.P - psh;
         const bool edge = G0 < 0 || G0 + 2 * LP2 > p.Win;
         if constexpr (FAST) {
 #pragma unroll
@@ -187,7 +214,8 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
     };
     // producers: parked outputs of tile t (staging buffer b) -> global memory
     auto flush = [&](int t, int b) {
-        const int n = tile_n(t), O0 = tile_O0(t);
+        const TilePos tp = tile_pos(t);
+        const int n = tp.n, O0 = tp.O0;
         const float* src = ost(b);
         if (vec_out) {
             const int orow = lane >> 5, ocol = 4 * (lane & 31);
@@ -244,30 +272,36 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
     __syncthreads();
     bf16x8 wreg[NP];
     if (consumer) {
+        // Entry e = rtid + 256 k: the lane part (filter m, channel half h, tap half) is the same for every k, the
+        // slice advances by 4 per k.  Everything that needs a multiplication is worked out once per thread (integer
+        // multiplies run at a quarter of the ALU rate, and this code is on the critical path of every workgroup).
         constexpr int NE = (NP * 64 + 255) / 256;
+        const int l = rtid & 63;
+        const int m = l & 15, h = (l >> 4) & 1, s0 = (rtid >> 6) + NP * (l >> 5);
+        const int wsm = static_cast<int>(p.w_sm), wsr = static_cast<int>(p.w_sr), wss = static_cast<int>(p.w_ss);
+        const int bm = min(m, p.M - 1) * wsm + static_cast<int>(p.w_s0);
+        int roff[8];  // offset of channel 8 h + j (clamped to the last channel)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) roff[j] = min(8 * h + j, p.R - 1) * wsr;
         unsigned wv[NE][8];
 #pragma unroll
         for (int k = 0; k < NE; ++k) {
-            const int e = min(rtid + k * 256, NP * 64 - 1);
-            const int pi = e >> 6, l = e & 63;
-            const int m = min(l & 15, p.M - 1), h = (l >> 4) & 1, s = min(pi + NP * (l >> 5), p.S - 1);
-            const int base = static_cast<int>(m * p.w_sm + p.w_s0 + s * p.w_ss);
+            const int base = bm + min(s0 + 4 * k, p.S - 1) * wss;
             if (p.w_contig) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) wv[k][j] = raw[base + min(8 * h + j, p.R - 1) * static_cast<int>(p.w_sr)];
+                for (int j = 0; j < 8; ++j) wv[k][j] = raw[base + roff[j]];
             } else {  // a block of a larger tensor: gather straight from global memory
 #pragma unroll
-                for (int j = 0; j < 8; ++j) wv[k][j] = wt[m * p.w_sm + p.w_s0 + s * p.w_ss + min(8 * h + j, p.R - 1) * p.w_sr];
+                for (int j = 0; j < 8; ++j) wv[k][j] = wt[base + roff[j]];
             }
         }
 #pragma unroll
         for (int k = 0; k < NE; ++k) {
             const int e = rtid + k * 256;
-            const int pi = e >> 6, l = e & 63;
-            const int m = l & 15, h = (l >> 4) & 1, s = pi + NP * (l >> 5);
+            const bool ok = m < p.M && s0 + 4 * k < p.S;
             unsigned v[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = (m < p.M && 8 * h + j < p.R && s < p.S) ? wv[k][j] : 0u;
+            for (int j = 0; j < 8; ++j) v[j] = (ok && 8 * h + j < p.R) ? wv[k][j] : 0u;
             if (e < NP * 64) entries[e] = u32x4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
         }
     } else if (t_begin < t_end) {
@@ -354,6 +388,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
             if (k > 0) flush(t - 1, (k - 1) & 1);
         }
         __syncthreads();
+        tile_advance();
     }
     if (!consumer && k > 0) flush(t_end - 1, (k - 1) & 1);
 }
