@@ -107,6 +107,9 @@ SMALL = [
     ("str_S12_d2",        2, 136, 72, 2500, 12, 2,  11),    # odd padding, channel count no multiple of 16
     ("str_S5_d16",        1, 256, 256, 1024, 5, 16, 32),    # one column tile per sample
     ("str_S9_d1_odd",     3, 160, 96, 2100, 9,  1,  4),     # an odd number of stages per workgroup
+    ("str_c200_fwd",      1, 200, 72, 1500, 9, 2,  7),     # weights too large for LDS in the forward pass only
+    ("str_k200_bwd",      2, 72, 200, 1100, 12, 4, 0),     # ... in the backward-data pass only; no padding
+    ("str_c264_short",    1, 264, 40, 70,  5,  1,  2),     # one short tile; 33 planes of channels
     ("c40_halo_gt_width", 2, 40, 24, 200,  51, 8,  200),   # many channels, halo (S-1)d = 400 exceeds W
     ("c40_tiny_Q",        3, 40, 24, 420,  51, 8,  0),     # Q = 20: less than one k-step / one position block pair
 ]
