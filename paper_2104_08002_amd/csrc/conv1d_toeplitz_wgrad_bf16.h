@@ -422,7 +422,8 @@ __global__ __launch_bounds__(512, 1) void toeplitz_wgrad_bf16_kernel(TzArgs a) {
         auto run = [&](auto odd_) {
             const int last = nunits - 1;
             Stage sa;
-            if constexpr (kTwoSets) {
+            // (with the dwords behind the slots, two sets of the d = 2 and d = 4 kernels no longer fit in registers)
+            if constexpr (kTwoSets && !(decltype(odd_)::value && (D == 2 || D == 4))) {
                 Stage sb;
                 prefetch(odd_, sa, 0);
                 prefetch(odd_, sb, min(1, last));
