@@ -1,4 +1,4 @@
-// Forward / backward-data passes (Eq. 2; Section 3.2) for bfloat16 inputs, MANY channels with FEW taps (5 to 12)
+// Forward / backward-data passes (Eq. 2; Section 3.2) for bfloat16 inputs, MANY channels with FEW taps (5 to 20)
 // and dilations 1, 2, 4, 8, 16: implicit GEMM with streamed weights and shared input operands.
 //
 //   out[n][m][o] = sum_r sum_s in[n][r][o + s*d - P] * wt(m, r, s)
@@ -404,7 +404,7 @@ SgPlan sg_plan(const CorrProblem& p) {
 #else
     if (p.d != 1 && p.d != 2 && p.d != 4 && p.d != 8 && p.d != 16) return pl;
 #endif
-    if (p.S < 5 || p.S > 12) return pl;
+    if (p.S < 5 || p.S > 20) return pl;
     if ((p.Win & 1) || (p.in_sn & 1) || (reinterpret_cast<uintptr_t>(p.in) & 3) || p.Win < 2) return pl;
     if (reinterpret_cast<uintptr_t>(p.wt) & 3) return pl;
     const bool fwd_mode = p.w_ss == 1 && p.w_sr == p.S && p.w_s0 == 0;
@@ -412,7 +412,7 @@ SgPlan sg_plan(const CorrProblem& p) {
     if (!fwd_mode && !bwd_mode) return pl;
     if (static_cast<long>(p.R) * p.Win >= (1L << 30)) return pl;
     if (static_cast<long>(p.M) * p.R * p.S >= (1L << 31) || p.M * p.w_sm >= (1L << 31) || p.R * p.w_sr >= (1L << 31)) return pl;
-    const int JT = p.S <= 8 ? 2 : 3;
+    const int JT = p.S <= 8 ? 2 : (p.S <= 12 ? 3 : 5);
     SgArgs& a = pl.a;
     a.in = static_cast<const unsigned short*>(p.in);
     a.wt = static_cast<const unsigned short*>(p.wt);
@@ -453,6 +453,10 @@ SgPlan sg_plan(const CorrProblem& p) {
         const long nct = static_cast<long>(p.N) * a.tiles_per_row;
         if (nct > 0x7fffffffL / 64 || a.nfg > 65535) return pl;
         a.nct = static_cast<int>(nct);
+        // 13 - 20 taps: the staged kernel's tiles are half as wide, and it is the faster one while the tiles of this
+        // kernel would leave half of the CUs idle (measured: N = 8, C = K = 256, W = 4096, S = 17: 90 us against 118 us;
+        // N = 2, W = 2048, S = 20: 81 us against 62 us)
+        if (JT == 5 && nct * a.nfg <= kNumCU / 2) return pl;
         const int fit = kNumCU / a.nfg > 0 ? kNumCU / a.nfg : 1;  // teams that run at the same time
         a.nteams = a.nct < fit ? a.nct : fit;
         pl.grid = a.nteams * a.nfg;
@@ -475,7 +479,14 @@ hipError_t sg_launch(const SgPlan& pl, hipStream_t st) {
 
 template <int D>
 hipError_t sg_launch_d(const SgPlan& pl, hipStream_t st) {
-    return pl.JT == 2 ? sg_launch<D, 2>(pl, st) : sg_launch<D, 3>(pl, st);
+    switch (pl.JT) {
+        case 2: return sg_launch<D, 2>(pl, st);
+        case 3: return sg_launch<D, 3>(pl, st);
+#ifndef CONV1D_DEV_FEW_KERNELS
+        case 5: return sg_launch<D, 5>(pl, st);
+#endif
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace

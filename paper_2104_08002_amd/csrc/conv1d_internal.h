@@ -100,7 +100,7 @@ hipError_t igemm_bf16_corr_launch(const CorrProblem& p, hipStream_t st);
 bool igemm_ring_bf16_corr_supported(const CorrProblem& p);
 hipError_t igemm_ring_bf16_corr_launch(const CorrProblem& p, hipStream_t st);
 
-// the same dilations with 5 to 12 taps and weights too large for LDS: streamed weights, tiles of 32 filters x 1024
+// the same dilations with 5 to 20 taps and weights too large for LDS: streamed weights, tiles of 32 filters x 1024
 // columns, input operands shared between taps and position blocks
 bool igemm_stream_bf16_corr_supported(const CorrProblem& p);
 hipError_t igemm_stream_bf16_corr_launch(const CorrProblem& p, hipStream_t st);

@@ -110,6 +110,8 @@ SMALL = [
     ("str_c200_fwd",      1, 200, 72, 1500, 9, 2,  7),     # weights too large for LDS in the forward pass only
     ("str_k200_bwd",      2, 72, 200, 1100, 12, 4, 0),     # ... in the backward-data pass only; no padding
     ("str_c264_short",    1, 264, 40, 70,  5,  1,  2),     # one short tile; 33 planes of channels
+    ("str5_fwd",          4, 152, 1056, 200, 17, 2, 16),   # 13 - 20 taps: taken when the tiles fill half of the CUs
+    ("str5_bwd",          4, 1056, 152, 210, 15, 8, 3),    # ... in the backward-data pass
     ("c40_halo_gt_width", 2, 40, 24, 200,  51, 8,  200),   # many channels, halo (S-1)d = 400 exceeds W
     ("c40_tiny_Q",        3, 40, 24, 420,  51, 8,  0),     # Q = 20: less than one k-step / one position block pair
 ]
