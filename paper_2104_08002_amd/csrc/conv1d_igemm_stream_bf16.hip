@@ -236,6 +236,15 @@ __global__ __launch_bounds__(512, 2) void igemm_stream_bf16_kernel(SgArgs a) {
                     ++n;
                 }
             }
+            // a stage behind the current one: with an odd number of stages the last pass asks for the (clamped) last
+            // stage after the counters have moved on to the tile behind it, which may lie in a sample that does not exist
+            while (cc < 0) {
+                cc += a.ncc;
+                if (tc-- == 0) {
+                    tc = a.tiles_per_row - 1;
+                    --n;
+                }
+            }
             Geo g;
             g.n = n;
             g.G0 = tc * kTW - a.P - a.delta;
