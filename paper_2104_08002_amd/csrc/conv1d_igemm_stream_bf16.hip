@@ -462,10 +462,10 @@ SgPlan sg_plan(const CorrProblem& p) {
         const long nct = static_cast<long>(p.N) * a.tiles_per_row;
         if (nct > 0x7fffffffL / 64 || a.nfg > 65535) return pl;
         a.nct = static_cast<int>(nct);
-        // 13 - 20 taps: the staged kernel's tiles are half as wide, and it is the faster one while the tiles of this
-        // kernel would leave half of the CUs idle (measured: N = 8, C = K = 256, W = 4096, S = 17: 90 us against 118 us;
-        // N = 2, W = 2048, S = 20: 81 us against 62 us)
-        if (JT == 5 && nct * a.nfg <= kNumCU / 2) return pl;
+        // The staged kernel's tiles are half as wide, and it is the faster one while the tiles of this kernel would
+        // leave half of the CUs idle (measured at C = K = 256: N = 8, W = 2048, S = 9: 54 us against 41 us; N = 4,
+        // W = 8192, S = 9: 57 us against 72 us; N = 8, W = 4096, S = 17: 90 us against 118 us)
+        if (nct * a.nfg <= kNumCU / 2) return pl;
         const int fit = kNumCU / a.nfg > 0 ? kNumCU / a.nfg : 1;  // teams that run at the same time
         a.nteams = a.nct < fit ? a.nct : fit;
         pl.grid = a.nteams * a.nfg;

@@ -102,16 +102,22 @@ SMALL = [
     ("res_S12_d16",       3, 40, 24, 5000, 12, 16, 43),
     ("res_S7_d4",         2, 72, 40, 1000, 7,  4,  12),
     ("res_S45_d8_c128",   1, 128, 48, 2000, 45, 8, 77),
-    # forward / backward-data with streamed weights: many filters and channels, 5 to 12 taps
-    ("str_S7_d8",         1, 128, 200, 3000, 7, 8,  21),    # filter count no multiple of 32
-    ("str_S12_d2",        2, 136, 72, 2500, 12, 2,  11),    # odd padding, channel count no multiple of 16
-    ("str_S5_d16",        1, 256, 256, 1024, 5, 16, 32),    # one column tile per sample
-    ("str_S9_d1_odd",     3, 160, 96, 2100, 9,  1,  4),     # an odd number of stages per workgroup
-    ("str_c200_fwd",      1, 200, 72, 1500, 9, 2,  7),     # weights too large for LDS in the forward pass only
-    ("str_k200_bwd",      2, 72, 200, 1100, 12, 4, 0),     # ... in the backward-data pass only; no padding
-    ("str_c264_short",    1, 264, 40, 70,  5,  1,  2),     # one short tile; 33 planes of channels
-    ("str5_fwd",          4, 152, 1056, 200, 17, 2, 16),   # 13 - 20 taps: taken when the tiles fill half of the CUs
-    ("str5_bwd",          4, 1056, 152, 210, 15, 8, 3),    # ... in the backward-data pass
+    # many filters and channels, few taps, few tiles: the staged kernel
+    ("wide_S7_d8",        1, 128, 200, 3000, 7, 8,  21),    # filter count no multiple of 32
+    ("wide_S12_d2",       2, 136, 72, 2500, 12, 2,  11),    # odd padding, channel count no multiple of 16
+    ("wide_S5_d16",       1, 256, 256, 1024, 5, 16, 32),    # one column tile per sample
+    ("wide_S9_d1_odd",    3, 160, 96, 2100, 9,  1,  4),
+    ("wide_c200_fwd",     1, 200, 72, 1500, 9, 2,  7),
+    ("wide_k200_bwd",     2, 72, 200, 1100, 12, 4, 0),     # no padding
+    ("wide_c264_short",   1, 264, 40, 70,  5,  1,  2),     # one short tile; 33 planes of channels
+    # forward / backward-data with streamed weights: weights too large for LDS and more than 128 (tile, filter
+    # group) pairs; 2, 3 and 5 tap groups, in the forward and in the backward-data pass
+    ("str2_fwd",          4, 288, 1056, 200, 7, 1,  3),
+    ("str2_bwd",          5, 1040, 288, 190, 5, 16, 32),    # ragged filter groups
+    ("str3_fwd",          4, 200, 1056, 1100, 9, 4, 16),    # a second tile of a few columns per sample
+    ("str3_bwd",          4, 1056, 200, 200, 12, 2, 11),    # odd padding
+    ("str5_fwd",          4, 232, 1056, 200, 17, 2, 16),    # an odd number of stages, the last tile of the last sample
+    ("str5_bwd",          4, 1056, 232, 210, 15, 8, 3),
     ("c40_halo_gt_width", 2, 40, 24, 200,  51, 8,  200),   # many channels, halo (S-1)d = 400 exceeds W
     ("c40_tiny_Q",        3, 40, 24, 420,  51, 8,  0),     # Q = 20: less than one k-step / one position block pair
 ]
