@@ -112,3 +112,31 @@ def test_wide_layers_dispatch_to_blocked_mfma_kernels():
     small = (g[0], 16, 16) + tuple(g[3:])
     assert binding.conv1d_bwd_weight_workspace_bytes(*g, 0) == binding.conv1d_bwd_weight_workspace_bytes(*small, 0)
     assert binding.conv1d_bwd_weight_workspace_bytes(*g, 0) == 256 * 51 * 256 * 4
+
+
+def test_plan_queries_survive_arbitrary_geometries():
+    """Host logic only: the kernel-family decision and the workspace size of every pass for a few hundred seeded
+    geometries (tiny and large channel counts, widths below one tile, dilations the fast families do not take).
+    Every answer is a known family name; a valid geometry never reports 'invalid', and its workspace is a multiple
+    of 256 bytes that a single MI355X can hold."""
+    import random
+
+    rnd = random.Random(20210408)
+    families = ("smallc_", "igemm_", "generic_")
+    binding.conv1d_set_variant(binding.VARIANT_AUTO)
+    for _ in range(400):
+        N = rnd.choice([1, 2, 3, 5, 16, 64])
+        C = rnd.choice([1, 3, 15, 16, 17, 40, 64, 200, 256, 1040])
+        K = rnd.choice([1, 2, 15, 16, 24, 64, 72, 256, 288, 1056])
+        S = rnd.choice([1, 2, 4, 5, 9, 12, 13, 17, 20, 33, 51, 52, 53, 70])
+        d = rnd.choice([1, 2, 3, 4, 6, 8, 16, 32])
+        W = rnd.choice([(S - 1) * d + 1, 8, 63, 200, 1024, 4097, 60000])
+        P = rnd.choice([0, 1, 3, (S - 1) * d // 2, (S - 1) * d])
+        if W + 2 * P - (S - 1) * d < 1:
+            continue
+        for dt in (0, 1):
+            for i in range(3):
+                name = binding.conv1d_kernel_name(i, N, C, K, W, S, d, P, dt)
+                assert name.startswith(families), (name, N, C, K, W, S, d, P, dt)
+            b = binding.conv1d_bwd_weight_workspace_bytes(N, C, K, W, S, d, P, dt)
+            assert b % 256 == 0 and 0 < b < (64 << 30), (b, N, C, K, W, S, d, P, dt)
