@@ -37,8 +37,12 @@
  *   OVERWRITE their output (beta = 0 in the notation of Eq. 3).  Inputs and
  *   outputs must not alias.  float tensors must be 4-byte aligned, bfloat16
  *   tensors 2-byte aligned; 16-byte alignment (any torch allocation) enables
- *   the fast kernels.  Calls are thread-safe and re-entrant across streams as
- *   long as their outputs and workspaces are distinct.
+ *   the fast kernels.  A bfloat16 weight tensor is read in 4-byte words: if
+ *   it holds an odd number of elements, the 2 bytes behind its last element
+ *   are read too (and ignored), so its allocation must extend to the next
+ *   4-byte boundary, as any device allocation does.  Calls are thread-safe
+ *   and re-entrant across streams as long as their outputs and workspaces
+ *   are distinct.
  *
  * Errors
  *   Every int-returning entry point returns CONV1D_OK (0) or a negative
