@@ -44,10 +44,29 @@
  *   and re-entrant across streams as long as their outputs and workspaces
  *   are distinct.
  *
+ * Non-finite inputs
+ *   Inputs are expected to be finite.  The kernels pad taps and channels up to
+ *   the sizes of their matrix tiles with zero weights (or zero-filled columns)
+ *   that multiply real input values, and 0 * Inf = NaN.  An Inf or NaN input
+ *   element can therefore (a) turn an output that the definition makes +-Inf
+ *   into NaN, and (b) turn outputs into NaN that the definition says do not
+ *   depend on it, but only these:
+ *     conv1d_fwd, conv1d_bwd_data: outputs of the SAME sample within 64*d
+ *       columns of the columns the element contributes to;
+ *     conv1d_bwd_weight: dw[.][c][.] for a non-finite x[n][c][i], and
+ *       dw[k][.][.] for a non-finite dy[n][k][q].
+ *   Every other output is computed as if the input were finite, and every
+ *   output that the definition makes non-finite is non-finite.
+ *
  * Errors
  *   Every int-returning entry point returns CONV1D_OK (0) or a negative
- *   conv1d_status_t; nothing is thrown and errno is untouched.  On an error
- *   no kernel has been launched.
+ *   conv1d_status_t; nothing is thrown and errno is untouched.  Argument errors
+ *   (CONV1D_EINVAL, CONV1D_EUNSUPPORTED, CONV1D_EWORKSPACE) are detected before
+ *   anything is launched.  CONV1D_EHIP reports that the HIP runtime refused a
+ *   launch; a pass that consists of several launches (FP32 layers with more
+ *   than 16 channels whose weights do not fit in LDS; the second stage of
+ *   conv1d_bwd_weight) may have enqueued its earlier kernels by then, so the
+ *   output is unspecified after CONV1D_EHIP.
  */
 #ifndef CONV1D_MI355X_H
 #define CONV1D_MI355X_H
@@ -116,14 +135,18 @@ size_t conv1d_bwd_weight_workspace_bytes(int N, int C, int K, int W, int S, int 
  * dw: device, float, K*C*S (overwritten).
  * workspace: device, 256-byte aligned, at least workspace_bytes >=
  * conv1d_bwd_weight_workspace_bytes(...); contents on entry are ignored and
- * on exit unspecified.  Two calls in flight must not share a workspace. */
+ * on exit unspecified.  Two calls in flight must not share a workspace.
+ * Sizes: about one S*16*16 float tile per workgroup, e.g. 12.5 MB for
+ * N=16, C=K=15, W=60000, S=51, d=8 and 27 MB for N=8, C=K=64, W=20000, S=51. */
 int conv1d_bwd_weight(const void* x, const void* dy, float* dw,
                       void* workspace, size_t workspace_bytes,
                       int N, int C, int K, int W, int S, int dilation, int padding,
                       int dtype, void* stream);
 
 /* Force a kernel family for all later calls of this process (CONV1D_VARIANT_*).
- * Returns CONV1D_EINVAL for an unknown value. Not meant for production use. */
+ * Returns CONV1D_EINVAL for an unknown value.  The setting is one process-wide
+ * atomic: changing it while other threads are inside the library changes the
+ * family of their later launches too.  For experiments and tests only. */
 int conv1d_set_variant(int variant);
 
 /* Name of the kernel the current variant setting selects for a pass

@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 from paper_2104_08002_amd import inputs
-from parity_util import TOL, check_full, check_sampled, gpu_passes, to_device
+from parity_util import assert_parity, check_full, check_sampled, gpu_passes, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -45,9 +45,7 @@ def _run_full(binding, oracle, wl, variant):
     finally:
         binding.conv1d_set_variant(0)
     errs = check_full(oracle, wl, data, got, passes)
-    print(wl.name, variant, errs, flush=True)
-    for p, e in errs.items():
-        assert e <= TOL[wl.dtype], (wl.name, variant, p, e)
+    assert_parity(wl.name, variant, wl.dtype, errs)
     return passes
 
 
@@ -171,9 +169,7 @@ def test_element_aligned_pointers(binding, oracle, case, dtype):
     torch.cuda.synchronize()
     got = {"fwd": y.cpu().numpy(), "bwd_data": dx.cpu().numpy(), "bwd_weight": dw.cpu().numpy()}
     errs = check_full(oracle, wl, data, got)
-    print(wl.name, errs, flush=True)
-    for p, e in errs.items():
-        assert e <= TOL[wl.dtype], (wl.name, p, e)
+    assert_parity(wl.name, "unaligned", wl.dtype, errs)
 
 
 # ---- genomics at full size, the configuration the benchmark times: whole-output comparison ------
@@ -182,27 +178,27 @@ def test_genomics_full_size(binding, oracle, wl):
     _run_full(binding, oracle, wl, "auto")
 
 
-# ---- filter-width x dilation sweep at full size: sampled outputs --------------------------------
+# ---- sampled comparison: only for widths whose whole output the oracle cannot finish in seconds ----
 def _run_sampled(binding, oracle, wl):
     data = inputs.make_inputs(wl)
     got = gpu_passes(wl, to_device(wl, data))
     errs = check_sampled(oracle, wl, data, got, np.random.default_rng(wl.seed))
-    print(wl.name, errs, flush=True)
-    for p, e in errs.items():
-        assert e <= TOL[wl.dtype], (wl.name, p, e)
+    assert_parity(wl.name, "sampled", wl.dtype, errs)
     for k, v in got.items():
         assert np.isfinite(v).all(), (wl.name, k)
 
 
+# ---- filter-width x dilation sweep and the wide configuration at full size, in the launch configuration the
+# ---- benchmark times: whole-output comparison (the oracle needs 1-8 s per pass on the machine's host cores) ----
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 @pytest.mark.parametrize("S", inputs.SWEEP_S)
 @pytest.mark.parametrize("d", inputs.SWEEP_D)
-def test_sweep_full_size_sampled(binding, oracle, S, d, dtype):
-    _run_sampled(binding, oracle, inputs.sweep_point(S, d, dtype))
+def test_sweep_full_size(binding, oracle, S, d, dtype):
+    _run_full(binding, oracle, inputs.sweep_point(S, d, dtype), "auto")
 
 
-def test_wide_full_size_sampled(binding, oracle):
-    _run_sampled(binding, oracle, inputs.WIDE_BF16)
+def test_wide_full_size(binding, oracle):
+    _run_full(binding, oracle, inputs.WIDE_BF16, "auto")
 
 
 # ---- long segments (the paper's 600000-wide inputs, Section 4.5.3): one sample, sampled outputs -----
@@ -268,8 +264,7 @@ def test_outputs_are_overwritten(binding, oracle, wl):
     binding.conv1d_bwd_weight(dev["x"], dev["dy"], wl.S, wl.d, wl.P, out=dw, workspace=ws.view(torch.uint8))
     torch.cuda.synchronize()
     got = {"fwd": y.cpu().numpy(), "bwd_data": dx.cpu().numpy(), "bwd_weight": dw.cpu().numpy()}
-    for p, e in check_full(oracle, wl, data, got).items():
-        assert e <= TOL["fp32"], (p, e)
+    assert_parity(wl.name, "nan_prefilled", "fp32", check_full(oracle, wl, data, got))
 
 
 # ---- a non-default stream --------------------------------------------------------------------------
@@ -287,5 +282,4 @@ def test_runs_on_callers_stream(binding, oracle):
         dw = binding.conv1d_bwd_weight(dev["x"], dev["dy"], wl.S, wl.d, wl.P)
     st.synchronize()
     got = {"fwd": y.cpu().numpy(), "bwd_data": dx.cpu().numpy(), "bwd_weight": dw.cpu().numpy()}
-    for p, e in check_full(oracle, wl, data, got).items():
-        assert e <= TOL["bf16"], (p, e)
+    assert_parity(wl.name, "side_stream", "bf16", check_full(oracle, wl, data, got))
