@@ -84,7 +84,7 @@ typedef enum {
     CONV1D_EINVAL = -1,       /* null pointer, non-positive size, d < 1, P < 0, Q <= 0, bad dtype, misaligned pointer */
     CONV1D_EUNSUPPORTED = -2, /* a forced kernel variant cannot run this geometry, or sizes overflow 32-bit tile indices */
     CONV1D_EWORKSPACE = -3,   /* workspace missing or smaller than conv1d_bwd_weight_workspace_bytes() */
-    CONV1D_EHIP = -4          /* the HIP runtime refused a launch (see hipGetLastError) */
+    CONV1D_EHIP = -4          /* the HIP runtime refused a launch */
 } conv1d_status_t;
 
 /* Kernel families.  AUTO lets the library choose from the geometry; the others

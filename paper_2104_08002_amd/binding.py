@@ -32,13 +32,14 @@ class Conv1dError(RuntimeError):
 
 
 def load() -> ctypes.CDLL:
-    """Load the shared library (building it first only when it does not exist)."""
+    """Load the shared library; build it first when it is missing or was built from other sources than the tree
+    holds (a stale library would silently test and time old kernels)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
-        from . import build as _build
+    from . import build as _build
 
+    if _build.needs_build():
         _build.build(verbose=False)
     lib = ctypes.CDLL(LIB_PATH)
     i, vp, sz = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
@@ -172,3 +173,4 @@ def conv1d_bwd_weight(x, dy, S: int, dilation: int, padding: int, out=None, work
                                     ws.numel() * ws.element_size(), N, C, K, W, S, dilation, padding, code,
                                     _stream_ptr(stream)))
     return dw
+

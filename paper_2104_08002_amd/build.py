@@ -6,6 +6,7 @@ hipcc cross-compiles without a GPU.  Each translation unit is compiled to an obj
 from __future__ import annotations
 
 import concurrent.futures
+import hashlib
 import os
 import shutil
 import subprocess
@@ -14,6 +15,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libconv1d_mi355x.so")
+STAMP = LIB + ".srchash"   # hash of the sources the library was built from (travels with the library)
 OBJ_DIR = os.path.join(HERE, "_build")
 
 # packed FP32 VALU forms are switched off for all device code on this machine pool
@@ -37,10 +39,21 @@ def sources():
     return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
+def source_hash() -> str:
+    """SHA-256 over every file the library is compiled from (csrc/*.hip, csrc/*.h, include/conv1d.h) and the flags."""
+    h = hashlib.sha256(" ".join(HIP_FLAGS).encode())
+    deps = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".h")))
+    deps.append(os.path.join(os.path.dirname(HERE), "include", "conv1d.h"))
+    for d in deps:
+        h.update(os.path.basename(d).encode())
+        with open(d, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
-    extra = ["-DCONV1D_DEV_FEW_KERNELS"] if os.environ.get("CONV1D_DEV_FEW_KERNELS") else []  # faster edit-compile loop
-    cmd = [hipcc(), *HIP_FLAGS, *extra, "-Rpass-analysis=kernel-resource-usage", "-c", src, "-o", obj]
+    cmd = [hipcc(), *HIP_FLAGS, "-Rpass-analysis=kernel-resource-usage", "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     lines = (r.stdout + r.stderr).splitlines()
     # a kernel that keeps an array in scratch memory runs orders of magnitude slower than intended: say so loudly
@@ -64,24 +77,32 @@ def _compile(src: str) -> str:
 def build(verbose: bool = True) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     srcs = sources()
+    stamp = source_hash()
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
         objs = list(ex.map(_compile, srcs))
     cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
+    with open(STAMP, "w") as f:
+        f.write(stamp + "\n")
     if verbose:
-        print(f"built {LIB}")
+        print(f"built {LIB} from sources {stamp}")
     return LIB
 
 
+def built_hash():
+    """Hash of the sources the existing library was built from; None when there is no library or no record."""
+    if not os.path.exists(LIB) or not os.path.exists(STAMP):
+        return None
+    with open(STAMP) as f:
+        return f.read().strip()
+
+
 def needs_build() -> bool:
-    if not os.path.exists(LIB):
-        return True
-    t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
-    deps.append(os.path.join(os.path.dirname(HERE), "include", "conv1d.h"))
-    return any(os.path.getmtime(d) > t for d in deps)
+    """True when the library is missing or was built from other sources than the ones in the tree (by content,
+    not by time stamps: copies of the tree do not keep those)."""
+    return built_hash() != source_hash()
 
 
 if __name__ == "__main__":

@@ -1,10 +1,31 @@
 // C ABI of the conv1d library: argument validation, kernel-family dispatch, status strings.
 // Every entry point only enqueues kernels on the caller's stream.
 #include <atomic>
+#include <mutex>
+#include <unordered_map>
 
 #include "conv1d_internal.h"
 
 using namespace conv1d;
+
+namespace conv1d {
+
+hipError_t ensure_dynamic_lds(const void* kern, size_t bytes) {
+    static std::mutex mutex;
+    static std::unordered_map<uintptr_t, size_t> granted;  // key: kernel address mixed with the GPU's index
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uintptr_t key = reinterpret_cast<uintptr_t>(kern) ^ (static_cast<uintptr_t>(dev + 1) << 56);
+    std::lock_guard<std::mutex> lock(mutex);
+    auto it = granted.find(key);
+    if (it != granted.end() && it->second >= bytes) return hipSuccess;
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+    if (e == hipSuccess) granted[key] = bytes;
+    return e;
+}
+
+}  // namespace conv1d
 
 namespace {
 
@@ -98,6 +119,20 @@ int run_corr(const CorrProblem& p, void* stream) {
     return e == hipSuccess ? CONV1D_OK : CONV1D_EHIP;
 }
 
+int run_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t wsb, int dtype, void* stream) {
+    WgradProblem p = wgrad_problem(g, x, dy, dw, ws, wsb, dtype == CONV1D_BF16);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    switch (pick_wgrad(p)) {
+        case CONV1D_VARIANT_GENERIC: e = generic_wgrad_launch(p, st); break;
+        case CONV1D_VARIANT_SMALLC: e = smallc_wgrad_launch(p, st); break;
+        case CONV1D_VARIANT_IGEMM: e = igemm_wgrad_launch(p, st); break;
+        default: return CONV1D_EUNSUPPORTED;
+    }
+    if (e == hipErrorInvalidValue) return CONV1D_EUNSUPPORTED;
+    return e == hipSuccess ? CONV1D_OK : CONV1D_EHIP;
+}
+
 const char* family_name(int fam, int bf16, bool wgrad) {
     switch (fam) {
         case CONV1D_VARIANT_GENERIC: return bf16 ? (wgrad ? "generic_wgrad_bf16" : "generic_fma_bf16") : (wgrad ? "generic_wgrad_fp32" : "generic_fma_fp32");
@@ -160,17 +195,7 @@ int conv1d_bwd_weight(const void* x, const void* dy, float* dw, void* workspace,
     const size_t need = conv1d_bwd_weight_workspace_bytes(N, C, K, W, S, dilation, padding, dtype);
     if (!workspace || workspace_bytes < need) return CONV1D_EWORKSPACE;
     if (!aligned(workspace, 256)) return CONV1D_EINVAL;
-    WgradProblem p = wgrad_problem(g, x, dy, dw, workspace, workspace_bytes, dtype == CONV1D_BF16);
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t e;
-    switch (pick_wgrad(p)) {
-        case CONV1D_VARIANT_GENERIC: e = generic_wgrad_launch(p, st); break;
-        case CONV1D_VARIANT_SMALLC: e = smallc_wgrad_launch(p, st); break;
-        case CONV1D_VARIANT_IGEMM: e = igemm_wgrad_launch(p, st); break;
-        default: return CONV1D_EUNSUPPORTED;
-    }
-    if (e == hipErrorInvalidValue) return CONV1D_EUNSUPPORTED;
-    return e == hipSuccess ? CONV1D_OK : CONV1D_EHIP;
+    return run_wgrad(g, x, dy, dw, workspace, workspace_bytes, dtype, stream);
 }
 
 int conv1d_set_variant(int variant) {

@@ -387,11 +387,7 @@ struct BlkPlan {
 };
 
 struct Shape { int FB, NT; };
-#ifdef CONV1D_DEV_FEW_KERNELS
-constexpr Shape kShapes[] = {{1, 17}, {4, 9}};
-#else
 constexpr Shape kShapes[] = {{1, 5}, {1, 9}, {1, 17}, {1, 26}, {2, 9}, {2, 17}, {4, 5}, {4, 9}};
-#endif
 
 // Geometry of one candidate (shape, channel blocks per workgroup, chunk length); false if it does not fit.
 bool blk_geometry(const WgradProblem& p, int FB, int NT, int ncbw, int QC, BlkPlan& pl) {
@@ -503,11 +499,9 @@ BlkPlan blk_plan(const WgradProblem& p) {
 template <int FB, int NT>
 hipError_t blk_launch(const BlkPlan& pl, hipStream_t st) {
     auto kern = pl.fast ? blocked_wgrad_bf16_kernel<FB, NT, true> : blocked_wgrad_bf16_kernel<FB, NT, false>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(pl.lds_bytes));
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), pl.lds_bytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(pl.grid), dim3(512), pl.lds_bytes, st, pl.a);
-    return hipGetLastError();
+    return launch_kernel(kern, dim3(pl.grid), dim3(512), pl.lds_bytes, st, pl.a);
 }
 
 }  // namespace
@@ -525,23 +519,20 @@ hipError_t blocked_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     hipError_t e = hipErrorInvalidValue;
     const int key = pl.FB * 100 + pl.NT;
     switch (key) {
-#ifndef CONV1D_DEV_FEW_KERNELS
         case 105: e = blk_launch<1, 5>(pl, st); break;
         case 109: e = blk_launch<1, 9>(pl, st); break;
         case 126: e = blk_launch<1, 26>(pl, st); break;
         case 209: e = blk_launch<2, 9>(pl, st); break;
         case 217: e = blk_launch<2, 17>(pl, st); break;
         case 405: e = blk_launch<4, 5>(pl, st); break;
-#endif
         case 117: e = blk_launch<1, 17>(pl, st); break;
         case 409: e = blk_launch<4, 9>(pl, st); break;
         default: break;
     }
     if (e != hipSuccess) return e;
     const long nel = static_cast<long>(pl.grid / pl.a.nstrips) * pl.tile;
-    hipLaunchKernelGGL(blocked_wgrad_reduce_kernel, dim3(cdiv(nel, 64)), dim3(256), 0, st, static_cast<const float*>(p.ws), p.dw, pl.a, pl.FB,
+    return launch_kernel(blocked_wgrad_reduce_kernel, dim3(cdiv(nel, 64)), dim3(256), 0, st, static_cast<const float*>(p.ws), p.dw, pl.a, pl.FB,
                        pl.NT);
-    return hipGetLastError();
 }
 
 }  // namespace conv1d

@@ -87,12 +87,8 @@ hipError_t generic_corr_launch(const CorrProblem& p, hipStream_t st) {
     const int otiles = cdiv(p.Wout, kThreads);
     const long blocks = static_cast<long>(p.N) * p.M * otiles;
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-    if (p.bf16) {
-        hipLaunchKernelGGL(generic_corr_kernel<true>, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, st, p, otiles);
-    } else {
-        hipLaunchKernelGGL(generic_corr_kernel<false>, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, st, p, otiles);
-    }
-    return hipGetLastError();
+    return launch_kernel(p.bf16 ? generic_corr_kernel<true> : generic_corr_kernel<false>, dim3(static_cast<unsigned>(blocks)),
+                         dim3(kThreads), 0, st, p, otiles);
 }
 
 size_t generic_wgrad_workspace(const WgradProblem& p) {
@@ -105,16 +101,11 @@ hipError_t generic_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     const long kcs = static_cast<long>(p.K) * p.C * p.S;
     const long blocks = kcs * nchunks;
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-    if (p.bf16) {
-        hipLaunchKernelGGL(generic_wgrad_partial_kernel<true>, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, st, p, nchunks, npc);
-    } else {
-        hipLaunchKernelGGL(generic_wgrad_partial_kernel<false>, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, st, p, nchunks, npc);
-    }
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_kernel(p.bf16 ? generic_wgrad_partial_kernel<true> : generic_wgrad_partial_kernel<false>,
+                                 dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, st, p, nchunks, npc);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(generic_wgrad_reduce_kernel, dim3(cdiv(kcs, kThreads)), dim3(kThreads), 0, st,
+    return launch_kernel(generic_wgrad_reduce_kernel, dim3(cdiv(kcs, kThreads)), dim3(kThreads), 0, st,
                        static_cast<const float*>(p.ws), p.dw, kcs, nchunks);
-    return hipGetLastError();
 }
 
 }  // namespace conv1d

@@ -481,11 +481,9 @@ bool igemm_bf16_corr_supported(const CorrProblem& p) { return ig_plan(p).ok; }
 hipError_t igemm_bf16_corr_launch(const CorrProblem& p, hipStream_t st) {
     const IgPlan pl = ig_plan(p);
     if (!pl.ok) return hipErrorInvalidValue;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(igemm_corr_bf16_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(pl.lds_bytes));
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(igemm_corr_bf16_kernel), pl.lds_bytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(igemm_corr_bf16_kernel, dim3(pl.grid), dim3(512), pl.lds_bytes, st, pl.a);
-    return hipGetLastError();
+    return launch_kernel(igemm_corr_bf16_kernel, dim3(pl.grid), dim3(512), pl.lds_bytes, st, pl.a);
 }
 
 }  // namespace conv1d

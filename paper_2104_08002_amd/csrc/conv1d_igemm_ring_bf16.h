@@ -447,11 +447,9 @@ struct RgPlan {
 template <int D, int FB, int JT, int KT>
 hipError_t rg_launch(const RgPlan& pl, hipStream_t st) {
     auto kern = igemm_ring_bf16_kernel<D, FB, JT, KT>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(pl.lds_bytes));
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), pl.lds_bytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(pl.grid), dim3(512), pl.lds_bytes, st, pl.a);
-    return hipGetLastError();
+    return launch_kernel(kern, dim3(pl.grid), dim3(512), pl.lds_bytes, st, pl.a);
 }
 
 template <int D, int KT>
@@ -459,7 +457,6 @@ hipError_t rg_launch_dk(const RgPlan& pl, hipStream_t st) {
     switch (pl.FB * 100 + pl.JT) {
         case 113: return rg_launch<D, 1, 13, KT>(pl, st);
         case 213: return rg_launch<D, 2, 13, KT>(pl, st);
-#ifndef CONV1D_DEV_FEW_KERNELS
         case 109: return rg_launch<D, 1, 9, KT>(pl, st);
         case 209: return rg_launch<D, 2, 9, KT>(pl, st);
         case 105: return rg_launch<D, 1, 5, KT>(pl, st);
@@ -468,16 +465,13 @@ hipError_t rg_launch_dk(const RgPlan& pl, hipStream_t st) {
         case 203: return rg_launch<D, 2, 3, KT>(pl, st);
         case 102: return rg_launch<D, 1, 2, KT>(pl, st);
         case 202: return rg_launch<D, 2, 2, KT>(pl, st);
-#endif
         default: return hipErrorInvalidValue;
     }
 }
 
 template <int D>
 hipError_t rg_launch_d(const RgPlan& pl, hipStream_t st) {
-#ifndef CONV1D_DEV_FEW_KERNELS
     if (pl.KT == 5) return rg_launch_dk<D, 5>(pl, st);
-#endif
     return rg_launch_dk<D, 8>(pl, st);
 }
 

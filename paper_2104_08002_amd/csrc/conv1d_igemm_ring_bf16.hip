@@ -22,11 +22,7 @@ RgPlan rg_plan_kt(const CorrProblem& p, int kT) {
     pl.ok = false;
     if (!p.bf16 || p.accumulate) return pl;
     if (p.R <= 16 && p.M <= 16) return pl;
-#ifdef CONV1D_DEV_FEW_KERNELS
-    if (p.d != 8) return pl;
-#else
     if (p.d != 1 && p.d != 2 && p.d != 4 && p.d != 8 && p.d != 16) return pl;
-#endif
     if (p.S < 5 || p.S > 52) return pl;
     if ((p.Win & 1) || (p.in_sn & 1) || (reinterpret_cast<uintptr_t>(p.in) & 3) || p.Win < 2) return pl;
     if (reinterpret_cast<uintptr_t>(p.wt) & 3) return pl;
@@ -36,9 +32,6 @@ RgPlan rg_plan_kt(const CorrProblem& p, int kT) {
     if (static_cast<long>(p.R) * p.Win >= (1L << 30)) return pl;
     if (static_cast<long>(p.M) * p.R * p.S >= (1L << 31) || p.M * p.w_sm >= (1L << 31) || p.R * p.w_sr >= (1L << 31)) return pl;
     const int JT = p.S <= 8 ? 2 : (p.S <= 12 ? 3 : (p.S <= 20 ? 5 : (p.S <= 36 ? 9 : 13)));
-#ifdef CONV1D_DEV_FEW_KERNELS
-    if (JT != 13) return pl;
-#endif
     RgArgs& a = pl.a;
     a.in = static_cast<const unsigned short*>(p.in);
     a.wt = static_cast<const unsigned short*>(p.wt);
@@ -111,13 +104,11 @@ RgPlan rg_plan_kt(const CorrProblem& p, int kT) {
 // workgroup walks whole tiles; 2.5 tiles per workgroup cost as much as 3).
 RgPlan rg_plan(const CorrProblem& p) {
     RgPlan best = rg_plan_kt(p, 8);
-#ifndef CONV1D_DEV_FEW_KERNELS
     if (best.ok) {
         const RgPlan alt = rg_plan_kt(p, 5);
         auto makespan = [](const RgPlan& pl) { return static_cast<long>(cdiv(pl.a.nct, pl.a.nteams)) * (2 * pl.KT + 1); };
         if (alt.ok && alt.FB == best.FB && makespan(alt) * 10 < makespan(best) * 9) best = alt;
     }
-#endif
     return best;
 }
 

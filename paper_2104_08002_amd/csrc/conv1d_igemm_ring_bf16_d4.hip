@@ -4,11 +4,7 @@
 namespace conv1d {
 namespace rg {
 
-#ifdef CONV1D_DEV_FEW_KERNELS
-hipError_t launch_d4(const RgPlan&, hipStream_t) { return hipErrorInvalidValue; }
-#else
 hipError_t launch_d4(const RgPlan& pl, hipStream_t st) { return rg_launch_d<4>(pl, st); }
-#endif
 
 }  // namespace rg
 }  // namespace conv1d

@@ -408,11 +408,7 @@ SgPlan sg_plan(const CorrProblem& p) {
     pl.ok = false;
     if (!p.bf16 || p.accumulate) return pl;
     if (p.M <= 16 || p.R <= 16) return pl;
-#ifdef CONV1D_DEV_FEW_KERNELS
-    if (p.d != 4) return pl;
-#else
     if (p.d != 1 && p.d != 2 && p.d != 4 && p.d != 8 && p.d != 16) return pl;
-#endif
     if (p.S < 5 || p.S > 20) return pl;
     if ((p.Win & 1) || (p.in_sn & 1) || (reinterpret_cast<uintptr_t>(p.in) & 3) || p.Win < 2) return pl;
     if (reinterpret_cast<uintptr_t>(p.wt) & 3) return pl;
@@ -479,11 +475,9 @@ SgPlan sg_plan(const CorrProblem& p) {
 template <int D, int JT>
 hipError_t sg_launch(const SgPlan& pl, hipStream_t st) {
     auto kern = igemm_stream_bf16_kernel<D, JT>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(pl.lds_bytes));
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), pl.lds_bytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(pl.grid), dim3(512), pl.lds_bytes, st, pl.a);
-    return hipGetLastError();
+    return launch_kernel(kern, dim3(pl.grid), dim3(512), pl.lds_bytes, st, pl.a);
 }
 
 template <int D>
@@ -491,9 +485,7 @@ hipError_t sg_launch_d(const SgPlan& pl, hipStream_t st) {
     switch (pl.JT) {
         case 2: return sg_launch<D, 2>(pl, st);
         case 3: return sg_launch<D, 3>(pl, st);
-#ifndef CONV1D_DEV_FEW_KERNELS
         case 5: return sg_launch<D, 5>(pl, st);
-#endif
         default: return hipErrorInvalidValue;
     }
 }
@@ -506,12 +498,10 @@ hipError_t igemm_stream_bf16_corr_launch(const CorrProblem& p, hipStream_t st) {
     const SgPlan pl = sg_plan(p);
     if (!pl.ok) return hipErrorInvalidValue;
     switch (pl.D) {
-#ifndef CONV1D_DEV_FEW_KERNELS
         case 1: return sg_launch_d<1>(pl, st);
         case 2: return sg_launch_d<2>(pl, st);
         case 8: return sg_launch_d<8>(pl, st);
         case 16: return sg_launch_d<16>(pl, st);
-#endif
         case 4: return sg_launch_d<4>(pl, st);
         default: return hipErrorInvalidValue;
     }

@@ -6,6 +6,9 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <utility>
+
 #include "../../include/conv1d.h"
 
 namespace conv1d {
@@ -134,5 +137,29 @@ __device__ __forceinline__ int xcd_logical_id(int b, int grid) {
 }
 
 inline int cdiv(long a, long b) { return static_cast<int>((a + b - 1) / b); }
+
+// ---- host helpers: launches ---------------------------------------------------------------------
+// Raise a kernel's dynamic LDS limit to `bytes` on the current GPU.  The runtime call costs microseconds, so the
+// largest size granted so far is remembered per (kernel, GPU) and the call is made only when it has to grow.
+hipError_t ensure_dynamic_lds(const void* kern, size_t bytes);
+
+namespace detail {
+template <typename Tuple, size_t... I>
+inline void arg_pointers(Tuple& vals, void** ptrs, std::index_sequence<I...>) {
+    ((ptrs[I] = static_cast<void*>(&std::get<I>(vals))), ...);
+}
+}  // namespace detail
+
+// Launch `kern` and return the status of THIS launch (hipGetLastError would also report, and clear, an error that
+// an unrelated earlier call of the host program left behind).
+template <typename... Params, typename... Args>
+inline hipError_t launch_kernel(void (*kern)(Params...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t st,
+                                const Args&... args) {
+    static_assert(sizeof...(Params) == sizeof...(Args), "kernel argument count");
+    std::tuple<Params...> vals(static_cast<Params>(args)...);
+    void* ptrs[sizeof...(Params) > 0 ? sizeof...(Params) : 1];
+    detail::arg_pointers(vals, ptrs, std::index_sequence_for<Params...>{});
+    return hipLaunchKernel(reinterpret_cast<const void*>(kern), grid, block, ptrs, lds_bytes, st);
+}
 
 }  // namespace conv1d

@@ -375,15 +375,13 @@ CorrF32Plan corr_f32_plan(const CorrProblem& p, bool blocks = false) {
 template <int RC, bool FAST>
 hipError_t corr_f32_launch_f(const CorrProblem& p, const CorrF32Plan& pl, hipStream_t st) {
     auto kern = smallc_corr_f32_kernel<RC, kCorrT, kCorrMaxS, FAST>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(pl.lds_bytes));
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), pl.lds_bytes);
     if (e != hipSuccess) return e;
     // one workgroup per CU in total: the filter blocks (grid rows) share the strips of tiles between them
     const int strips = cdiv(kNumCU, cdiv(p.M, 16));
     const int grid = pl.ntiles < strips ? pl.ntiles : strips;
-    hipLaunchKernelGGL(kern, dim3(grid, cdiv(p.M, 16)), dim3(512), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.LP4, pl.nbuf,
+    return launch_kernel(kern, dim3(grid, cdiv(p.M, 16)), dim3(512), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.LP4, pl.nbuf,
                        pl.raw_in_lds, pl.ncb, pl.vec_out);
-    return hipGetLastError();
 }
 
 template <int RC>
@@ -733,13 +731,11 @@ WgradF32Plan wgrad_f32_plan(const WgradProblem& p, bool blocks = false) {
 template <int NT>
 hipError_t wgrad_f32_launch_nt(const WgradProblem& p, const WgradF32Plan& pl, hipStream_t st) {
     auto kern = pl.fast ? smallc_wgrad_f32_kernel<NT, kWgradMaxS, true> : smallc_wgrad_f32_kernel<NT, kWgradMaxS, false>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(pl.lds_bytes));
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), pl.lds_bytes);
     if (e != hipSuccess) return e;
     const int pairs = cdiv(p.K, 16) * cdiv(p.C, 16);
-    hipLaunchKernelGGL(kern, dim3(pl.grid, pairs), dim3(512), pl.lds_bytes, st, p, pl.chunks_per_row, pl.nchunks, pl.QC, pl.LQS, pl.LXS,
+    return launch_kernel(kern, dim3(pl.grid, pairs), dim3(512), pl.lds_bytes, st, p, pl.chunks_per_row, pl.nchunks, pl.QC, pl.LQS, pl.LXS,
                        pl.LX4);
-    return hipGetLastError();
 }
 
 }  // namespace
@@ -747,8 +743,7 @@ hipError_t wgrad_f32_launch_nt(const WgradProblem& p, const WgradF32Plan& pl, hi
 hipError_t smallc_wgrad_reduce_launch(const float* ws, float* dw, int K, int C, int S, long dw_sk, long dw_sc, int nwg,
                                       hipStream_t st) {
     const int pairs = cdiv(K, 16) * cdiv(C, 16);
-    hipLaunchKernelGGL(smallc_wgrad_reduce_kernel, dim3(S * 4, pairs), dim3(512), 0, st, ws, dw, K, C, S, dw_sk, dw_sc, nwg);
-    return hipGetLastError();
+    return launch_kernel(smallc_wgrad_reduce_kernel, dim3(S * 4, pairs), dim3(512), 0, st, ws, dw, K, C, S, dw_sk, dw_sc, nwg);
 }
 
 hipError_t smallc_corr_launch_impl(const CorrProblem& p, bool blocks, hipStream_t st);

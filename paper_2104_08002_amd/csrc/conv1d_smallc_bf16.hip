@@ -440,12 +440,10 @@ CorrPlan corr_plan(const CorrProblem& p) {
 template <int NP, int G, bool FAST>
 hipError_t corr_launch_f(const CorrProblem& p, const CorrPlan& pl, hipStream_t st) {
     auto kern = smallc_corr_bf16_kernel<NP, G, kCorrT, kCorrMaxT, FAST>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(pl.lds_bytes));
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), pl.lds_bytes);
     if (e != hipSuccess) return e;
     const int grid = pl.ntiles < kNumCU ? pl.ntiles : kNumCU;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.vec_out);
-    return hipGetLastError();
+    return launch_kernel(kern, dim3(grid), dim3(512), pl.lds_bytes, st, p, pl.tiles_per_row, pl.ntiles, pl.LPS, pl.vec_out);
 }
 
 template <int NP, int G>
@@ -456,13 +454,11 @@ hipError_t corr_launch_t(const CorrProblem& p, const CorrPlan& pl, hipStream_t s
 template <int NP>
 hipError_t corr_launch_np(const CorrProblem& p, const CorrPlan& pl, hipStream_t st) {
     switch (pl.G) {
-#ifndef CONV1D_DEV_FEW_KERNELS
         case 1: return corr_launch_t<NP, 1>(p, pl, st);
         case 4:
             return corr_launch_t<NP, 4>(p, pl, st);
         case 8: return corr_launch_t<NP, 8>(p, pl, st);
         case 16: return corr_launch_t<NP, 16>(p, pl, st);
-#endif
         case 2: return corr_launch_t<NP, 2>(p, pl, st);
         default: return corr_launch_t<NP, 0>(p, pl, st);
     }
@@ -725,13 +721,11 @@ hipError_t smallc_bf16_corr_launch(const CorrProblem& p, hipStream_t st) {
     const CorrPlan pl = corr_plan(p);
     if (!pl.ok) return hipErrorInvalidValue;
     switch (pl.NP) {
-#ifndef CONV1D_DEV_FEW_KERNELS
         case 3: return corr_launch_np<3>(p, pl, st);
         case 5: return corr_launch_np<5>(p, pl, st);
         case 9: return corr_launch_np<9>(p, pl, st);
         case 13: return corr_launch_np<13>(p, pl, st);
         case 17: return corr_launch_np<17>(p, pl, st);
-#endif
         case 26: return corr_launch_np<26>(p, pl, st);
         default: return hipErrorInvalidValue;
     }
@@ -747,12 +741,8 @@ size_t smallc_bf16_wgrad_workspace(const WgradProblem& p) {
 hipError_t smallc_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     const WgradPlan pl = wgrad_plan(p);
     if (!pl.ok) return hipErrorInvalidValue;
-    if (pl.fast) {
-        hipLaunchKernelGGL(smallc_wgrad_bf16_d8_kernel<true>, dim3(pl.grid), dim3(512), 0, st, p, pl.SPR, pl.UPS, pl.units_per_row);
-    } else {
-        hipLaunchKernelGGL(smallc_wgrad_bf16_d8_kernel<false>, dim3(pl.grid), dim3(512), 0, st, p, pl.SPR, pl.UPS, pl.units_per_row);
-    }
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_kernel(pl.fast ? smallc_wgrad_bf16_d8_kernel<true> : smallc_wgrad_bf16_d8_kernel<false>, dim3(pl.grid),
+                                 dim3(512), 0, st, p, pl.SPR, pl.UPS, pl.units_per_row);
     if (e != hipSuccess) return e;
     return smallc_wgrad_reduce_launch(static_cast<const float*>(p.ws), p.dw, p.K, p.C, p.S, p.dw_sk, p.dw_sc, pl.grid, st);
 }

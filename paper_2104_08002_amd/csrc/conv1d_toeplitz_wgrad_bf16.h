@@ -486,11 +486,9 @@ constexpr int kNTWs[] = {13, 9, 5, 3, 2};  // taps per consumer wave (a tap grou
 template <int D, int FB, int NTW>
 hipError_t launch(const TzPlan& pl, hipStream_t st) {
     auto kern = pl.fast ? toeplitz_wgrad_bf16_kernel<D, FB, NTW, true> : toeplitz_wgrad_bf16_kernel<D, FB, NTW, false>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(pl.lds_bytes));
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), pl.lds_bytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(pl.grid), dim3(512), pl.lds_bytes, st, pl.a);
-    return hipGetLastError();
+    return launch_kernel(kern, dim3(pl.grid), dim3(512), pl.lds_bytes, st, pl.a);
 }
 
 // every (filter blocks, taps per wave) shape of one dilation; one translation unit per dilation
@@ -499,7 +497,6 @@ hipError_t launch_dilation(const TzPlan& pl, hipStream_t st) {
     switch (pl.FB * 100 + pl.NTW) {
         case 113: return launch<D, 1, 13>(pl, st);
         case 213: return launch<D, 2, 13>(pl, st);
-#ifndef CONV1D_DEV_FEW_KERNELS
         case 109: return launch<D, 1, 9>(pl, st);
         case 209: return launch<D, 2, 9>(pl, st);
         case 105: return launch<D, 1, 5>(pl, st);
@@ -508,7 +505,6 @@ hipError_t launch_dilation(const TzPlan& pl, hipStream_t st) {
         case 203: return launch<D, 2, 3>(pl, st);
         case 102: return launch<D, 1, 2>(pl, st);
         case 202: return launch<D, 2, 2>(pl, st);
-#endif
         default: return hipErrorInvalidValue;
     }
 }

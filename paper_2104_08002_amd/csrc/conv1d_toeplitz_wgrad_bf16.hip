@@ -111,11 +111,7 @@ TzPlan tz_plan(const WgradProblem& p) {
     TzPlan pl{};
     pl.ok = false;
     if (!p.bf16) return pl;
-#ifdef CONV1D_DEV_FEW_KERNELS
-    if (p.d != 4 && p.d != 8) return pl;
-#else
     if (p.d != 1 && p.d != 2 && p.d != 4 && p.d != 8 && p.d != 16) return pl;
-#endif
     if (p.dw_sc != p.S || p.dw_sk != static_cast<long>(p.C) * p.S) return pl;  // writes the whole dw tensor
     if (static_cast<long>(p.C) * p.W >= (1L << 30) || static_cast<long>(p.K) * p.Q >= (1L << 30)) return pl;
     if (static_cast<long>(p.K) * p.C * p.S >= (1L << 31)) return pl;
@@ -123,9 +119,6 @@ TzPlan tz_plan(const WgradProblem& p) {
     // wasted the blocked kernel, whose tap groups are finer, is the better choice
     int best = 0, best_slots = 0;
     for (int ntw : tz::kNTWs) {
-#ifdef CONV1D_DEV_FEW_KERNELS
-        if (ntw != 13) continue;
-#endif
         const int slots = cdiv(p.S, 4 * ntw) * 4 * ntw;
         if (best == 0 || slots < best_slots) { best = ntw; best_slots = slots; }
     }
@@ -187,9 +180,8 @@ hipError_t toeplitz_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     }
     if (e != hipSuccess) return e;
     const long nel = static_cast<long>(pl.grid / pl.a.nstrips) * pl.tile;
-    hipLaunchKernelGGL(toeplitz_wgrad_reduce_kernel, dim3(cdiv(nel, 64)), dim3(256), 0, st, static_cast<const float*>(p.ws), p.dw, pl.a, pl.FB,
+    return launch_kernel(toeplitz_wgrad_reduce_kernel, dim3(cdiv(nel, 64)), dim3(256), 0, st, static_cast<const float*>(p.ws), p.dw, pl.a, pl.FB,
                        pl.NTW);
-    return hipGetLastError();
 }
 
 }  // namespace conv1d

@@ -4,11 +4,7 @@
 namespace conv1d {
 namespace tz {
 
-#ifdef CONV1D_DEV_FEW_KERNELS
-hipError_t launch_d2(const TzPlan&, hipStream_t) { return hipErrorInvalidValue; }
-#else
 hipError_t launch_d2(const TzPlan& pl, hipStream_t st) { return launch_dilation<2>(pl, st); }
-#endif
 
 }  // namespace tz
 }  // namespace conv1d
