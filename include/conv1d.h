@@ -84,7 +84,8 @@ typedef enum {
     CONV1D_EINVAL = -1,       /* null pointer, non-positive size, d < 1, P < 0, Q <= 0, bad dtype, misaligned pointer */
     CONV1D_EUNSUPPORTED = -2, /* a forced kernel variant cannot run this geometry, or sizes overflow 32-bit tile indices */
     CONV1D_EWORKSPACE = -3,   /* workspace missing or smaller than conv1d_bwd_weight_workspace_bytes() */
-    CONV1D_EHIP = -4          /* the HIP runtime refused a launch */
+    CONV1D_EHIP = -4,         /* the HIP runtime refused a launch */
+    CONV1D_ESCRATCH = -5      /* conv1d_bwd_weight_noalloc: the geometry needs more than CONV1D_NOALLOC_SCRATCH_BYTES */
 } conv1d_status_t;
 
 /* Kernel families.  AUTO lets the library choose from the geometry; the others
@@ -142,6 +143,26 @@ int conv1d_bwd_weight(const void* x, const void* dy, float* dw,
                       void* workspace, size_t workspace_bytes,
                       int N, int C, int K, int W, int S, int dilation, int padding,
                       int dtype, void* stream);
+
+/* conv1d_bwd_weight for callers that cannot allocate device memory or bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same result, bit for bit, as conv1d_bwd_weight on the same
+ * inputs.  The partial sums go to a buffer of CONV1D_NOALLOC_SCRATCH_BYTES that
+ * is part of the library's device image (one copy per GPU, held until the
+ * process ends); the call allocates and frees nothing (its first call on a GPU
+ * looks the buffer's address up, with that GPU current; `stream` must belong
+ * to the current GPU).  Returns CONV1D_ESCRATCH, having launched nothing, when
+ * conv1d_bwd_weight_workspace_bytes(...) exceeds the buffer.  All calls on one
+ * GPU share the buffer: two calls that overlap in time on the same GPU (on
+ * different streams or from different threads) race and give wrong results;
+ * calls queued on one stream are safe.  The buffer keeps the last call's
+ * partial sums; nothing in it has to be cleared, every kernel writes the
+ * partial sums it later reads.
+ * x, dy, dw and the geometry as for conv1d_bwd_weight. */
+#define CONV1D_NOALLOC_SCRATCH_BYTES (64u << 20)
+int conv1d_bwd_weight_noalloc(const void* x, const void* dy, float* dw,
+                              int N, int C, int K, int W, int S, int dilation, int padding,
+                              int dtype, void* stream);
 
 /* Force a kernel family for all later calls of this process (CONV1D_VARIANT_*).
  * Returns CONV1D_EINVAL for an unknown value.  The setting is one process-wide

@@ -19,7 +19,7 @@ PASS_FWD, PASS_BWD_DATA, PASS_BWD_WEIGHT = 0, 1, 2
 
 EXPORTS = (
     "conv1d_out_width", "conv1d_fwd", "conv1d_bwd_data", "conv1d_bwd_weight_workspace_bytes",
-    "conv1d_bwd_weight", "conv1d_set_variant", "conv1d_kernel_name", "conv1d_status_string",
+    "conv1d_bwd_weight", "conv1d_bwd_weight_noalloc", "conv1d_set_variant", "conv1d_kernel_name", "conv1d_status_string",
 )
 
 _lib = None
@@ -54,6 +54,8 @@ def load() -> ctypes.CDLL:
     lib.conv1d_bwd_weight_workspace_bytes.argtypes = geom + [i]
     lib.conv1d_bwd_weight.restype = i
     lib.conv1d_bwd_weight.argtypes = [vp, vp, vp, vp, sz] + geom + [i, vp]
+    lib.conv1d_bwd_weight_noalloc.restype = i
+    lib.conv1d_bwd_weight_noalloc.argtypes = [vp, vp, vp] + geom + [i, vp]
     lib.conv1d_set_variant.restype = i
     lib.conv1d_set_variant.argtypes = [i]
     lib.conv1d_kernel_name.restype = ctypes.c_char_p
@@ -174,3 +176,23 @@ def conv1d_bwd_weight(x, dy, S: int, dilation: int, padding: int, out=None, work
                                     _stream_ptr(stream)))
     return dw
 
+
+NOALLOC_SCRATCH_BYTES = 64 << 20
+
+
+def conv1d_bwd_weight_noalloc(x, dy, S: int, dilation: int, padding: int, out, stream=None):
+    """dw = conv1d_bwd_weight(x, dy) into the caller's `out`, partial sums in the library's built-in buffer."""
+    import torch
+
+    _dev(x, "x"), _dev(dy, "dy")
+    N, C, W = x.shape
+    N2, K, Q = dy.shape
+    if N2 != N or dy.dtype != x.dtype:
+        raise ValueError("x and dy disagree in batch or dtype")
+    if conv1d_out_width(W, S, dilation, padding) != Q:
+        raise ValueError("dy width does not match the geometry")
+    if tuple(out.shape) != (K, C, S) or out.dtype != torch.float32:
+        raise ValueError("out has the wrong shape or dtype")
+    _check(load().conv1d_bwd_weight_noalloc(x.data_ptr(), dy.data_ptr(), _dev(out, "out").data_ptr(), N, C, K, W, S,
+                                            dilation, padding, _dtype_code(x), _stream_ptr(stream)))
+    return out

@@ -27,9 +27,35 @@ hipError_t ensure_dynamic_lds(const void* kern, size_t bytes) {
 
 }  // namespace conv1d
 
+// Partial sums of conv1d_bwd_weight_noalloc: one array per GPU the library runs on, held until the process ends.
+// In host code this name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[CONV1D_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 std::atomic<int> g_variant{CONV1D_VARIANT_AUTO};
+
+// device address of `scratch` on each GPU, looked up on the first call with that GPU current
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t scratch_for_current_device(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 struct Geom {
     int N, C, K, W, S, d, P, Q;
@@ -198,6 +224,20 @@ int conv1d_bwd_weight(const void* x, const void* dy, float* dw, void* workspace,
     return run_wgrad(g, x, dy, dw, workspace, workspace_bytes, dtype, stream);
 }
 
+int conv1d_bwd_weight_noalloc(const void* x, const void* dy, float* dw, int N, int C, int K, int W, int S,
+                              int dilation, int padding, int dtype, void* stream) {
+    Geom g;
+    if (!x || !dy || !dw || (dtype != CONV1D_FP32 && dtype != CONV1D_BF16)) return CONV1D_EINVAL;
+    if (!make_geom(N, C, K, W, S, dilation, padding, &g)) return CONV1D_EINVAL;
+    const size_t ea = dtype == CONV1D_BF16 ? 2 : 4;
+    if (!aligned(x, ea) || !aligned(dy, ea) || !aligned(dw, 4)) return CONV1D_EINVAL;
+    const size_t need = conv1d_bwd_weight_workspace_bytes(N, C, K, W, S, dilation, padding, dtype);
+    if (need > CONV1D_NOALLOC_SCRATCH_BYTES) return CONV1D_ESCRATCH;
+    void* ws = nullptr;
+    if (scratch_for_current_device(&ws) != hipSuccess) return CONV1D_EHIP;
+    // nothing has to start at zero: every kernel family writes each partial sum before its second stage reads it
+    return run_wgrad(g, x, dy, dw, ws, CONV1D_NOALLOC_SCRATCH_BYTES, dtype, stream);
+}
 int conv1d_set_variant(int variant) {
     if (variant < CONV1D_VARIANT_AUTO || variant > CONV1D_VARIANT_IGEMM) return CONV1D_EINVAL;
     g_variant.store(variant, std::memory_order_relaxed);
@@ -223,6 +263,7 @@ const char* conv1d_status_string(int status) {
         case CONV1D_EUNSUPPORTED: return "geometry not supported by the selected kernel variant";
         case CONV1D_EWORKSPACE: return "workspace missing or too small";
         case CONV1D_EHIP: return "HIP runtime error on launch";
+        case CONV1D_ESCRATCH: return "geometry needs more scratch than the library's built-in buffer (CONV1D_NOALLOC_SCRATCH_BYTES): use conv1d_bwd_weight with a workspace";
         default: return "unknown status";
     }
 }

@@ -40,8 +40,8 @@ def test_out_width():
 
 
 def test_status_strings(lib):
-    seen = {binding.conv1d_status_string(s) for s in (0, -1, -2, -3, -4)}
-    assert len(seen) == 5 and binding.conv1d_status_string(0) == "ok"
+    seen = {binding.conv1d_status_string(s) for s in (0, -1, -2, -3, -4, -5)}
+    assert len(seen) == 6 and binding.conv1d_status_string(0) == "ok"
     assert "unknown" in binding.conv1d_status_string(-99)
 
 
@@ -65,6 +65,13 @@ def test_argument_validation_without_gpu(lib):
     assert lib.conv1d_bwd_weight(None, fake, fake, fake, 1 << 20, *g, 0, None) == -1
     assert lib.conv1d_bwd_weight(fake, fake, fake, ctypes.c_void_p(0x1010), 1 << 20, *g, 0, None) == -1  # ws alignment
     assert lib.conv1d_set_variant(99) == -1 and lib.conv1d_set_variant(0) == 0
+    # the entry point without a workspace: same argument checks, and a geometry beyond its built-in buffer is
+    # rejected before any HIP call
+    assert lib.conv1d_bwd_weight_noalloc(None, fake, fake, *g, 0, None) == -1
+    assert lib.conv1d_bwd_weight_noalloc(fake, fake, fake, 2, 4, 4, 8, 5, 2, 0, 0, None) == -1
+    big = (8, 256, 256, 20000, 51, 8, 200)
+    assert binding.conv1d_bwd_weight_workspace_bytes(*big, 1) > binding.NOALLOC_SCRATCH_BYTES
+    assert lib.conv1d_bwd_weight_noalloc(fake, fake, fake, *big, 1, None) == -5
 
 
 def test_workspace_query_and_kernel_names():
