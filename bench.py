@@ -21,6 +21,7 @@ sys.path.insert(0, ROOT)
 PEAK = {"bf16": 2500.0, "fp32": 157.3}      # dense MFMA TFLOP/s, MI355X
 HBM_PEAK_GBS = 8000.0
 PASSES = ("fwd", "bwd_data", "bwd_weight")
+REGIONS = 5                                  # timed regions of --steps steps each; the median region is reported
 
 
 def algorithmic_bytes(wl, p):
@@ -94,6 +95,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="genomics_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ubench", action="store_true", help="skip the MFMA-only / copy microbenchmarks (measured peaks)")
     ap.add_argument("--variant", type=int, default=0, help="force a kernel family (0 = auto)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 256 MiB device-to-device copy 5 times (reference for HBM byte counters)")
@@ -112,7 +114,7 @@ def main() -> int:
     import numpy as np
     import torch
 
-    from paper_2104_08002_amd import binding, inputs
+    from paper_2104_08002_amd import binding, build, inputs
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -131,62 +133,101 @@ def main() -> int:
         return sweep_table(args, np, torch, binding, inputs)
     wl = inputs.WORKLOADS[args.workload]
     data = inputs.make_inputs(wl)
-    dev = {}
-    for k in ("x", "w", "dy"):
-        if wl.dtype == "bf16":
-            dev[k] = torch.from_numpy(data[k + "_bits"].view(np.int16)).cuda().view(torch.bfloat16)
-        else:
-            dev[k] = torch.from_numpy(data[k]).cuda()
     code = 1 if wl.dtype == "bf16" else 0
-    y = torch.empty((wl.N, wl.K, wl.Q), dtype=torch.float32, device="cuda")
-    dx = torch.empty((wl.N, wl.C, wl.W), dtype=torch.float32, device="cuda")
-    dw = torch.empty((wl.K, wl.C, wl.S), dtype=torch.float32, device="cuda")
-    ws = torch.empty(max(256, binding.conv1d_bwd_weight_workspace_bytes(*wl.geometry(), code)), dtype=torch.uint8,
-                     device="cuda")
+    ws_bytes = max(256, binding.conv1d_bwd_weight_workspace_bytes(*wl.geometry(), code))
 
-    launch = {
-        "fwd": lambda: binding.conv1d_fwd(dev["x"], dev["w"], wl.d, wl.P, out=y),
-        "bwd_data": lambda: binding.conv1d_bwd_data(dev["dy"], dev["w"], wl.W, wl.d, wl.P, out=dx),
-        "bwd_weight": lambda: binding.conv1d_bwd_weight(dev["x"], dev["dy"], wl.S, wl.d, wl.P, out=dw, workspace=ws),
-    }
+    def make_set():
+        s = {}
+        for k in ("x", "w", "dy"):
+            if wl.dtype == "bf16":
+                s[k] = torch.from_numpy(data[k + "_bits"].view(np.int16)).cuda().view(torch.bfloat16)
+            else:
+                s[k] = torch.from_numpy(data[k]).cuda()
+        s["y"] = torch.empty((wl.N, wl.K, wl.Q), dtype=torch.float32, device="cuda")
+        s["dx"] = torch.empty((wl.N, wl.C, wl.W), dtype=torch.float32, device="cuda")
+        s["dw"] = torch.empty((wl.K, wl.C, wl.S), dtype=torch.float32, device="cuda")
+        s["ws"] = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        return s
+
+    # Buffer set 0 is the "hot" configuration: the same tensors step after step (for genomics they stay in the 256 MB
+    # last-level cache).  The "cold" configuration walks through several sets of distinct tensors with the same
+    # contents, so that more than 1 GB passes between two uses of a tensor and every input comes from HBM.
+    set_bytes = sum(t.numel() * t.element_size() for t in make_set().values())
+    nsets = max(4, -(-(1 << 30) // set_bytes))
+    sets = [make_set() for _ in range(nsets)]
+
+    def launch(p, s):
+        if p == "fwd":
+            binding.conv1d_fwd(s["x"], s["w"], wl.d, wl.P, out=s["y"])
+        elif p == "bwd_data":
+            binding.conv1d_bwd_data(s["dy"], s["w"], wl.W, wl.d, wl.P, out=s["dx"])
+        else:
+            binding.conv1d_bwd_weight(s["x"], s["dy"], wl.S, wl.d, wl.P, out=s["dw"], workspace=s["ws"])
 
     run_passes = tuple(p for p in PASSES if p in args.passes.split(","))
 
-    def step():
+    def step(s):
         for p in run_passes:
-            launch[p]()
+            launch(p, s)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    def timed_regions(cold):
+        """REGIONS regions of exactly args.steps steps each, every one bracketed by a device synchronisation."""
+        out, k = [], 0
+        for _ in range(REGIONS):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                step(sets[k % nsets] if cold else sets[0])
+                k += 1
+            torch.cuda.synchronize()
+            out.append((time.perf_counter() - t0) * 1e3 / args.steps)
+        return out
+
+    for i in range(max(args.warmup, 1)):
+        step(sets[0])
+    for s in sets[1:]:
+        step(s)  # every set once: first-touch costs stay out of the cold figure
+    hot_regions = timed_regions(False)
+    cold_regions = timed_regions(True)
+    ms_per_step = sorted(hot_regions)[REGIONS // 2]
+    ms_per_step_cold = sorted(cold_regions)[REGIONS // 2]
     value = len(run_passes) * wl.flops / (ms_per_step * 1e-3) / 1e12
+    value_cold = len(run_passes) * wl.flops / (ms_per_step_cold * 1e-3) / 1e12
 
     # per-pass device time: HIP events on the stream the kernels are launched on (torch's current stream)
-    per_pass = {}
-    for p in run_passes:
+    def event_times(p, cold):
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
         torch.cuda.synchronize()
-        for a, b in evs:
+        for i, (a, b) in enumerate(evs):
+            s = sets[i % nsets] if cold else sets[0]
             a.record()
-            launch[p]()
+            launch(p, s)
             b.record()
         torch.cuda.synchronize()
-        ms = sorted(a.elapsed_time(b) for a, b in evs)
-        avg = sum(ms) / len(ms)
+        return sorted(a.elapsed_time(b) for a, b in evs)
+
+    per_pass = {}
+    for p in run_passes:
+        ms = event_times(p, False)
+        msc = event_times(p, True)
+        avg, avgc = sum(ms) / len(ms), sum(msc) / len(msc)
         tf = wl.flops / (avg * 1e-3) / 1e12
         gbs = algorithmic_bytes(wl, p) / (avg * 1e-3) / 1e9
         per_pass[p] = {
             "kernel": binding.conv1d_kernel_name(PASSES.index(p), *wl.geometry(), code),
             "avg_us": round(avg * 1e3, 2), "median_us": round(ms[len(ms) // 2] * 1e3, 2),
+            "cold_us": round(avgc * 1e3, 2), "cold_median_us": round(msc[len(msc) // 2] * 1e3, 2),
             "tflops": round(tf, 2), "frac_mfma_peak": round(tf / PEAK[wl.dtype], 4),
             "algorithmic_GBps": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+            "cold_tflops": round(wl.flops / (avgc * 1e-3) / 1e12, 2),
+            "cold_algorithmic_GBps": round(algorithmic_bytes(wl, p) / (avgc * 1e-3) / 1e9, 1),
         }
+    # measured denominators: what this GPU sustains on an MFMA-only loop and on a plain copy
+    measured = None
+    if not args.no_ubench:
+        from paper_2104_08002_amd import ubench
+
+        measured = ubench.measure()
     # The dominant kernel is the one with the largest share of the step.  fwd and bwd_data are launches of the same
     # kernel (one launch per pass); bwd_weight is its own kernel plus the small second stage.
     share = {}
@@ -196,18 +237,30 @@ def main() -> int:
     dom_passes = share[dom_kernel]
     dom = dom_passes[0]
     avg_us = sum(per_pass[p]["avg_us"] for p in dom_passes) / len(dom_passes)
-    tf = wl.flops / (avg_us * 1e-6) / 1e12
+    cold_us = sum(per_pass[p]["cold_us"] for p in dom_passes) / len(dom_passes)
     alg_bytes = sum(algorithmic_bytes(wl, p) for p in dom_passes) / len(dom_passes)
-    gbs = alg_bytes / (avg_us * 1e-6) / 1e9
     # which roof bounds the dominant kernel: time at MFMA peak vs time at HBM peak for its algorithmic work
     t_mfma = wl.flops / (PEAK[wl.dtype] * 1e12)
     t_hbm = alg_bytes / (HBM_PEAK_GBS * 1e9)
     if t_hbm > t_mfma:
-        roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)}
+        ach, achc = alg_bytes / (avg_us * 1e-6) / 1e9, alg_bytes / (cold_us * 1e-6) / 1e9
+        roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+                "achieved_cold": round(achc, 1), "frac_cold": round(achc / HBM_PEAK_GBS, 4)}
+        if measured:
+            roof["measured_peak"] = measured["hbm_copy_gbps"]
+            roof["frac_of_measured_peak"] = round(ach / measured["hbm_copy_gbps"], 4)
+            roof["frac_cold_of_measured_peak"] = round(achc / measured["hbm_copy_gbps"], 4)
     else:
-        roof = {"bound": "mfma", "achieved": round(tf, 2), "peak": PEAK[wl.dtype], "unit": "TFLOP/s", "frac": round(tf / PEAK[wl.dtype], 4)}
+        ach, achc = wl.flops / (avg_us * 1e-6) / 1e12, wl.flops / (cold_us * 1e-6) / 1e12
+        roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK[wl.dtype], "unit": "TFLOP/s", "frac": round(ach / PEAK[wl.dtype], 4),
+                "achieved_cold": round(achc, 2), "frac_cold": round(achc / PEAK[wl.dtype], 4)}
+        if measured:
+            mp = measured["mfma_bf16_tflops" if wl.dtype == "bf16" else "mfma_fp32_tflops"]
+            roof["measured_peak"] = mp
+            roof["frac_of_measured_peak"] = round(ach / mp, 4)
+            roof["frac_cold_of_measured_peak"] = round(achc / mp, 4)
     roof.update({"kernel": dom_kernel, "passes": dom_passes, "launches_per_step": len(dom_passes), "avg_us": round(avg_us, 2),
-                 "traffic": stored_traffic(wl.name, dom)})
+                 "cold_us": round(cold_us, 2), "algorithmic_bytes": int(alg_bytes), "traffic": stored_traffic(wl.name, dom)})
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -227,11 +280,19 @@ def main() -> int:
     out = {
         "metric": "TFLOP/s per step (fwd + bwd_data + bwd_weight), 1 MI355X", "value": round(value, 3), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "timing": f"median of {REGIONS} regions of {args.steps} steps, each between two device synchronisations",
+        "regions_ms_per_step": [round(v, 4) for v in hot_regions],
+        "cold": {"ms_per_step": round(ms_per_step_cold, 4), "value": round(value_cold, 3),
+                 "frac_mfma_peak": round(value_cold / PEAK[wl.dtype], 4),
+                 "regions_ms_per_step": [round(v, 4) for v in cold_regions], "buffer_sets": nsets,
+                 "bytes_per_set": set_bytes,
+                 "what": "the same step walking through distinct buffer sets, so that no tensor is still cached when it is used again"},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "N": wl.N, "C": wl.C, "K": wl.K, "W": wl.W, "S": wl.S, "dilation": wl.d,
                    "padding": wl.P, "Q": wl.Q, "gflop_per_pass": round(wl.flops / 1e9, 3), "outputs": "fp32"},
         "frac_mfma_peak": round(value / PEAK[wl.dtype], 4),
         "passes": list(run_passes), "per_pass": per_pass, "roofline": roof, "cpu_baseline": cpu,
+        "measured_peak": measured, "library_sources": build.built_hash(),
     }
     print(json.dumps(out))
     return 0

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(_HERE, "peaks.hip")
 LIB = os.path.join(_HERE, "libconv1d_ubench.so")
 
-MFMA_SHAPES = {0: "bf16_32x32x16", 1: "bf16_16x16x32", 2: "fp32_32x32x2", 3: "fp32_16x16x4"}
+MFMA_SHAPES = {0: "bf16_32x32x16", 1: "fp32_32x32x2"}
 COPY_SIZES_MB = (64, 256, 1024)
 
 
@@ -35,6 +35,7 @@ def measure() -> dict:
     lib = ctypes.CDLL(LIB)
     lib.conv1d_ubench_mfma_tflops.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
     lib.conv1d_ubench_copy_gbps.argtypes = [ctypes.c_size_t, ctypes.POINTER(ctypes.c_double)]
+    lib.conv1d_ubench_stream_gbps.argtypes = [ctypes.c_int, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double)]
     lib.conv1d_ubench_device.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
     out = {}
     cu, mhz = ctypes.c_int(), ctypes.c_int()
@@ -49,8 +50,13 @@ def measure() -> dict:
         if lib.conv1d_ubench_copy_gbps(mb << 20, ctypes.byref(v)) != 0:
             raise RuntimeError(f"copy microbenchmark {mb} MB failed")
         out[f"copy_{mb}MB_gbps"] = round(v.value, 1)
-    out["mfma_bf16_tflops"] = max(out["mfma_bf16_32x32x16_tflops"], out["mfma_bf16_16x16x32_tflops"])
-    out["mfma_fp32_tflops"] = max(out["mfma_fp32_32x32x2_tflops"], out["mfma_fp32_16x16x4_tflops"])
+    for mode, name in ((0, "fill"), (1, "read")):
+        for mb in COPY_SIZES_MB:
+            if lib.conv1d_ubench_stream_gbps(mode, mb << 20, ctypes.byref(v)) != 0:
+                raise RuntimeError(f"{name} microbenchmark {mb} MB failed")
+            out[f"{name}_{mb}MB_gbps"] = round(v.value, 1)
+    out["mfma_bf16_tflops"] = out["mfma_bf16_32x32x16_tflops"]
+    out["mfma_fp32_tflops"] = out["mfma_fp32_32x32x2_tflops"]
     out["hbm_copy_gbps"] = out["copy_1024MB_gbps"]
     # the dense bf16 peak of 2.5 PFLOP/s is quoted at 2.4 GHz: the MFMA-only rate bounds the sustained clock from below
     out["implied_clock_ghz_at_least"] = round(2.4 * out["mfma_bf16_tflops"] / 2516.6, 2)

@@ -7,7 +7,6 @@
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 // NACC independent accumulators per wave: enough to cover the MFMA latency, no memory traffic in the loop
@@ -32,24 +31,6 @@ __global__ __launch_bounds__(256) void mfma_bf16_32x32x16_kernel(float* out, int
 }
 
 template <int NACC>
-__global__ __launch_bounds__(256) void mfma_bf16_16x16x32_kernel(float* out, int iters) {
-    bf16x8 a, b;
-    for (int i = 0; i < 8; ++i) {
-        a[i] = static_cast<__bf16>(static_cast<float>((threadIdx.x + i) & 7));
-        b[i] = static_cast<__bf16>(static_cast<float>(i));
-    }
-    f32x4 acc[NACC];
-    for (int j = 0; j < NACC; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int j = 0; j < NACC; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[j], 0, 0, 0);
-    }
-    float s = 0.f;
-    for (int j = 0; j < NACC; ++j) s += acc[j][0] + acc[j][1] + acc[j][2] + acc[j][3];
-    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
-}
-
-template <int NACC>
 __global__ __launch_bounds__(256) void mfma_f32_32x32x2_kernel(float* out, int iters) {
     const float a = static_cast<float>(threadIdx.x & 7), b = 1.0f;
     f32x16 acc[NACC];
@@ -65,24 +46,29 @@ __global__ __launch_bounds__(256) void mfma_f32_32x32x2_kernel(float* out, int i
     out[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
-template <int NACC>
-__global__ __launch_bounds__(256) void mfma_f32_16x16x4_kernel(float* out, int iters) {
-    const float a = static_cast<float>(threadIdx.x & 7), b = 1.0f;
-    f32x4 acc[NACC];
-    for (int j = 0; j < NACC; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int j = 0; j < NACC; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[j], 0, 0, 0);
-    }
-    float s = 0.f;
-    for (int j = 0; j < NACC; ++j) s += acc[j][0] + acc[j][1] + acc[j][2] + acc[j][3];
-    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
-}
-
 __global__ __launch_bounds__(256) void copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst, size_t n) {
     size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
     const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
     for (; i < n; i += stride) dst[i] = src[i];
+}
+
+// write-only and read-only streams: a pass of the layer writes twice as many bytes as it reads, a copy does not
+__global__ __launch_bounds__(256) void fill_kernel(float4* __restrict__ dst, size_t n) {
+    size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
+    const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+    const float4 v{1.f, 2.f, 3.f, 4.f};
+    for (; i < n; i += stride) dst[i] = v;
+}
+
+__global__ __launch_bounds__(256) void read_kernel(const float4* __restrict__ src, float* __restrict__ out, size_t n) {
+    size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
+    const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+    float4 s{0.f, 0.f, 0.f, 0.f};
+    for (; i < n; i += stride) {
+        const float4 v = src[i];
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    if (s.x + s.y + s.z + s.w == 12345.678f) out[0] = s.x;  // never true for the 0x01 pattern: keeps the loads alive
 }
 
 struct Timer {
@@ -122,7 +108,7 @@ int num_cus() {
 extern "C" {
 
 // Sustained dense MFMA rate of the whole GPU in TFLOP/s with 2 waves per SIMD and no memory traffic.
-// shape 0: v_mfma_f32_32x32x16_bf16, 1: v_mfma_f32_16x16x32_bf16, 2: v_mfma_f32_32x32x2_f32, 3: v_mfma_f32_16x16x4_f32.
+// shape 0: v_mfma_f32_32x32x16_bf16, 1: v_mfma_f32_32x32x2_f32 (the 16 x 16 shapes have the same nominal rate).
 // Returns 0 and writes *tflops, or -1 on a HIP error / unknown shape.
 int conv1d_ubench_mfma_tflops(int shape, double* tflops) {
     const int ncu = num_cus();
@@ -141,16 +127,8 @@ int conv1d_ubench_mfma_tflops(int shape, double* tflops) {
                 flop = waves * iters * 4 * 2.0 * 32 * 32 * 16;
                 break;
             case 1:
-                ms = t.best_ms([&] { hipLaunchKernelGGL(mfma_bf16_16x16x32_kernel<8>, dim3(blocks), dim3(256), 0, nullptr, out, iters); }, 3);
-                flop = waves * iters * 8 * 2.0 * 16 * 16 * 32;
-                break;
-            case 2:
                 ms = t.best_ms([&] { hipLaunchKernelGGL(mfma_f32_32x32x2_kernel<4>, dim3(blocks), dim3(256), 0, nullptr, out, iters / 4); }, 3);
                 flop = waves * (iters / 4) * 4 * 2.0 * 32 * 32 * 2;
-                break;
-            case 3:
-                ms = t.best_ms([&] { hipLaunchKernelGGL(mfma_f32_16x16x4_kernel<8>, dim3(blocks), dim3(256), 0, nullptr, out, iters / 4); }, 3);
-                flop = waves * (iters / 4) * 8 * 2.0 * 16 * 16 * 4;
                 break;
             default: break;
         }
@@ -183,6 +161,34 @@ int conv1d_ubench_copy_gbps(size_t bytes, double* gbps) {
     (void)hipFree(b);
     if (ms <= 0.f || !launched) return -1;
     *gbps = 2.0 * static_cast<double>(bytes) / (ms * 1e-3) / 1e9;
+    return 0;
+}
+
+// Rate of a write-only stream (mode 0) or a read-only stream (mode 1) over `bytes` of device memory in GB/s.
+int conv1d_ubench_stream_gbps(int mode, size_t bytes, double* gbps) {
+    const int ncu = num_cus();
+    if (ncu <= 0 || !gbps || bytes < 4096 || (mode != 0 && mode != 1)) return -1;
+    bytes &= ~static_cast<size_t>(15);
+    float4* a = nullptr;
+    float* out = nullptr;
+    if (hipMalloc(&a, bytes) != hipSuccess) return -1;
+    if (hipMalloc(&out, 256) != hipSuccess) {
+        (void)hipFree(a);
+        return -1;
+    }
+    float ms = -1.f;
+    Timer t;
+    if (t.ok() && hipMemset(a, 1, bytes) == hipSuccess) {
+        if (mode == 0)
+            ms = t.best_ms([&] { hipLaunchKernelGGL(fill_kernel, dim3(ncu * 8), dim3(256), 0, nullptr, a, bytes / 16); }, 5);
+        else
+            ms = t.best_ms([&] { hipLaunchKernelGGL(read_kernel, dim3(ncu * 8), dim3(256), 0, nullptr, a, out, bytes / 16); }, 5);
+    }
+    const bool launched = hipGetLastError() == hipSuccess;
+    (void)hipFree(a);
+    (void)hipFree(out);
+    if (ms <= 0.f || !launched) return -1;
+    *gbps = static_cast<double>(bytes) / (ms * 1e-3) / 1e9;
     return 0;
 }
 
