@@ -13,4 +13,8 @@ from .conv1d_oracle import (  # noqa: F401
     fwd_at,
     bwd_data_at,
     bwd_weight_at,
+    round_bf16,
+    epilogue,
+    fwd_ex,
+    bwd_data_ex,
 )

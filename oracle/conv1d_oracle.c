@@ -26,6 +26,12 @@
  * OpenMP splits independent output elements across threads and never splits
  * a reduction, so results do not depend on the thread count.
  *
+ * Epilogue (conv1d_oracle_epilogue): what a framework does to the layer's
+ * output next.  Section 3 leaves the bias to the framework: z = y + bias[k].
+ * Section 4.4 follows the layer with a ReLU that stays in BF16: a = max(z, 0),
+ * stored as bfloat16 (nearest value, ties to the even significand).  Each of
+ * the three steps is optional.  The magnitude companion gains |bias[k]|.
+ *
  * The *_at variants evaluate the same definitions at a caller-given list of
  * output coordinates (for full-size workloads where the whole output would
  * take minutes).
@@ -215,5 +221,43 @@ void conv1d_oracle_bwd_weight_at(const double *x, const double *dy, const int64_
             }
         out[t] = acc;
         if (outabs) outabs[t] = aacc;
+    }
+}
+
+/* ---- epilogue: bias (Section 3), ReLU and BF16 storage (Section 4.4) ----- */
+/* Nearest bfloat16 (8 significant bits, exponent range of binary32), ties to
+ * even, written from the definition: scale the significand to 8 bits, round
+ * to the nearest integer in the default (ties-to-even) mode, scale back.
+ * Below 2^-126 the spacing stays 2^-133 (subnormals); beyond the largest
+ * finite bfloat16 the result is +-infinity. */
+double conv1d_oracle_round_bf16(double v)
+{
+    if (v == 0.0 || isnan(v) || isinf(v)) return v;
+    int e;
+    (void)frexp(v, &e);               /* |v| = m * 2^e, m in [0.5, 1) */
+    int lsb = e - 8;                  /* exponent of the last kept bit */
+    if (lsb < -133) lsb = -133;
+    const double r = ldexp(nearbyint(ldexp(v, -lsb)), lsb);
+    const double max_bf16 = ldexp(255.0, 120);   /* (2 - 2^-7) * 2^127 */
+    if (fabs(r) > max_bf16) return v > 0 ? INFINITY : -INFINITY;
+    return r;
+}
+
+/* y[n][k][q] (rows = N*K, each of `width` columns) is updated in place:
+ * + bias[row % K] if bias != NULL, then max(.,0) if relu, then rounded to
+ * bfloat16 if round_bf16.  yabs (may be NULL) gains |bias|. */
+void conv1d_oracle_epilogue(double *y, double *yabs, const double *bias, long N, long K, long width,
+                            int relu, int round_bf16)
+{
+#pragma omp parallel for schedule(static)
+    for (long r = 0; r < N * K; ++r) {
+        const double b = bias ? bias[r % K] : 0.0;
+        for (long q = 0; q < width; ++q) {
+            double z = y[r * width + q] + b;
+            if (relu && z < 0.0) z = 0.0;
+            if (round_bf16) z = conv1d_oracle_round_bf16(z);
+            y[r * width + q] = z;
+            if (yabs) yabs[r * width + q] += fabs(b);
+        }
     }
 }

@@ -54,6 +54,10 @@ def _load():
             fn = getattr(lib, name)
             fn.restype = None
             fn.argtypes = [_D, _D, _I64, _L, _D, _D] + dims
+        lib.conv1d_oracle_round_bf16.restype = ctypes.c_double
+        lib.conv1d_oracle_round_bf16.argtypes = [ctypes.c_double]
+        lib.conv1d_oracle_epilogue.restype = None
+        lib.conv1d_oracle_epilogue.argtypes = [_D, _D, _D, _L, _L, _L, ctypes.c_int, ctypes.c_int]
         _lib = lib
     return _lib
 
@@ -181,3 +185,35 @@ def bwd_weight_at(x, dy, idx, S: int, d: int, P: int):
     _load().conv1d_oracle_bwd_weight_at(_p(x), _p(dy), idx.ctypes.data_as(_I64), len(idx), _p(out),
                                         _p(oa), N, C, K, W, S, d, P)
     return out, oa
+
+
+def round_bf16(v: float) -> float:
+    """Nearest bfloat16 to a double, ties to even (the storage rounding of Section 4.4's BF16 layers)."""
+    return float(_load().conv1d_oracle_round_bf16(float(v)))
+
+
+def epilogue(y, bias=None, relu: bool = False, out_bf16: bool = False, yabs=None):
+    """In place on y[N,K,width] (float64): + bias[k] (Section 3: the bias the framework adds), max(., 0) and bfloat16
+    storage (Section 4.4: the BF16 ReLU that follows the layer).  yabs, when given, gains |bias[k]|."""
+    if y.dtype != np.float64 or not y.flags.c_contiguous or y.ndim != 3:
+        raise ValueError("y must be a contiguous float64 array [N, K, width]")
+    N, K, width = y.shape
+    b = None if bias is None else _f64(bias, (K,))
+    if yabs is not None and (yabs.dtype != np.float64 or yabs.shape != y.shape or not yabs.flags.c_contiguous):
+        raise ValueError("yabs must match y")
+    _load().conv1d_oracle_epilogue(_p(y), _p(yabs), _p(b), N, K, width, int(bool(relu)), int(bool(out_bf16)))
+    return y
+
+
+def fwd_ex(x, w, d: int, P: int, bias=None, relu: bool = False, out_bf16: bool = False, with_abs: bool = False):
+    """The forward pass followed by the epilogue: round_bf16?(relu?(fwd(x, w) + bias?))."""
+    y, ya = fwd(x, w, d, P, with_abs=True)
+    epilogue(y, bias, relu, out_bf16, ya)
+    return (y, ya) if with_abs else y
+
+
+def bwd_data_ex(dy, w, W: int, d: int, P: int, out_bf16: bool = False, with_abs: bool = False):
+    """The backward-data pass with its result stored as bfloat16 (Section 4.4: gradients stay in BF16)."""
+    dx, da = bwd_data(dy, w, W, d, P, with_abs=True)
+    epilogue(dx, None, False, out_bf16, da)
+    return (dx, da) if with_abs else dx
