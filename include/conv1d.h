@@ -26,8 +26,9 @@
  *   dx [N][C][W]   gradient w.r.t. the input   float
  *   dw [K][C][S]   gradient w.r.t. the weights float
  * `dtype` is CONV1D_FP32 (IEEE binary32) or CONV1D_BF16 (bfloat16, 2 bytes);
- * products are accumulated in FP32 and outputs are always FP32, never rounded
- * back to bfloat16.  C, K and W may be odd for either dtype.
+ * products are accumulated in FP32 and outputs are FP32, never rounded back to
+ * bfloat16, except where a caller of the _ex entry points asks for bfloat16
+ * storage.  C, K and W may be odd for either dtype.
  *
  * Pointers, ownership, execution
  *   Every tensor pointer is a DEVICE pointer owned by the caller and must stay
@@ -113,6 +114,20 @@ int conv1d_fwd(const void* x, const void* w, float* y,
                int N, int C, int K, int W, int S, int dilation, int padding,
                int dtype, void* stream);
 
+/* Forward pass with a fused epilogue:
+ *   z = conv1d_fwd(x, w)[n][k][q] + bias[k]      bias: device, float, K elements, or NULL for none
+ *                                                 (Section 3 leaves the bias to the framework: this is where it goes)
+ *   z = max(z, 0)                                 with CONV1D_EPI_RELU (Section 4.4: the ReLU that follows the layer)
+ *   y = z as float, or as bfloat16 (nearest, ties to even) with CONV1D_EPI_OUT_BF16, which needs dtype ==
+ *       CONV1D_BF16 (Section 4.4: activations stay in BF16, no conversion pass).
+ * y: device, N*K*Q elements of float (4-byte aligned) or bfloat16 (2-byte aligned), overwritten.
+ * flags = 0 and bias = NULL is conv1d_fwd.  Unknown flag bits: CONV1D_EINVAL. */
+#define CONV1D_EPI_RELU 1
+#define CONV1D_EPI_OUT_BF16 2
+int conv1d_fwd_ex(const void* x, const void* w, const float* bias, void* y,
+                  int N, int C, int K, int W, int S, int dilation, int padding,
+                  int dtype, int flags, void* stream);
+
 /* Backward-data pass (Section 3.2, Algorithm 3: the adjoint of the forward map in x):
  *   dx[n][c][i] = sum_{k<K} sum_{s<S} w[k][c][s] * dy[n][k][i + P - s*d],  dy = 0 outside [0,Q).
  * dy: device, dtype, N*K*Q elements (read).  w: device, dtype, K*C*S (read).
@@ -120,6 +135,13 @@ int conv1d_fwd(const void* x, const void* w, float* y,
 int conv1d_bwd_data(const void* dy, const void* w, float* dx,
                     int N, int C, int K, int W, int S, int dilation, int padding,
                     int dtype, void* stream);
+
+/* Backward-data pass whose result is stored as bfloat16 with CONV1D_EPI_OUT_BF16 (Section 4.4: in BF16 training
+ * the gradients that flow to the previous layer stay in BF16); needs dtype == CONV1D_BF16.  dx: device, N*C*W
+ * elements of float or bfloat16, overwritten.  No other flag is valid here; flags = 0 is conv1d_bwd_data. */
+int conv1d_bwd_data_ex(const void* dy, const void* w, void* dx,
+                       int N, int C, int K, int W, int S, int dilation, int padding,
+                       int dtype, int flags, void* stream);
 
 /* Bytes of device scratch conv1d_bwd_weight needs for this geometry (partial
  * sums of the first reduction stage).  Returns 0 for an invalid geometry.

@@ -18,7 +18,8 @@ VARIANT_AUTO, VARIANT_GENERIC, VARIANT_SMALLC, VARIANT_IGEMM = 0, 1, 2, 3
 PASS_FWD, PASS_BWD_DATA, PASS_BWD_WEIGHT = 0, 1, 2
 
 EXPORTS = (
-    "conv1d_out_width", "conv1d_fwd", "conv1d_bwd_data", "conv1d_bwd_weight_workspace_bytes",
+    "conv1d_out_width", "conv1d_fwd", "conv1d_fwd_ex", "conv1d_bwd_data", "conv1d_bwd_data_ex",
+    "conv1d_bwd_weight_workspace_bytes",
     "conv1d_bwd_weight", "conv1d_bwd_weight_noalloc", "conv1d_set_variant", "conv1d_kernel_name", "conv1d_status_string",
 )
 
@@ -48,6 +49,10 @@ def load() -> ctypes.CDLL:
     lib.conv1d_out_width.argtypes = [i] * 4
     lib.conv1d_fwd.restype = i
     lib.conv1d_fwd.argtypes = [vp, vp, vp] + geom + [i, vp]
+    lib.conv1d_fwd_ex.restype = i
+    lib.conv1d_fwd_ex.argtypes = [vp, vp, vp, vp] + geom + [i, i, vp]
+    lib.conv1d_bwd_data_ex.restype = i
+    lib.conv1d_bwd_data_ex.argtypes = [vp, vp, vp] + geom + [i, i, vp]
     lib.conv1d_bwd_data.restype = i
     lib.conv1d_bwd_data.argtypes = [vp, vp, vp] + geom + [i, vp]
     lib.conv1d_bwd_weight_workspace_bytes.restype = sz
@@ -133,6 +138,55 @@ def conv1d_fwd(x, w, dilation: int, padding: int, out=None, stream=None):
     _check(load().conv1d_fwd(x.data_ptr(), w.data_ptr(), _dev(y, "out").data_ptr(), N, C, K, W, S, dilation,
                              padding, _dtype_code(x), _stream_ptr(stream)))
     return y
+
+
+EPI_RELU, EPI_OUT_BF16 = 1, 2
+
+
+def conv1d_fwd_ex(x, w, dilation: int, padding: int, bias=None, relu: bool = False, out_bf16: bool = False, out=None,
+                  stream=None):
+    """y = [bf16](relu?(conv1d_fwd(x, w) + bias?)) in one pass -> float32 or bfloat16 [N,K,Q]."""
+    import torch
+
+    _dev(x, "x"), _dev(w, "w")
+    N, C, W = x.shape
+    K, C2, S = w.shape
+    if C2 != C or w.dtype != x.dtype:
+        raise ValueError("x and w disagree in channels or dtype")
+    if bias is not None and (_dev(bias, "bias").dtype != torch.float32 or tuple(bias.shape) != (K,)):
+        raise ValueError("bias must be a float32 tensor [K]")
+    Q = conv1d_out_width(W, S, dilation, padding)
+    if Q <= 0:
+        raise Conv1dError(-1, conv1d_status_string(-1))
+    odt = torch.bfloat16 if out_bf16 else torch.float32
+    y = out if out is not None else torch.empty((N, K, Q), dtype=odt, device=x.device)
+    if tuple(y.shape) != (N, K, Q) or y.dtype != odt:
+        raise ValueError("out has the wrong shape or dtype")
+    flags = (EPI_RELU if relu else 0) | (EPI_OUT_BF16 if out_bf16 else 0)
+    _check(load().conv1d_fwd_ex(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None,
+                                _dev(y, "out").data_ptr(), N, C, K, W, S, dilation, padding, _dtype_code(x), flags,
+                                _stream_ptr(stream)))
+    return y
+
+
+def conv1d_bwd_data_ex(dy, w, W: int, dilation: int, padding: int, out_bf16: bool = False, out=None, stream=None):
+    """dx = conv1d_bwd_data(dy, w), stored as bfloat16 when out_bf16 -> [N,C,W]."""
+    import torch
+
+    _dev(dy, "dy"), _dev(w, "w")
+    N, K, Q = dy.shape
+    K2, C, S = w.shape
+    if K2 != K or w.dtype != dy.dtype:
+        raise ValueError("dy and w disagree in filters or dtype")
+    if conv1d_out_width(W, S, dilation, padding) != Q:
+        raise ValueError("dy width does not match the geometry")
+    odt = torch.bfloat16 if out_bf16 else torch.float32
+    dx = out if out is not None else torch.empty((N, C, W), dtype=odt, device=dy.device)
+    if tuple(dx.shape) != (N, C, W) or dx.dtype != odt:
+        raise ValueError("out has the wrong shape or dtype")
+    _check(load().conv1d_bwd_data_ex(dy.data_ptr(), w.data_ptr(), _dev(dx, "out").data_ptr(), N, C, K, W, S, dilation,
+                                     padding, _dtype_code(dy), EPI_OUT_BF16 if out_bf16 else 0, _stream_ptr(stream)))
+    return dx
 
 
 def conv1d_bwd_data(dy, w, W: int, dilation: int, padding: int, out=None, stream=None):

@@ -183,22 +183,42 @@ int conv1d_out_width(int W, int S, int dilation, int padding) {
 
 int conv1d_fwd(const void* x, const void* w, float* y, int N, int C, int K, int W, int S, int dilation,
                int padding, int dtype, void* stream) {
+    return conv1d_fwd_ex(x, w, nullptr, y, N, C, K, W, S, dilation, padding, dtype, 0, stream);
+}
+
+int conv1d_fwd_ex(const void* x, const void* w, const float* bias, void* y, int N, int C, int K, int W, int S,
+                  int dilation, int padding, int dtype, int flags, void* stream) {
     Geom g;
     if (!x || !w || !y || (dtype != CONV1D_FP32 && dtype != CONV1D_BF16)) return CONV1D_EINVAL;
+    if (flags & ~(CONV1D_EPI_RELU | CONV1D_EPI_OUT_BF16)) return CONV1D_EINVAL;
+    const bool out_bf16 = flags & CONV1D_EPI_OUT_BF16;
+    if (out_bf16 && dtype != CONV1D_BF16) return CONV1D_EINVAL;
     if (!make_geom(N, C, K, W, S, dilation, padding, &g)) return CONV1D_EINVAL;
     const size_t ea = dtype == CONV1D_BF16 ? 2 : 4;
-    if (!aligned(x, ea) || !aligned(w, ea) || !aligned(y, 4)) return CONV1D_EINVAL;
-    return run_corr(fwd_problem(g, x, w, y, dtype == CONV1D_BF16), stream);
+    if (!aligned(x, ea) || !aligned(w, ea) || !aligned(y, out_bf16 ? 2 : 4) || !aligned(bias, 4)) return CONV1D_EINVAL;
+    CorrProblem p = fwd_problem(g, x, w, static_cast<float*>(y), dtype == CONV1D_BF16);
+    p.epi = Epilogue{bias, (flags & CONV1D_EPI_RELU) ? 1 : 0, out_bf16 ? 1 : 0};
+    return run_corr(p, stream);
 }
 
 int conv1d_bwd_data(const void* dy, const void* w, float* dx, int N, int C, int K, int W, int S, int dilation,
                     int padding, int dtype, void* stream) {
+    return conv1d_bwd_data_ex(dy, w, dx, N, C, K, W, S, dilation, padding, dtype, 0, stream);
+}
+
+int conv1d_bwd_data_ex(const void* dy, const void* w, void* dx, int N, int C, int K, int W, int S, int dilation,
+                       int padding, int dtype, int flags, void* stream) {
     Geom g;
     if (!dy || !w || !dx || (dtype != CONV1D_FP32 && dtype != CONV1D_BF16)) return CONV1D_EINVAL;
+    if (flags & ~CONV1D_EPI_OUT_BF16) return CONV1D_EINVAL;  // a gradient has no bias and no ReLU of its own
+    const bool out_bf16 = flags & CONV1D_EPI_OUT_BF16;
+    if (out_bf16 && dtype != CONV1D_BF16) return CONV1D_EINVAL;
     if (!make_geom(N, C, K, W, S, dilation, padding, &g)) return CONV1D_EINVAL;
     const size_t ea = dtype == CONV1D_BF16 ? 2 : 4;
-    if (!aligned(dy, ea) || !aligned(w, ea) || !aligned(dx, 4)) return CONV1D_EINVAL;
-    return run_corr(bwd_data_problem(g, dy, w, dx, dtype == CONV1D_BF16), stream);
+    if (!aligned(dy, ea) || !aligned(w, ea) || !aligned(dx, out_bf16 ? 2 : 4)) return CONV1D_EINVAL;
+    CorrProblem p = bwd_data_problem(g, dy, w, static_cast<float*>(dx), dtype == CONV1D_BF16);
+    p.epi = Epilogue{nullptr, 0, out_bf16 ? 1 : 0};
+    return run_corr(p, stream);
 }
 
 size_t conv1d_bwd_weight_workspace_bytes(int N, int C, int K, int W, int S, int dilation, int padding, int dtype) {

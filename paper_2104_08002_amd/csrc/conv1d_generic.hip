@@ -32,8 +32,25 @@ __global__ __launch_bounds__(kThreads) void generic_corr_kernel(CorrProblem p, i
             }
         }
     }
+    const long idx = static_cast<long>(n) * p.out_sn + static_cast<long>(m) * p.Wout + o;
+    if (p.accumulate) {
+        p.out[idx] += acc;
+    } else {
+        epi_store(p.epi, p.out, idx, epi_apply(p.epi, acc, epi_bias(p.epi, m)));
+    }
+}
+
+// bias and ReLU in place on a float output whose sums were accumulated by several launches
+__global__ __launch_bounds__(kThreads) void generic_epilogue_kernel(CorrProblem p, int otiles) {
+    const long blk = blockIdx.x;
+    const int ot = static_cast<int>(blk % otiles);
+    const long nm = blk / otiles;
+    const int m = static_cast<int>(nm % p.M);
+    const int n = static_cast<int>(nm / p.M);
+    const int o = ot * kThreads + threadIdx.x;
+    if (o >= p.Wout) return;
     float* dst = p.out + static_cast<long>(n) * p.out_sn + static_cast<long>(m) * p.Wout + o;
-    *dst = p.accumulate ? *dst + acc : acc;
+    *dst = epi_apply(p.epi, *dst, epi_bias(p.epi, m));
 }
 
 // partial[chunk][k][c][s] = sum over the chunk's samples and all q.
@@ -89,6 +106,14 @@ hipError_t generic_corr_launch(const CorrProblem& p, hipStream_t st) {
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
     return launch_kernel(p.bf16 ? generic_corr_kernel<true> : generic_corr_kernel<false>, dim3(static_cast<unsigned>(blocks)),
                          dim3(kThreads), 0, st, p, otiles);
+}
+
+hipError_t generic_epilogue_launch(const CorrProblem& p, hipStream_t st) {
+    if (p.epi.out_bf16) return hipErrorInvalidValue;
+    const int otiles = cdiv(p.Wout, kThreads);
+    const long blocks = static_cast<long>(p.N) * p.M * otiles;
+    if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+    return launch_kernel(generic_epilogue_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, st, p, otiles);
 }
 
 size_t generic_wgrad_workspace(const WgradProblem& p) {

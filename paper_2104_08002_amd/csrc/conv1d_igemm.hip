@@ -28,7 +28,8 @@ CorrProblem corr_block(const CorrProblem& p, int m0, int r0) {
     b.R = p.R - r0 < kBlock ? p.R - r0 : kBlock;
     b.in = advance(p.in, static_cast<long>(r0) * p.Win, p.bf16);
     b.wt = advance(p.wt, m0 * p.w_sm + r0 * p.w_sr, p.bf16);
-    b.out = p.out + static_cast<long>(m0) * p.Wout;
+    b.out = reinterpret_cast<float*>(reinterpret_cast<char*>(p.out) + static_cast<long>(m0) * p.Wout * (p.epi.out_bf16 ? 2 : 4));
+    if (p.epi.bias) b.epi.bias = p.epi.bias + m0;
     b.accumulate = p.accumulate || r0 > 0;
     b.w_contig = 0;
     return b;
@@ -52,54 +53,98 @@ bool fp32_pairs_in_one_launch(const WgradProblem& p) {
     return bytes > 0 && bytes <= kMaxPairsWorkspace;
 }
 
+// How a layer with more than one block runs.
+enum class CorrRoute {
+    kNone,
+    kRing, kStream, kStaged,   // bf16: one launch of a many-channel kernel
+    kF32Whole,                 // fp32: one launch, channel blocks reduced in the accumulators
+    kF32PerChannelBlock,       // fp32: one launch per channel block, accumulating into the output
+    kRows,                     // one launch per filter block (each reduces its channel blocks itself)
+    kPairs                     // some filter block needs one launch per channel block, accumulating into the output
+};
+
+CorrProblem without_epilogue(CorrProblem p) {
+    p.epi = Epilogue{};
+    return p;
+}
+
+CorrRoute corr_route(const CorrProblem& p) {
+    if (p.bf16 && igemm_ring_bf16_corr_supported(p)) return CorrRoute::kRing;
+    if (p.bf16 && igemm_stream_bf16_corr_supported(p)) return CorrRoute::kStream;
+    if (p.bf16 && igemm_bf16_corr_supported(p)) return CorrRoute::kStaged;
+    if (p.R <= kBlock && p.M <= kBlock) return CorrRoute::kNone;  // one block: that is the small-channel family itself
+    if (!smallc_corr_supported(corr_block(p, 0, 0))) return CorrRoute::kNone;  // the first block pair is the largest one
+    if (!p.bf16) {
+        CorrProblem whole = p;
+        whole.w_contig = 0;
+        if (smallc_corr_f32_blocks_supported(whole)) return CorrRoute::kF32Whole;
+        CorrProblem cols = corr_block(p, 0, 0);
+        cols.M = p.M;
+        if (smallc_corr_f32_blocks_supported(cols)) return CorrRoute::kF32PerChannelBlock;
+    }
+    for (int m0 = 0; m0 < p.M; m0 += kBlock) {
+        CorrProblem rows = corr_block(p, m0, 0);
+        rows.R = p.R;
+        if (!smallc_corr_supported(rows)) return CorrRoute::kPairs;
+    }
+    return CorrRoute::kRows;
+}
+
+bool accumulates(CorrRoute r) { return r == CorrRoute::kF32PerChannelBlock || r == CorrRoute::kPairs; }
+
 }  // namespace
 
-// The first block pair is the largest one; the others differ from it only by having fewer rows.
 bool igemm_corr_supported(const CorrProblem& p) {
-    if (p.bf16 && (igemm_ring_bf16_corr_supported(p) || igemm_stream_bf16_corr_supported(p) || igemm_bf16_corr_supported(p))) return true;
-    if (p.R <= kBlock && p.M <= kBlock) return false;  // one block: that is the small-channel family itself
-    return smallc_corr_supported(corr_block(p, 0, 0));
+    const CorrRoute r = corr_route(p);
+    if (r == CorrRoute::kNone) return false;
+    // partial sums that pass through the output tensor need it to hold floats
+    return !(p.epi.out_bf16 && accumulates(r));
 }
 
 hipError_t igemm_corr_launch(const CorrProblem& p, hipStream_t st) {
     if (!igemm_corr_supported(p)) return hipErrorInvalidValue;
-    if (p.bf16 && igemm_ring_bf16_corr_supported(p)) return igemm_ring_bf16_corr_launch(p, st);
-    if (p.bf16 && igemm_stream_bf16_corr_supported(p)) return igemm_stream_bf16_corr_launch(p, st);
-    if (p.bf16 && igemm_bf16_corr_supported(p)) return igemm_bf16_corr_launch(p, st);
-    if (!p.bf16) {
-        // every filter block in one launch when the kernel can hold the weights of all channel blocks of a block
-        CorrProblem whole = p;
-        whole.w_contig = 0;
-        if (smallc_corr_f32_blocks_supported(whole)) return smallc_corr_f32_blocks_launch(whole, st);
-        // else one launch per channel block (all filter blocks each), accumulating into the output
-        CorrProblem cols = corr_block(p, 0, 0);
-        cols.M = p.M;
-        if (smallc_corr_f32_blocks_supported(cols)) {
-            for (int r0 = 0; r0 < p.R; r0 += kBlock) {
-                cols = corr_block(p, 0, r0);
-                cols.M = p.M;
-                const hipError_t e = smallc_corr_f32_blocks_launch(cols, st);
+    const CorrRoute route = corr_route(p);
+    switch (route) {
+        case CorrRoute::kRing: return igemm_ring_bf16_corr_launch(p, st);
+        case CorrRoute::kStream: return igemm_stream_bf16_corr_launch(p, st);
+        case CorrRoute::kStaged: return igemm_bf16_corr_launch(p, st);
+        case CorrRoute::kF32Whole: {
+            // every filter block in one launch: the kernel holds the weights of all channel blocks of a block
+            CorrProblem whole = p;
+            whole.w_contig = 0;
+            return smallc_corr_f32_blocks_launch(whole, st);
+        }
+        default: break;
+    }
+    // Launches that accumulate into the output leave the epilogue to one elementwise kernel at the end.
+    const CorrProblem q = accumulates(route) ? without_epilogue(p) : p;
+    if (route == CorrRoute::kF32PerChannelBlock) {
+        // one launch per channel block (all filter blocks each)
+        for (int r0 = 0; r0 < q.R; r0 += kBlock) {
+            CorrProblem cols = corr_block(q, 0, r0);
+            cols.M = q.M;
+            const hipError_t e = smallc_corr_f32_blocks_launch(cols, st);
+            if (e != hipSuccess) return e;
+        }
+    } else {
+        for (int m0 = 0; m0 < q.M; m0 += kBlock) {
+            // all channel blocks in one launch when the kernel can keep their weights in LDS ...
+            CorrProblem rows = corr_block(q, m0, 0);
+            rows.R = q.R;
+            if (smallc_corr_supported(rows)) {
+                const hipError_t e = smallc_corr_launch(rows, st);
+                if (e != hipSuccess) return e;
+                continue;
+            }
+            // ... else one launch per channel block, accumulating into the output
+            for (int r0 = 0; r0 < q.R; r0 += kBlock) {
+                const CorrProblem b = corr_block(q, m0, r0);
+                const hipError_t e = smallc_corr_launch(b, st);
                 if (e != hipSuccess) return e;
             }
-            return hipSuccess;
         }
     }
-    for (int m0 = 0; m0 < p.M; m0 += kBlock) {
-        // all channel blocks in one launch when the kernel can keep their weights in LDS ...
-        CorrProblem rows = corr_block(p, m0, 0);
-        rows.R = p.R;
-        if (smallc_corr_supported(rows)) {
-            const hipError_t e = smallc_corr_launch(rows, st);
-            if (e != hipSuccess) return e;
-            continue;
-        }
-        // ... else one launch per channel block, accumulating into the output
-        for (int r0 = 0; r0 < p.R; r0 += kBlock) {
-            const CorrProblem b = corr_block(p, m0, r0);
-            const hipError_t e = smallc_corr_launch(b, st);
-            if (e != hipSuccess) return e;
-        }
-    }
+    if (accumulates(route) && (p.epi.bias || p.epi.relu)) return generic_epilogue_launch(p, st);
     return hipSuccess;
 }
 

@@ -66,6 +66,7 @@ struct IgArgs {
     long su;          // elements between the starts of consecutive runs
     long wbytes;      // size of the weight tensor
     int raw_slots;    // NU * NPc
+    Epilogue epi;
 };
 
 __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
@@ -150,15 +151,17 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
                 const int ct = tile;
                 const int n = ct / a.tiles_per_row;
                 const int o = (ct - n * a.tiles_per_row) * kTW + cw * (kT * 16) + li;
-                float* base = a.out + static_cast<long>(n) * a.out_sn;
+                const long base = static_cast<long>(n) * a.out_sn;
 #pragma unroll
                 for (int fb = 0; fb < kFB; ++fb)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int m = (fg * kFB + fb) * 16 + 4 * kb + i;
+                        const float bm = m < a.M ? epi_bias(a.epi, m) : 0.f;
 #pragma unroll
                         for (int t = 0; t < kT; ++t) {
-                            if (m < a.M && o + 16 * t < a.Wout) base[static_cast<long>(m) * a.Wout + o + 16 * t] = acc[fb][t][i];
+                            if (m < a.M && o + 16 * t < a.Wout)
+                                epi_store(a.epi, a.out, base + static_cast<long>(m) * a.Wout + o + 16 * t, epi_apply(a.epi, acc[fb][t][i], bm));
                         }
                     }
 #pragma unroll
@@ -426,6 +429,7 @@ IgPlan ig_plan(const CorrProblem& p) {
     a.in = static_cast<const unsigned short*>(p.in);
     a.wt = static_cast<const unsigned short*>(p.wt);
     a.out = p.out;
+    a.epi = p.epi;
     a.N = p.N; a.R = p.R; a.M = p.M; a.Win = p.Win; a.Wout = p.Wout; a.S = p.S; a.d = p.d; a.P = p.P;
     a.w_sm = p.w_sm; a.w_sr = p.w_sr; a.w_s0 = p.w_s0; a.w_ss = p.w_ss; a.in_sn = p.in_sn; a.out_sn = p.out_sn;
     a.delta = (p.P & 1) ? 1 : 0;  // (column block start - P) - delta is even

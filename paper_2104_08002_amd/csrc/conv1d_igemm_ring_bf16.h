@@ -68,6 +68,7 @@ struct RgArgs {
     long wbytes;       // size of the weight tensor
     int raw_slots;     // NU * NPc
     int vec_out;       // output rows and the base pointer are 16-byte aligned
+    Epilogue epi;
 };
 
 // operand geometry of a dilation
@@ -363,20 +364,22 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
                 const int ct = tile;
                 const int n = ct / a.tiles_per_row;
                 const int o = (ct - n * a.tiles_per_row) * kTW + cw * (kT * 16) + 4 * kb;
-                float* base = a.out + static_cast<long>(n) * a.out_sn;
+                const long base = static_cast<long>(n) * a.out_sn;
 #pragma unroll
                 for (int fb = 0; fb < FB; ++fb) {
                     const int m = (fg * FB + fb) * 16 + li;
                     if (m < a.M) {
-                        float* row = base + static_cast<long>(m) * a.Wout + o;
+                        const long row = base + static_cast<long>(m) * a.Wout + o;
+                        const float bm = epi_bias(a.epi, m);
 #pragma unroll
                         for (int t = 0; t < kT; ++t) {
+                            const f32x4 v = epi_apply4(a.epi, acc[fb][t], bm);
                             if (a.vec_out && o + 16 * t + 3 < a.Wout) {
-                                *reinterpret_cast<f32x4*>(row + 16 * t) = acc[fb][t];
+                                epi_store4(a.epi, a.out, row + 16 * t, v);
                             } else {
 #pragma unroll
                                 for (int i = 0; i < 4; ++i)
-                                    if (o + 16 * t + i < a.Wout) row[16 * t + i] = acc[fb][t][i];
+                                    if (o + 16 * t + i < a.Wout) epi_store(a.epi, a.out, row + 16 * t + i, v[i]);
                             }
                         }
                     }

@@ -36,6 +36,7 @@ RgPlan rg_plan_kt(const CorrProblem& p, int kT) {
     a.in = static_cast<const unsigned short*>(p.in);
     a.wt = static_cast<const unsigned short*>(p.wt);
     a.out = p.out;
+    a.epi = p.epi;
     a.N = p.N; a.R = p.R; a.M = p.M; a.Win = p.Win; a.Wout = p.Wout; a.S = p.S; a.P = p.P;
     a.w_sm = p.w_sm; a.w_sr = p.w_sr; a.in_sn = p.in_sn; a.out_sn = p.out_sn;
     a.delta = (p.P & 1) ? 1 : 0;

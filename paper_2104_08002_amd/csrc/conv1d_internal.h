@@ -13,6 +13,15 @@
 
 namespace conv1d {
 
+// What happens to an output value between the accumulator and memory.  Section 3 leaves the bias to the framework
+// and Section 4.4 follows the layer with a ReLU that stays in bfloat16; fused here, they cost no extra pass over the
+// output: z = acc + bias[m]; z = max(z, 0) if relu; stored as float, or as bfloat16 (nearest, ties to even).
+struct Epilogue {
+    const float* bias;  // one value per output row m (filter); nullptr: none
+    int relu;
+    int out_bf16;       // the output tensor holds bfloat16 elements
+};
+
 // One "correlation problem": the forward pass and the backward-data pass are both
 //   out[n][m][o] = sum_{r<R} sum_{s<S} in[n][r][o + s*d - P] * wt(m, r, s),   in = 0 outside [0, Win)
 // The forward pass (Eq. 2) has in = x, R = C, M = K, P = padding and wt(m,r,s) = w[m][r][s].
@@ -33,6 +42,8 @@ struct CorrProblem {
     int accumulate;
     // != 0 when the M*R*S weights wt(m,r,s) are exactly the contiguous elements wt[0 .. M*R*S)
     int w_contig;
+    // applied by the kernel that completes an output element; never combined with accumulate != 0
+    Epilogue epi;
 };
 
 // The backward-weight problem (Section 3.3):
@@ -52,6 +63,8 @@ struct WgradProblem {
 
 // generic (plain FMA) family: any geometry
 hipError_t generic_corr_launch(const CorrProblem& p, hipStream_t st);
+// bias and ReLU of p.epi applied in place to a float output (after launches that accumulated into it)
+hipError_t generic_epilogue_launch(const CorrProblem& p, hipStream_t st);
 size_t generic_wgrad_workspace(const WgradProblem& p);
 hipError_t generic_wgrad_launch(const WgradProblem& p, hipStream_t st);
 
@@ -126,6 +139,42 @@ __device__ __forceinline__ float load_elem(const void* base, long idx) {
         return bf16_to_float(static_cast<const unsigned short*>(base)[idx]);
     } else {
         return static_cast<const float*>(base)[idx];
+    }
+}
+
+typedef __attribute__((ext_vector_type(4))) float epi_f32x4;
+typedef __attribute__((ext_vector_type(4))) __bf16 epi_bf16x4;
+
+__device__ __forceinline__ float epi_bias(const Epilogue& e, int m) { return e.bias ? e.bias[m] : 0.f; }
+
+// bias and ReLU (a comparison, not a max: NaN stays NaN)
+__device__ __forceinline__ float epi_apply(const Epilogue& e, float v, float bias_m) {
+    v += bias_m;
+    return (e.relu && v < 0.f) ? 0.f : v;
+}
+
+__device__ __forceinline__ epi_f32x4 epi_apply4(const Epilogue& e, epi_f32x4 v, float bias_m) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = epi_apply(e, v[i], bias_m);
+    return v;
+}
+
+// element `idx` of an output tensor whose element type the epilogue names (float -> bfloat16 is the hardware's
+// nearest-even conversion)
+__device__ __forceinline__ void epi_store(const Epilogue& e, float* out, long idx, float v) {
+    if (e.out_bf16) {
+        reinterpret_cast<__bf16*>(out)[idx] = static_cast<__bf16>(v);
+    } else {
+        out[idx] = v;
+    }
+}
+
+// four adjacent elements from idx on; idx is a multiple of 4 and the tensor is 16-byte aligned
+__device__ __forceinline__ void epi_store4(const Epilogue& e, float* out, long idx, epi_f32x4 v) {
+    if (e.out_bf16) {
+        *reinterpret_cast<epi_bf16x4*>(reinterpret_cast<__bf16*>(out) + idx) = __builtin_convertvector(v, epi_bf16x4);
+    } else {
+        *reinterpret_cast<epi_f32x4*>(out + idx) = v;
     }
 }
 

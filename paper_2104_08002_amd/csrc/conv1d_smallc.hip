@@ -281,17 +281,30 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
         // 16-column block, one 16-byte store per block when the row starts allow it.
         const int n = tile_n(t), O0 = tile_O0(t);
         if (li < Mb) {
-            float* row = p.out + static_cast<long>(n) * p.out_sn + static_cast<long>(16 * mb + li) * p.Wout;
+            const long rowi = static_cast<long>(n) * p.out_sn + static_cast<long>(16 * mb + li) * p.Wout;
+            float* row = p.out + rowi;
+            const float bm = p.accumulate ? 0.f : epi_bias(p.epi, 16 * mb + li);
 #pragma unroll
             for (int j = 0; j < T; ++j) {
                 const int o = O0 + ob + j * 16 + 4 * kb;
-                if (vec_out && o + 4 <= p.Wout) {
-                    f32x4* dst = reinterpret_cast<f32x4*>(row + o);
-                    *dst = p.accumulate ? *dst + acc[j] : acc[j];
-                } else {
+                if (p.accumulate) {  // a further channel block of a layer: float output, no epilogue
+                    if (vec_out && o + 4 <= p.Wout) {
+                        f32x4* dst = reinterpret_cast<f32x4*>(row + o);
+                        *dst = *dst + acc[j];
+                    } else {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (o + i < p.Wout) row[o + i] = p.accumulate ? row[o + i] + acc[j][i] : acc[j][i];
+                        for (int i = 0; i < 4; ++i)
+                            if (o + i < p.Wout) row[o + i] += acc[j][i];
+                    }
+                } else {
+                    const f32x4 v = epi_apply4(p.epi, acc[j], bm);
+                    if (vec_out && o + 4 <= p.Wout) {
+                        epi_store4(p.epi, p.out, rowi + o, v);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (o + i < p.Wout) epi_store(p.epi, p.out, rowi + o + i, v[i]);
+                    }
                 }
             }
         }

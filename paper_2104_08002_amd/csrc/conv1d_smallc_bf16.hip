@@ -217,16 +217,24 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
         const TilePos tp = tile_pos(t);
         const int n = tp.n, O0 = tp.O0;
         const float* src = ost(b);
+        // the bias is already in the sums (the accumulators start from it); ReLU and the bfloat16 conversion happen
+        // here, behind branches that are uniform for the launch
         if (vec_out) {
             const int orow = lane >> 5, ocol = 4 * (lane & 31);
             const int o = O0 + ob + ocol;
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                const f32x4 v = *reinterpret_cast<const f32x4*>(src + (2 * q + orow) * kOS + ocol);
-                float* base = p.out + static_cast<long>(n) * p.out_sn + static_cast<long>(2 * q) * p.Wout + O0 + ob;  // uniform
+                f32x4 v = *reinterpret_cast<const f32x4*>(src + (2 * q + orow) * kOS + ocol);
+                const long base = static_cast<long>(n) * p.out_sn + static_cast<long>(2 * q) * p.Wout + O0 + ob;  // uniform
                 if (2 * q + orow < p.M && o < p.Wout) {
-                    f32x4* dst = reinterpret_cast<f32x4*>(base + static_cast<unsigned>(orow * p.Wout + ocol));
-                    *dst = p.accumulate ? *dst + v : v;
+                    const long idx = base + static_cast<unsigned>(orow * p.Wout + ocol);
+                    if (p.accumulate) {
+                        f32x4* dst = reinterpret_cast<f32x4*>(p.out + idx);
+                        *dst = *dst + v;
+                    } else {
+                        if (p.epi.relu) v = epi_apply4(p.epi, v, 0.f);
+                        epi_store4(p.epi, p.out, idx, v);
+                    }
                 }
             }
         } else {
@@ -234,8 +242,12 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
                 const int m = idx / (T * 16), col = idx - m * (T * 16);
                 const int o = O0 + ob + col;
                 if (m < p.M && o < p.Wout) {
-                    float* dst = p.out + static_cast<long>(n) * p.out_sn + static_cast<long>(m) * p.Wout + o;
-                    *dst = p.accumulate ? *dst + src[m * kOS + col] : src[m * kOS + col];
+                    const long di = static_cast<long>(n) * p.out_sn + static_cast<long>(m) * p.Wout + o;
+                    if (p.accumulate) {
+                        p.out[di] += src[m * kOS + col];
+                    } else {
+                        epi_store(p.epi, p.out, di, epi_apply(p.epi, src[m * kOS + col], 0.f));
+                    }
                 }
             }
         }
@@ -316,10 +328,12 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
     __syncthreads();  // the slice entries alias the staging buffers: every wave has its copy before anyone parks
 
     // ---- consumer side: one tile's reduction, parked in LDS ------------------------------------------
+    // lane (li, kb) accumulates filter li: its sums start from that filter's bias
+    const float bias_li = (!p.accumulate && p.epi.bias && li < p.M) ? p.epi.bias[li] : 0.f;
     auto compute = [&](const u32x4* wb, float* dst) {
         f32x4 acc[T];
 #pragma unroll
-        for (int j = 0; j < T; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < T; ++j) acc[j] = f32x4{bias_li, bias_li, bias_li, bias_li};
         const u32x4* bbase = wb + (kb & 1) * LPS + ob + li + (kb >> 1) * NP * d + psh;
         // The input fragment is the A operand and the weight slice the B operand, so the accumulator tile is
         // [position][filter]: lane (li, kb) holds filter li at the 4 adjacent columns 4 kb .. 4 kb + 3 of tile j,

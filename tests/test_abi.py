@@ -65,6 +65,13 @@ def test_argument_validation_without_gpu(lib):
     assert lib.conv1d_bwd_weight(None, fake, fake, fake, 1 << 20, *g, 0, None) == -1
     assert lib.conv1d_bwd_weight(fake, fake, fake, ctypes.c_void_p(0x1010), 1 << 20, *g, 0, None) == -1  # ws alignment
     assert lib.conv1d_set_variant(99) == -1 and lib.conv1d_set_variant(0) == 0
+    # fused epilogues: unknown flag bits, bfloat16 output for float inputs, ReLU on a gradient
+    assert lib.conv1d_fwd_ex(fake, fake, None, fake, *g, 0, 4, None) == -1
+    assert lib.conv1d_fwd_ex(fake, fake, None, fake, *g, 0, 2, None) == -1
+    assert lib.conv1d_fwd_ex(fake, fake, ctypes.c_void_p(0x1002), fake, *g, 0, 0, None) == -1      # misaligned bias
+    assert lib.conv1d_fwd_ex(fake, fake, None, None, *g, 1, 3, None) == -1
+    assert lib.conv1d_bwd_data_ex(fake, fake, fake, *g, 1, 1, None) == -1
+    assert lib.conv1d_bwd_data_ex(fake, fake, fake, *g, 0, 2, None) == -1
     # the entry point without a workspace: same argument checks, and a geometry beyond its built-in buffer is
     # rejected before any HIP call
     assert lib.conv1d_bwd_weight_noalloc(None, fake, fake, *g, 0, None) == -1
