@@ -48,16 +48,27 @@ def stored_traffic(workload, pass_name):
 
 def sweep_table(args, np, torch, binding, inputs) -> int:
     """Median device time (HIP events), TFLOP/s and fraction of the dense MFMA peak per pass and sweep point."""
-    wls = list(inputs.sweep(args.sweep)) + ([inputs.WIDE_BF16] if args.sweep == "bf16" else [])
-    print(f"# {'workload':22s} " + " ".join(f"| {p:>10s}: kernel family, us, TFLOP/s, % of peak" for p in PASSES))
+    if args.sweep == "q":
+        # the paper's own grid (Section 4.3): batch 56, output widths 1000 ... 60000, three filter widths per family
+        wls = [inputs.q_sweep_point(f, Q, S) for f in inputs.Q_SWEEP_FAMILIES for S in (5, 21, 51) for Q in inputs.Q_SWEEP_Q]
+    else:
+        wls = list(inputs.sweep(args.sweep)) + ([inputs.WIDE_BF16] if args.sweep == "bf16" else [])
+    print(f"# {'workload':26s} " + " ".join(f"| {p:>10s}: kernel family, us, TFLOP/s, % of peak" for p in PASSES))
     for wl in wls:
-        data = inputs.make_inputs(wl)
         dev = {}
-        for k in ("x", "w", "dy"):
-            if wl.dtype == "bf16":
-                dev[k] = torch.from_numpy(data[k + "_bits"].view(np.int16)).cuda().view(torch.bfloat16)
-            else:
-                dev[k] = torch.from_numpy(data[k]).cuda()
+        if args.sweep == "q":
+            # timing only: U[-1,1] tensors drawn on the device (seeded), the host generator would dominate the run
+            gen = torch.Generator(device="cuda").manual_seed(wl.seed)
+            tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+            for k, shape in (("x", (wl.N, wl.C, wl.W)), ("w", (wl.K, wl.C, wl.S)), ("dy", (wl.N, wl.K, wl.Q))):
+                dev[k] = (torch.rand(shape, generator=gen, device="cuda") * 2 - 1).to(tdt)
+        else:
+            data = inputs.make_inputs(wl)
+            for k in ("x", "w", "dy"):
+                if wl.dtype == "bf16":
+                    dev[k] = torch.from_numpy(data[k + "_bits"].view(np.int16)).cuda().view(torch.bfloat16)
+                else:
+                    dev[k] = torch.from_numpy(data[k]).cuda()
         code = 1 if wl.dtype == "bf16" else 0
         y = torch.empty((wl.N, wl.K, wl.Q), dtype=torch.float32, device="cuda")
         dx = torch.empty((wl.N, wl.C, wl.W), dtype=torch.float32, device="cuda")
@@ -84,7 +95,7 @@ def sweep_table(args, np, torch, binding, inputs) -> int:
             tf = wl.flops / (ms * 1e-3) / 1e12
             fam = binding.conv1d_kernel_name(i, *wl.geometry(), code).split("_")[0]
             cols.append(f"| {fam:>7s} {ms * 1e3:8.1f} us {tf:7.1f} TF {100 * tf / PEAK[wl.dtype]:5.1f} %")
-        print(f"{wl.name:24s} " + " ".join(cols), flush=True)
+        print(f"{wl.name:28s} " + " ".join(cols), flush=True)
     return 0
 
 
@@ -104,9 +115,10 @@ def main() -> int:
                     help="only run a plain 256 MiB device-to-device copy 5 times (reference for HBM byte counters)")
     ap.add_argument("--passes", default=",".join(PASSES),
                     help="comma-separated subset of passes to run (profiling runs; the headline needs all three)")
-    ap.add_argument("--sweep", choices=["fp32", "bf16"],
+    ap.add_argument("--sweep", choices=["fp32", "bf16", "q"],
                     help="instead of the headline line: per-pass device times of the 25 filter-width x dilation "
-                         "points (C = K = 64) of that dtype, plus the wide configuration for bf16, one text line each")
+                         "points (C = K = 64) of that dtype, plus the wide configuration for bf16, one text line each; "
+                         "q: the paper's grid of Section 4.3 (batch 56, output widths 1000 ... 60000, four families)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "

@@ -85,6 +85,28 @@ def sweep(dtype: str) -> Iterator[Workload]:
             yield sweep_point(S, d, dtype)
 
 
+# The paper's own single-layer grid (Section 4.3, the axes of Figs. 4-6): batch 56, output widths 1000 ... 60000,
+# for 15 channels and filters at dilation 8 (FP32, Fig. 4), 64 at dilation 1 (FP32, Fig. 5), and 32 and 16 at
+# dilation 4 in BF16 (Fig. 6 and the BF16 training shape of Section 4.4).  Same padding, all tensors U[-1,1].
+Q_SWEEP_Q = (1000, 2000, 5000, 10000, 20000, 60000)
+Q_SWEEP_S = (1, 5, 9, 15, 21, 25, 31, 49, 51)
+Q_SWEEP_FAMILIES = {
+    "c15_d8_fp32": (15, 8, "fp32"),
+    "c64_d1_fp32": (64, 1, "fp32"),
+    "c32_d4_bf16": (32, 4, "bf16"),
+    "c16_d4_bf16": (16, 4, "bf16"),
+}
+Q_SWEEP_N = 56
+
+
+def q_sweep_point(family: str, Q: int, S: int) -> Workload:
+    ch, d, dtype = Q_SWEEP_FAMILIES[family]
+    i_f = list(Q_SWEEP_FAMILIES).index(family)
+    return Workload(f"q_{family}_S{S}_Q{Q}", Q_SWEEP_N, ch, ch, Q, S, d, same_padding(S, d), dtype,
+                    "uniform", "uniform", "uniform",
+                    BASE_SEED + 10000 + 1000 * i_f + 10 * Q_SWEEP_S.index(S) + Q_SWEEP_Q.index(Q))
+
+
 WORKLOADS: Dict[str, Workload] = {w.name: w for w in (TINY, GENOMICS_FP32, GENOMICS_BF16, WIDE_BF16)}
 WORKLOADS.update({w.name: w for dt in ("fp32", "bf16") for w in sweep(dt)})
 for _dt in ("fp32", "bf16"):

@@ -201,6 +201,21 @@ def test_wide_full_size(binding, oracle):
     _run_full(binding, oracle, inputs.WIDE_BF16, "auto")
 
 
+# ---- the paper's own grid (Section 4.3): batch 56, output widths 1000 ... 60000, four channel/dilation families ----
+Q_POINTS = [(f, Q, 51) for f in inputs.Q_SWEEP_FAMILIES for Q in inputs.Q_SWEEP_Q]
+Q_POINTS += [(f, 1000, S) for f in inputs.Q_SWEEP_FAMILIES for S in (1, 5, 21)]       # short rows, few taps
+
+
+@pytest.mark.parametrize("family,Q,S", Q_POINTS, ids=[f"{f}_S{S}_Q{Q}" for f, Q, S in Q_POINTS])
+def test_paper_grid_batch56(binding, oracle, family, Q, S):
+    wl = inputs.q_sweep_point(family, Q, S)
+    # whole output wherever the oracle finishes in well under a minute; sampled for the two largest 64-channel points
+    if wl.flops > 3e11:
+        _run_sampled(binding, oracle, wl)
+    else:
+        _run_full(binding, oracle, wl, "auto")
+
+
 # ---- long segments (the paper's 600000-wide inputs, Section 4.5.3): one sample, sampled outputs -----
 LONG = [
     # name                N  C   K   W       S   d  P
