@@ -106,6 +106,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="genomics_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-backward", action="store_true",
+                    help="run the backward passes as conv1d_bwd_data + conv1d_bwd_weight instead of one conv1d_bwd call")
     ap.add_argument("--timing", choices=["both", "hot", "cold"], default="both",
                     help="profiling runs: launch only the hot (one buffer set) or only the cold (rotating sets) configuration, "
                          "so that a kernel trace of the run averages one of them")
@@ -181,11 +183,22 @@ def main() -> int:
 
     run_passes = tuple(p for p in PASSES if p in args.passes.split(","))
 
-    def step(s):
+    # A step is forward + both backward passes.  The backward passes go through conv1d_bwd (one call, same results
+    # bit for bit) unless --separate-backward asks for conv1d_bwd_data and conv1d_bwd_weight as calls of their own.
+    one_call_backward = set(("bwd_data", "bwd_weight")) <= set(run_passes)
+
+    def step_separate(s):
         for p in run_passes:
             launch(p, s)
 
-    def timed_regions(cold):
+    def step_one_call(s):
+        if "fwd" in run_passes:
+            launch("fwd", s)
+        binding.conv1d_bwd(s["x"], s["dy"], s["w"], wl.d, wl.P, out_dx=s["dx"], out_dw=s["dw"], workspace=s["ws"])
+
+    step = step_one_call if (one_call_backward and not args.separate_backward) else step_separate
+
+    def timed_regions(cold, step):
         """REGIONS regions of exactly args.steps steps each, every one bracketed by a device synchronisation."""
         out, k = [], 0
         for _ in range(REGIONS):
@@ -202,10 +215,25 @@ def main() -> int:
         step(sets[0])
     for s in sets[1:]:
         step(s)  # every set once: first-touch costs stay out of the cold figure
+    # The first ~50 ms of work after an idle period run slower (clocks ramp up): the regions of a cold start showed
+    # 96, 88, 84, 82, 80 us per step.  Keep the GPU busy for that long before anything is timed.
+    torch.cuda.synchronize()
+    t_ramp = time.perf_counter()
+    while time.perf_counter() - t_ramp < 0.1:
+        for _ in range(20):
+            step(sets[0])
+        torch.cuda.synchronize()
     # --timing hot / cold: both figures come from the one configuration asked for (the JSON says so in "timing_mode")
     hot_is_cold, cold_is_hot = args.timing == "cold", args.timing == "hot"
-    hot_regions = timed_regions(hot_is_cold)
-    cold_regions = timed_regions(not cold_is_hot)
+    hot_regions = timed_regions(hot_is_cold, step)
+    cold_regions = timed_regions(not cold_is_hot, step)
+    separate = None
+    if step is step_one_call and args.timing == "both":
+        for _ in range(3):
+            step_separate(sets[0])
+        sep = sorted(timed_regions(False, step_separate))[REGIONS // 2]
+        separate = {"ms_per_step": round(sep, 4), "value": round(len(run_passes) * wl.flops / (sep * 1e-3) / 1e12, 3),
+                    "what": "the same step with conv1d_bwd_data and conv1d_bwd_weight as two calls"}
     ms_per_step = sorted(hot_regions)[REGIONS // 2]
     ms_per_step_cold = sorted(cold_regions)[REGIONS // 2]
     value = len(run_passes) * wl.flops / (ms_per_step * 1e-3) / 1e12
@@ -218,7 +246,10 @@ def main() -> int:
         for i, (a, b) in enumerate(evs):
             s = sets[i % nsets] if cold else sets[0]
             a.record()
-            launch(p, s)
+            if p == "bwd":
+                binding.conv1d_bwd(s["x"], s["dy"], s["w"], wl.d, wl.P, out_dx=s["dx"], out_dw=s["dw"], workspace=s["ws"])
+            else:
+                launch(p, s)
             b.record()
         torch.cuda.synchronize()
         return sorted(a.elapsed_time(b) for a, b in evs)
@@ -271,6 +302,12 @@ def main() -> int:
                         "frac_mfma_peak": round(wl.flops / (res["avg_us"] * 1e-6) / 1e12 / PEAK[wl.dtype], 4),
                         "algorithmic_GBps": round(nbytes / (res["avg_us"] * 1e-6) / 1e9, 1)})
             epilogue[name] = res
+    bwd_one_call = None
+    if one_call_backward:
+        ms, msc = event_times("bwd", hot_is_cold), event_times("bwd", not cold_is_hot)
+        bwd_one_call = {"avg_us": round(1e3 * sum(ms) / len(ms), 2), "median_us": round(ms[len(ms) // 2] * 1e3, 2),
+                        "cold_us": round(1e3 * sum(msc) / len(msc), 2),
+                        "tflops": round(2 * wl.flops / (sum(ms) / len(ms) * 1e-3) / 1e12, 2)}
     # measured denominators: what this GPU sustains on an MFMA-only loop and on a plain copy
     measured = None
     if not args.no_ubench and args.timing == "both":
@@ -329,6 +366,8 @@ def main() -> int:
     out = {
         "metric": "TFLOP/s per step (fwd + bwd_data + bwd_weight), 1 MI355X", "value": round(value, 3), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "backward": "conv1d_bwd (one call for both backward passes)" if step is step_one_call else "conv1d_bwd_data + conv1d_bwd_weight",
+        "separate_backward_calls": separate, "bwd_one_call": bwd_one_call,
         "timing_mode": args.timing,
         "timing": f"median of {REGIONS} regions of {args.steps} steps, each between two device synchronisations",
         "regions_ms_per_step": [round(v, 4) for v in hot_regions],

@@ -166,6 +166,19 @@ int conv1d_bwd_weight(const void* x, const void* dy, float* dw,
                       int N, int C, int K, int W, int S, int dilation, int padding,
                       int dtype, void* stream);
 
+/* Both backward passes of a layer in one call, as a framework's backward step asks for them (Section 4.3 times
+ * forward() and backward() of the layer; backward is Sections 3.2 and 3.3 together):
+ *   dx = conv1d_bwd_data(dy, w)   and   dw = conv1d_bwd_weight(x, dy),   results bit-identical to those calls.
+ * The kernels of the two passes are queued back to back; for bfloat16 layers with C, K <= 16 and d = 8 the
+ * second stage of the weight gradient is not a launch of its own: the backward-data kernel adds up the partial
+ * sums while it waits for its first inputs.  Workspace as for conv1d_bwd_weight
+ * (conv1d_bwd_workspace_bytes returns the same size).  dx and dw must not alias each other or an input. */
+size_t conv1d_bwd_workspace_bytes(int N, int C, int K, int W, int S, int dilation, int padding, int dtype);
+int conv1d_bwd(const void* x, const void* dy, const void* w, float* dx, float* dw,
+               void* workspace, size_t workspace_bytes,
+               int N, int C, int K, int W, int S, int dilation, int padding,
+               int dtype, void* stream);
+
 /* conv1d_bwd_weight for callers that cannot allocate device memory or bring a
  * workspace: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  Same result, bit for bit, as conv1d_bwd_weight on the same

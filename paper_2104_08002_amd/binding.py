@@ -19,7 +19,7 @@ PASS_FWD, PASS_BWD_DATA, PASS_BWD_WEIGHT = 0, 1, 2
 
 EXPORTS = (
     "conv1d_out_width", "conv1d_fwd", "conv1d_fwd_ex", "conv1d_bwd_data", "conv1d_bwd_data_ex",
-    "conv1d_bwd_weight_workspace_bytes",
+    "conv1d_bwd_weight_workspace_bytes", "conv1d_bwd_workspace_bytes", "conv1d_bwd",
     "conv1d_bwd_weight", "conv1d_bwd_weight_noalloc", "conv1d_set_variant", "conv1d_kernel_name", "conv1d_status_string",
 )
 
@@ -59,6 +59,10 @@ def load() -> ctypes.CDLL:
     lib.conv1d_bwd_weight_workspace_bytes.argtypes = geom + [i]
     lib.conv1d_bwd_weight.restype = i
     lib.conv1d_bwd_weight.argtypes = [vp, vp, vp, vp, sz] + geom + [i, vp]
+    lib.conv1d_bwd_workspace_bytes.restype = sz
+    lib.conv1d_bwd_workspace_bytes.argtypes = geom + [i]
+    lib.conv1d_bwd.restype = i
+    lib.conv1d_bwd.argtypes = [vp, vp, vp, vp, vp, vp, sz] + geom + [i, vp]
     lib.conv1d_bwd_weight_noalloc.restype = i
     lib.conv1d_bwd_weight_noalloc.argtypes = [vp, vp, vp] + geom + [i, vp]
     lib.conv1d_set_variant.restype = i
@@ -250,3 +254,28 @@ def conv1d_bwd_weight_noalloc(x, dy, S: int, dilation: int, padding: int, out, s
     _check(load().conv1d_bwd_weight_noalloc(x.data_ptr(), dy.data_ptr(), _dev(out, "out").data_ptr(), N, C, K, W, S,
                                             dilation, padding, _dtype_code(x), _stream_ptr(stream)))
     return out
+
+
+def conv1d_bwd(x, dy, w, dilation: int, padding: int, out_dx=None, out_dw=None, workspace=None, stream=None):
+    """(dx, dw) = both backward passes of the layer in one call -> float32 [N,C,W] and [K,C,S]."""
+    import torch
+
+    _dev(x, "x"), _dev(dy, "dy"), _dev(w, "w")
+    N, C, W = x.shape
+    N2, K, Q = dy.shape
+    K2, C2, S = w.shape
+    if N2 != N or K2 != K or C2 != C or dy.dtype != x.dtype or w.dtype != x.dtype:
+        raise ValueError("x, dy and w disagree in shape or dtype")
+    if conv1d_out_width(W, S, dilation, padding) != Q:
+        raise ValueError("dy width does not match the geometry")
+    code = _dtype_code(x)
+    need = int(load().conv1d_bwd_workspace_bytes(N, C, K, W, S, dilation, padding, code))
+    ws = workspace if workspace is not None else torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    dx = out_dx if out_dx is not None else torch.empty((N, C, W), dtype=torch.float32, device=x.device)
+    dw = out_dw if out_dw is not None else torch.empty((K, C, S), dtype=torch.float32, device=x.device)
+    if tuple(dx.shape) != (N, C, W) or tuple(dw.shape) != (K, C, S) or dx.dtype != torch.float32 or dw.dtype != torch.float32:
+        raise ValueError("an output has the wrong shape or dtype")
+    _check(load().conv1d_bwd(x.data_ptr(), dy.data_ptr(), w.data_ptr(), _dev(dx, "out_dx").data_ptr(),
+                             _dev(dw, "out_dw").data_ptr(), ws.data_ptr(), ws.numel() * ws.element_size(), N, C, K, W, S,
+                             dilation, padding, code, _stream_ptr(stream)))
+    return dx, dw

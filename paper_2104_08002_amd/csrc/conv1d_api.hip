@@ -244,6 +244,43 @@ int conv1d_bwd_weight(const void* x, const void* dy, float* dw, void* workspace,
     return run_wgrad(g, x, dy, dw, workspace, workspace_bytes, dtype, stream);
 }
 
+size_t conv1d_bwd_workspace_bytes(int N, int C, int K, int W, int S, int dilation, int padding, int dtype) {
+    return conv1d_bwd_weight_workspace_bytes(N, C, K, W, S, dilation, padding, dtype);
+}
+
+int conv1d_bwd(const void* x, const void* dy, const void* w, float* dx, float* dw, void* workspace,
+               size_t workspace_bytes, int N, int C, int K, int W, int S, int dilation, int padding, int dtype,
+               void* stream) {
+    Geom g;
+    if (!x || !dy || !w || !dx || !dw || (dtype != CONV1D_FP32 && dtype != CONV1D_BF16)) return CONV1D_EINVAL;
+    if (!make_geom(N, C, K, W, S, dilation, padding, &g)) return CONV1D_EINVAL;
+    const size_t ea = dtype == CONV1D_BF16 ? 2 : 4;
+    if (!aligned(x, ea) || !aligned(dy, ea) || !aligned(w, ea) || !aligned(dx, 4) || !aligned(dw, 4)) return CONV1D_EINVAL;
+    const size_t need = conv1d_bwd_weight_workspace_bytes(N, C, K, W, S, dilation, padding, dtype);
+    if (!workspace || workspace_bytes < need) return CONV1D_EWORKSPACE;
+    if (!aligned(workspace, 256)) return CONV1D_EINVAL;
+    const int bf16 = dtype == CONV1D_BF16;
+    CorrProblem cp = bwd_data_problem(g, dy, w, dx, bf16);
+    WgradProblem wp = wgrad_problem(g, x, dy, dw, workspace, workspace_bytes, bf16);
+    const int corr_family = pick_corr(cp), wgrad_family = pick_wgrad(wp);
+    if (corr_family < 0 || wgrad_family < 0) return CONV1D_EUNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // Small-channel bf16 layers: the first stage of the weight gradient runs first, and the backward-data kernel that
+    // follows adds up its partial tiles while it waits for its own first inputs (no second-stage launch).
+    if (bf16 && corr_family == CONV1D_VARIANT_SMALLC && wgrad_family == CONV1D_VARIANT_SMALLC &&
+        smallc_bf16_corr_grid(cp) >= 4 * g.S) {
+        int nwg = 0;
+        hipError_t e = smallc_bf16_wgrad_stage1_launch(wp, st, &nwg);
+        if (e == hipErrorInvalidValue) return CONV1D_EUNSUPPORTED;
+        if (e != hipSuccess) return CONV1D_EHIP;
+        cp.tail = WgradTail{static_cast<const float*>(workspace), dw, g.K, g.C, g.S, nwg, wp.dw_sk, wp.dw_sc};
+        return run_corr(cp, stream);
+    }
+    const int r = run_wgrad(g, x, dy, dw, workspace, workspace_bytes, dtype, stream);
+    if (r != CONV1D_OK) return r;
+    return run_corr(cp, stream);
+}
+
 int conv1d_bwd_weight_noalloc(const void* x, const void* dy, float* dw, int N, int C, int K, int W, int S,
                               int dilation, int padding, int dtype, void* stream) {
     Geom g;

@@ -22,6 +22,16 @@ struct Epilogue {
     int out_bf16;       // the output tensor holds bfloat16 elements
 };
 
+// Second stage of a backward-weight pass whose first stage left one S x 16 x 16 partial tile per workgroup
+// (ws[(g*S + s)*256 + k*16 + c]): dw[k][c][s] = sum over g, in a fixed order.  Either a kernel of its own, or a side
+// job of the backward-data kernel that follows the first stage in a fused backward call (ws == nullptr: none).
+struct WgradTail {
+    const float* ws;
+    float* dw;
+    int K, C, S, nwg;
+    long dw_sk, dw_sc;
+};
+
 // One "correlation problem": the forward pass and the backward-data pass are both
 //   out[n][m][o] = sum_{r<R} sum_{s<S} in[n][r][o + s*d - P] * wt(m, r, s),   in = 0 outside [0, Win)
 // The forward pass (Eq. 2) has in = x, R = C, M = K, P = padding and wt(m,r,s) = w[m][r][s].
@@ -44,6 +54,8 @@ struct CorrProblem {
     int w_contig;
     // applied by the kernel that completes an output element; never combined with accumulate != 0
     Epilogue epi;
+    // side job for the first 4*S workgroups of the small-channel bf16 kernel (fused backward); else ws == nullptr
+    WgradTail tail;
 };
 
 // The backward-weight problem (Section 3.3):
@@ -90,6 +102,10 @@ hipError_t smallc_bf16_corr_launch(const CorrProblem& p, hipStream_t st);
 bool smallc_bf16_wgrad_supported(const WgradProblem& p);
 size_t smallc_bf16_wgrad_workspace(const WgradProblem& p);
 hipError_t smallc_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st);
+// first stage only: *nwg receives the number of partial tiles it leaves in the workspace
+hipError_t smallc_bf16_wgrad_stage1_launch(const WgradProblem& p, hipStream_t st, int* nwg);
+// number of workgroups smallc_bf16_corr_launch would start for this problem (0: not supported)
+int smallc_bf16_corr_grid(const CorrProblem& p);
 // fixed-order sum of per-workgroup partial tiles ws[(wg*S + s)*256 + k*16 + c] into dw[k][c][s]
 hipError_t smallc_wgrad_reduce_launch(const float* ws, float* dw, int K, int C, int S, long dw_sk, long dw_sc, int nwg,
                                       hipStream_t st);
@@ -176,6 +192,40 @@ __device__ __forceinline__ void epi_store4(const Epilogue& e, float* out, long i
     } else {
         *reinterpret_cast<epi_f32x4*>(out + idx) = v;
     }
+}
+
+// ---- second stage of the small-channel backward-weight kernels ------------------------------------------------
+// Work of "block" b (b < 4*S) of 512 threads on 64 consecutive elements of the S*256 partial tile: thread
+// (grp = tid >> 4, el = tid & 15) adds the tiles of workgroup group grp (of 32 contiguous groups) left to right for
+// the 4 elements 4 el .. 4 el + 3 (phase 1, result in part[grp][el]); after a workgroup barrier the threads of
+// group 0 add the 32 group sums left to right and store (phase 2).  The order never depends on who runs it.
+constexpr int kTailGroups = 32;
+constexpr int kTailPartSlots = kTailGroups * 17;  // 16-byte LDS slots the two phases share
+
+__device__ __forceinline__ void wgrad_tail_phase1(const WgradTail& t, int b, int tid, epi_f32x4* part) {
+    const int el = tid & 15, grp = tid >> 4;
+    const int e = b * 64 + 4 * el;
+    const int total = t.S * 256;
+    const int per = (t.nwg + kTailGroups - 1) / kTailGroups;
+    const int g0 = grp * per, g1 = min(t.nwg, g0 + per);
+    epi_f32x4 sum = epi_f32x4{0.f, 0.f, 0.f, 0.f};
+    const float* src = t.ws + e;
+#pragma unroll 8
+    for (int g = g0; g < g1; ++g) sum += *reinterpret_cast<const epi_f32x4*>(src + static_cast<long>(g) * total);
+    part[grp * 17 + el] = sum;
+}
+
+__device__ __forceinline__ void wgrad_tail_phase2(const WgradTail& t, int b, int tid, const epi_f32x4* part) {
+    if (tid >= 16) return;
+    const int el = tid;
+    epi_f32x4 sum = part[el];
+#pragma unroll
+    for (int i = 1; i < kTailGroups; ++i) sum += part[i * 17 + el];
+    const int e = b * 64 + 4 * el;
+    const int s = e >> 8, k = (e >> 4) & 15, c0 = e & 15;  // the 4 elements are 4 adjacent channels
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (k < t.K && c0 + j < t.C) t.dw[k * t.dw_sk + (c0 + j) * t.dw_sc + s] = sum[j];
 }
 
 // Workgroups are dealt round-robin to the 8 XCDs (workgroup b runs on XCD b % 8).  The logical index numbers

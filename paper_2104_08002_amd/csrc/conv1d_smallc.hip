@@ -658,40 +658,20 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_f32_kernel(WgradProblem p
 // blockIdx.y numbers the (filter block, channel block) pairs of a batched launch (K, C: totals).
 __global__ __launch_bounds__(512) void smallc_wgrad_reduce_kernel(const float* __restrict__ ws, float* __restrict__ dw, int K, int C, int S, long dw_sk,
                                                                   long dw_sc, int nwg) {
-    constexpr int kGroups = 32;
-    __shared__ f32x4 part[kGroups][17];
+    __shared__ epi_f32x4 part[kTailPartSlots];
+    WgradTail t;
     {
         const int ncbp = (C + 15) >> 4;
         const int pair = blockIdx.y, kbi = pair / ncbp, cbi = pair - kbi * ncbp;
-        ws += static_cast<long>(pair) * nwg * S * 256;
-        dw += kbi * 16 * dw_sk + cbi * 16 * dw_sc;
-        K = min(16, K - 16 * kbi);
-        C = min(16, C - 16 * cbi);
+        t.ws = ws + static_cast<long>(pair) * nwg * S * 256;
+        t.dw = dw + kbi * 16 * dw_sk + cbi * 16 * dw_sc;
+        t.K = min(16, K - 16 * kbi);
+        t.C = min(16, C - 16 * cbi);
+        t.S = S; t.nwg = nwg; t.dw_sk = dw_sk; t.dw_sc = dw_sc;
     }
-    // a block of 32 x 16 threads handles 64 consecutive tile elements: thread (grp, el) adds its group's
-    // workgroups for the 4 elements 4 el .. 4 el + 3 with 16-byte loads (256-byte row segments per group)
-    const int el = threadIdx.x & 15, grp = threadIdx.x >> 4;
-    const int e = blockIdx.x * 64 + 4 * el;  // index into one workgroup's S*256 partial tile (a multiple of 64)
-    const int total = S * 256;
-    const int per = (nwg + kGroups - 1) / kGroups;
-    const int g0 = grp * per, g1 = min(nwg, g0 + per);
-    f32x4 t = f32x4{0.f, 0.f, 0.f, 0.f};
-    {
-        const float* src = ws + e;
-#pragma unroll 8
-        for (int g = g0; g < g1; ++g) t += *reinterpret_cast<const f32x4*>(src + static_cast<long>(g) * total);
-    }
-    part[grp][el] = t;
+    wgrad_tail_phase1(t, blockIdx.x, threadIdx.x, part);
     __syncthreads();
-    if (grp == 0) {
-        f32x4 sum = part[0][el];
-#pragma unroll
-        for (int i = 1; i < kGroups; ++i) sum += part[i][el];
-        const int s = e >> 8, k = (e >> 4) & 15, c0 = e & 15;  // the 4 elements are 4 adjacent channels
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (k < K && c0 + j < C) dw[k * dw_sk + (c0 + j) * dw_sc + s] = sum[j];
-    }
+    wgrad_tail_phase2(t, blockIdx.x, threadIdx.x, part);
 }
 
 struct WgradF32Plan {

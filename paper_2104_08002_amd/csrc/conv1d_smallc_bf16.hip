@@ -260,6 +260,10 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
     // then keeps all NP slices in registers.  Both areas alias the output staging buffers.
     u32x4* entries = lds4 + 4 * LPS;
     unsigned short* raw = reinterpret_cast<unsigned short*>(entries + NP * 64);
+    // Fused backward: the first 4*S workgroups also finish the backward-weight pass that ran just before (its second
+    // stage), in the shadow of this prologue's memory latency; the group sums sit behind the raw weight copy.
+    epi_f32x4* tail_part = reinterpret_cast<epi_f32x4*>(entries + 2 * NP * 64);
+    const bool tail_job = p.tail.ws != nullptr && static_cast<int>(blockIdx.x) < 4 * p.tail.S;
     if (p.w_contig) {
         const int nW = p.M * p.R * p.S;
         constexpr int NV = (16 * 16 * 2 * NP / 8 + 511) / 512;  // 16-byte pieces per thread, worst case
@@ -281,7 +285,9 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
     } else if (!consumer && t_begin < t_end) {
         prefetch(t_begin);
     }
+    if (tail_job) wgrad_tail_phase1(p.tail, blockIdx.x, tid, tail_part);
     __syncthreads();
+    if (tail_job) wgrad_tail_phase2(p.tail, blockIdx.x, tid, tail_part);
     bf16x8 wreg[NP];
     if (consumer) {
         // Entry e = rtid + 256 k: the lane part (filter m, channel half h, tap half) is the same for every k, the
@@ -731,6 +737,12 @@ WgradPlan wgrad_plan(const WgradProblem& p) {
 
 bool smallc_bf16_corr_supported(const CorrProblem& p) { return corr_plan(p).ok; }
 
+int smallc_bf16_corr_grid(const CorrProblem& p) {
+    const CorrPlan pl = corr_plan(p);
+    if (!pl.ok) return 0;
+    return pl.ntiles < kNumCU ? pl.ntiles : kNumCU;
+}
+
 hipError_t smallc_bf16_corr_launch(const CorrProblem& p, hipStream_t st) {
     const CorrPlan pl = corr_plan(p);
     if (!pl.ok) return hipErrorInvalidValue;
@@ -752,13 +764,19 @@ size_t smallc_bf16_wgrad_workspace(const WgradProblem& p) {
     return pl.ok ? static_cast<size_t>(pl.grid) * p.S * 256 * sizeof(float) : 0;
 }
 
-hipError_t smallc_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st) {
+hipError_t smallc_bf16_wgrad_stage1_launch(const WgradProblem& p, hipStream_t st, int* nwg) {
     const WgradPlan pl = wgrad_plan(p);
     if (!pl.ok) return hipErrorInvalidValue;
-    hipError_t e = launch_kernel(pl.fast ? smallc_wgrad_bf16_d8_kernel<true> : smallc_wgrad_bf16_d8_kernel<false>, dim3(pl.grid),
-                                 dim3(512), 0, st, p, pl.SPR, pl.UPS, pl.units_per_row);
+    *nwg = pl.grid;
+    return launch_kernel(pl.fast ? smallc_wgrad_bf16_d8_kernel<true> : smallc_wgrad_bf16_d8_kernel<false>, dim3(pl.grid),
+                         dim3(512), 0, st, p, pl.SPR, pl.UPS, pl.units_per_row);
+}
+
+hipError_t smallc_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st) {
+    int nwg = 0;
+    const hipError_t e = smallc_bf16_wgrad_stage1_launch(p, st, &nwg);
     if (e != hipSuccess) return e;
-    return smallc_wgrad_reduce_launch(static_cast<const float*>(p.ws), p.dw, p.K, p.C, p.S, p.dw_sk, p.dw_sc, pl.grid, st);
+    return smallc_wgrad_reduce_launch(static_cast<const float*>(p.ws), p.dw, p.K, p.C, p.S, p.dw_sk, p.dw_sc, nwg, st);
 }
 
 }  // namespace conv1d
