@@ -99,6 +99,45 @@ def sweep_table(args, np, torch, binding, inputs) -> int:
     return 0
 
 
+def protocol_table(args, torch, inputs) -> int:
+    """The paper's own measurement (Section 4.3): wall time of net.forward(x) and of out.sum().backward() on a single
+    layer, averaged over 20 iterations, framework overhead included (the sum, the all-ones upstream gradient, the
+    accumulation into .grad, dtype casts).  Efficiency = nominal FLOPs / time / dense MFMA peak of the input type."""
+    import time as _t
+
+    from paper_2104_08002_amd import autograd
+
+    wls = [inputs.GENOMICS_FP32, inputs.GENOMICS_BF16] + [inputs.q_sweep_point(f, Q, 51) for f, Q in (
+        ("c15_d8_fp32", 60000), ("c64_d1_fp32", 10000), ("c64_d1_fp32", 60000), ("c32_d4_bf16", 60000), ("c16_d4_bf16", 60000))]
+    iters = 20
+    print(f"# {'layer':28s} | forward ms, TFLOP/s, % of peak | sum().backward() ms, TFLOP/s (2 passes), % of peak")
+    for wl in wls:
+        tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+        gen = torch.Generator(device="cuda").manual_seed(wl.seed)
+        net = autograd.Conv1d(wl.C, wl.K, wl.S, dilation=wl.d, padding=wl.P, dtype=tdt)
+        x = (torch.rand((wl.N, wl.C, wl.W), generator=gen, device="cuda") * 2 - 1).to(tdt).requires_grad_(True)
+        tf = tb = 0.0
+        for it in range(iters + 3):
+            torch.cuda.synchronize()
+            t0 = _t.perf_counter()
+            out = net.forward(x)
+            torch.cuda.synchronize()
+            t1 = _t.perf_counter()
+            out.sum().backward()
+            torch.cuda.synchronize()
+            t2 = _t.perf_counter()
+            if it >= 3:
+                tf += t1 - t0
+                tb += t2 - t1
+            x.grad = None
+            net.weight.grad = None
+        tf, tb = tf / iters, tb / iters
+        ff, fb = wl.flops / tf / 1e12, 2 * wl.flops / tb / 1e12
+        print(f"{wl.name:30s} | {tf * 1e3:8.3f} ms {ff:7.1f} TF {100 * ff / PEAK[wl.dtype]:5.1f} % | {tb * 1e3:8.3f} ms {fb:7.1f} TF "
+              f"{100 * fb / PEAK[wl.dtype]:5.1f} %", flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -106,6 +145,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="genomics_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--protocol", action="store_true",
+                    help="instead of the headline line: the paper's measurement protocol (Section 4.3) on single layers: "
+                         "wall time of net.forward(x) and out.sum().backward() through the autograd wrapper, 20 iterations")
     ap.add_argument("--separate-backward", action="store_true",
                     help="run the backward passes as conv1d_bwd_data + conv1d_bwd_weight instead of one conv1d_bwd call")
     ap.add_argument("--timing", choices=["both", "hot", "cold"], default="both",
@@ -148,6 +190,8 @@ def main() -> int:
     binding.conv1d_set_variant(args.variant)
     if args.sweep:
         return sweep_table(args, np, torch, binding, inputs)
+    if args.protocol:
+        return protocol_table(args, torch, inputs)
     wl = inputs.WORKLOADS[args.workload]
     data = inputs.make_inputs(wl)
     code = 1 if wl.dtype == "bf16" else 0

@@ -221,21 +221,32 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
         // here, behind branches that are uniform for the launch
         if (vec_out) {
             const int orow = lane >> 5, ocol = 4 * (lane & 31);
-            const int o = O0 + ob + ocol;
+            const bool col_ok = O0 + ob + ocol < p.Wout;
+            // All eight LDS reads are issued before the first store: a read-wait-store chain per row pair would put
+            // eight LDS round trips in a row on the producers' critical path.  Each variant of the store loop sits
+            // behind a branch that is uniform for the launch, so the plain float path has no branch inside.
+            f32x4 v[8];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                f32x4 v = *reinterpret_cast<const f32x4*>(src + (2 * q + orow) * kOS + ocol);
-                const long base = static_cast<long>(n) * p.out_sn + static_cast<long>(2 * q) * p.Wout + O0 + ob;  // uniform
-                if (2 * q + orow < p.M && o < p.Wout) {
-                    const long idx = base + static_cast<unsigned>(orow * p.Wout + ocol);
-                    if (p.accumulate) {
-                        f32x4* dst = reinterpret_cast<f32x4*>(p.out + idx);
-                        *dst = *dst + v;
-                    } else {
-                        if (p.epi.relu) v = epi_apply4(p.epi, v, 0.f);
-                        epi_store4(p.epi, p.out, idx, v);
+            for (int q = 0; q < 8; ++q) v[q] = *reinterpret_cast<const f32x4*>(src + (2 * q + orow) * kOS + ocol);
+            const long base = static_cast<long>(n) * p.out_sn + O0 + ob;                   // uniform
+            const unsigned lane_off = static_cast<unsigned>(orow * p.Wout + ocol);
+            if (!p.accumulate && !p.epi.relu && !p.epi.out_bf16) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    if (col_ok && 2 * q + orow < p.M)
+                        *reinterpret_cast<f32x4*>(p.out + base + static_cast<long>(2 * q) * p.Wout + lane_off) = v[q];
+            } else if (p.accumulate) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    if (col_ok && 2 * q + orow < p.M) {
+                        f32x4* dst = reinterpret_cast<f32x4*>(p.out + base + static_cast<long>(2 * q) * p.Wout + lane_off);
+                        *dst = *dst + v[q];
                     }
-                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    if (col_ok && 2 * q + orow < p.M)
+                        epi_store4(p.epi, p.out, base + static_cast<long>(2 * q) * p.Wout + lane_off, epi_apply4(p.epi, v[q], 0.f));
             }
         } else {
             for (int idx = lane; idx < 16 * T * 16; idx += 64) {
@@ -487,8 +498,8 @@ hipError_t corr_launch_np(const CorrProblem& p, const CorrPlan& pl, hipStream_t 
 // ------------------------------------------------------------------------------------------------
 // backward-weight, d == 8
 // ------------------------------------------------------------------------------------------------
-// A workgroup (4 waves) owns a strip of one sample: `UPS` consecutive units of 416 output columns
-// (13 k-steps of 32).  Columns are handled as 16-byte slots of 8 bf16: dy slot i <-> q = 8i..8i+7,
+// A workgroup owns a strip of one sample: consecutive units of 416 output columns (13 k-steps of 32; the
+// last unit of a strip may be shorter).  Columns are handled as 16-byte slots of 8 bf16: dy slot i <-> q = 8i..8i+7,
 // x slot i <-> input positions 8i - P .. 8i - P + 7 (so tap s reads x slot = dy slot + s).
 // Wave v owns taps s = v + 4i (i < 13).  In k-step t its lane (li, kb) needs, for tap slot i, the
 // x operand X_f = x[li][slots 4f + v + kb], f = t + i: a sliding window of 13 operands kept in a
@@ -497,7 +508,7 @@ hipError_t corr_launch_np(const CorrProblem& p, const CorrPlan& pl, hipStream_t 
 // the halo never has to be staged again.  The next period/unit is fetched from global memory into
 // registers while the MFMAs of the current unit run.
 //   xbuf [16][kXR]  row = channel, slot i <-> x slot 52(j+1) + i      (kXP = 60 slots staged)
-//   dybuf[16][kDR]  row = filter,  slot i <-> dy slot 52j + i
+//   dybuf[16][kDR]  row = filter,  slot i <-> dy slot 52j + i         (j, and the slots, count from the strip's start)
 constexpr int kNT = 13;            // taps per wave == operands in the ring == k-steps per unit
 constexpr int kUnitSlots = 4 * kNT;  // 52 slots = 416 columns
 constexpr int kXP = 60;            // x slots staged per period (52 + look-ahead of the highest tap slot)
@@ -507,9 +518,9 @@ constexpr int kWgMaxS = 7;         // 16 * (60 + 52) slots / 256 producer thread
 // Workgroup = 8 waves, one workgroup per CU: waves 0-3 ("consumers", one per tap class) do the operand
 // reads and MFMAs; waves 4-7 ("producers") fetch stage s+2 from global memory into registers and write
 // stage s+1 into the free half of the double-buffered LDS while the consumers work on stage s.  Stage s of
-// a strip is {x period j0+s+1, dy unit j0+s}; one workgroup barrier per unit hands the buffers over.
+// a strip is {x period s+1, dy unit s}; one workgroup barrier per unit hands the buffers over.
 template <bool FAST>
-__global__ __launch_bounds__(512, 2) void smallc_wgrad_bf16_d8_kernel(WgradProblem p, int SPR, int UPS, int units_per_row) {
+__global__ __launch_bounds__(512, 2) void smallc_wgrad_bf16_d8_kernel(WgradProblem p, int SPR, int KSS, int KS) {
     __shared__ u32x4 xbuf[2][16 * kXR];
     __shared__ u32x4 dybuf[2][16 * kDR];
     const int tid = threadIdx.x;
@@ -524,10 +535,17 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_bf16_d8_kernel(WgradProbl
     const int kb = lane >> 4;
     const unsigned short* __restrict__ x = static_cast<const unsigned short*>(p.x);
     const unsigned short* __restrict__ dy = static_cast<const unsigned short*>(p.dy);
+    // A strip is a run of KSS k-steps (32 columns each) of one sample, cut where the columns divide evenly over the
+    // workgroups, not at unit boundaries: its units are numbered from 0, and the last one may have fewer than 13
+    // k-steps (the consumers stop there; what is staged beyond the strip's last column is zero).
     const int n = blockIdx.x / SPR;
-    const int j0 = (blockIdx.x - n * SPR) * UPS;
-    const int j1 = min(j0 + UPS, units_per_row);
-    const int Qb = min(j1 * kUnitSlots * 8, p.Q);  // this strip's dy columns end here
+    const int ks0 = (blockIdx.x - n * SPR) * KSS;
+    const int ks1 = min(ks0 + KSS, KS);
+    const int sb = 4 * ks0;  // first dy slot of the strip
+    const int j0 = 0;
+    const int j1 = (ks1 - ks0 + kNT - 1) / kNT;
+    const int last_steps = (ks1 - ks0) - (j1 - 1) * kNT;  // k-steps of the last unit: 1 .. 13
+    const int Qb = min(ks1 * 32, p.Q);  // this strip's dy columns end here
     const unsigned short* xn = x + static_cast<long>(n) * p.x_sn;
     const unsigned short* dyn = dy + static_cast<long>(n) * p.dy_sn;
 
@@ -549,12 +567,12 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_bf16_d8_kernel(WgradProbl
         if (e < NX) {
             const int r = e / kXP, i = e - r * kXP;
             w.off = static_cast<unsigned>(min(r, p.C - 1) * p.W);
-            w.g0 = 8 * (kUnitSlots * (j0 + 1) + i) - p.P;
+            w.g0 = 8 * (sb + kUnitSlots + i) - p.P;
             w.lds = (r * kXR + i) | kIsX | (r < p.C ? 0 : kRowBad);
         } else {
             const int e2 = e - NX, r = e2 / kUnitSlots, i = e2 - r * kUnitSlots;
             w.off = static_cast<unsigned>(min(r, p.K - 1) * p.Q);
-            w.g0 = 8 * (kUnitSlots * j0 + i);
+            w.g0 = 8 * (sb + i);
             w.lds = (r * kDR + i) | (r < p.K ? 0 : kRowBad);
         }
         return w;
@@ -648,26 +666,36 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_bf16_d8_kernel(WgradProbl
     __syncthreads();
 
     if (consumer) {
-        for (int j = j0; j < j1; ++j) {
-            const int b = (j - j0) & 1;
+        // One unit: 13 k-steps (fewer in the last unit of a strip).  The dy operand of a k-step is read two k-steps
+        // ahead (three registers in rotation): one step ahead, its latency under load showed at the head of every step.
+        auto unit = [&](int b, auto partial, int nsteps) {
             const u32x4* xp = xbuf[b] + li * kXR + cw + kb;
             const u32x4* ap = dybuf[b] + li * kDR + kb;
-            bf16x8 a = as_bf16x8(ap[0]);
+            bf16x8 av[3];
+            av[0] = as_bf16x8(ap[0]);
+            av[1] = as_bf16x8(ap[4]);
 #pragma unroll
             for (int u = 0; u < kNT; ++u) {
-                // ring slot u is dead once tap slot 0 has consumed it: refill it (and fetch the next dy
-                // operand) right away so the other taps' MFMAs cover the LDS latency
-                acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ring[u], acc[0], 0, 0, 0);
-                const bf16x8 a_nxt = as_bf16x8(ap[4 * (u + 1 < kNT ? u + 1 : u)]);
-                ring[u] = as_bf16x8(xp[4 * u]);
-                __builtin_amdgcn_sched_barrier(0);
+                // (a guard per step, not an early exit: the loop has to unroll completely, the ring is indexed by u)
+                if (!decltype(partial)::value || u < nsteps) {
+                    // ring slot u is dead once tap slot 0 has consumed it: refill it (and fetch a later dy
+                    // operand) right away so the other taps' MFMAs cover the LDS latency
+                    acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[u % 3], ring[u], acc[0], 0, 0, 0);
+                    if (u + 2 < kNT) av[(u + 2) % 3] = as_bf16x8(ap[4 * (u + 2)]);
+                    ring[u] = as_bf16x8(xp[4 * u]);
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int i = 1; i < kNT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ring[(u + i) % kNT], acc[i], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                a = a_nxt;
+                    for (int i = 1; i < kNT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[u % 3], ring[(u + i) % kNT], acc[i], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
+        };
+        for (int j = j0; j + 1 < j1; ++j) {
+            unit((j - j0) & 1, std::false_type{}, kNT);
             __syncthreads();
         }
+        unit((j1 - 1 - j0) & 1, std::true_type{}, last_steps);
+        __syncthreads();
     } else {
         // Stage j + 1 sits in preB while an even stage (counted from j0) is consumed and in preA otherwise; its
         // registers then take stage j + 3.  The steady loop has no branch around a load, so the compiler can tell
@@ -709,7 +737,7 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_bf16_d8_kernel(WgradProbl
 }
 
 struct WgradPlan {
-    int SPR, UPS, units_per_row, grid, fast;
+    int SPR, KSS, KS, grid, fast;
     bool ok;
 };
 
@@ -718,12 +746,13 @@ WgradPlan wgrad_plan(const WgradProblem& p) {
     pl.ok = false;
     if (!p.bf16 || p.C > 16 || p.K > 16 || p.d != 8 || p.S > 4 * kNT) return pl;
     if (static_cast<long>(p.C) * p.W >= (1L << 30) || static_cast<long>(p.K) * p.Q >= (1L << 30)) return pl;
-    pl.units_per_row = cdiv(p.Q, kUnitSlots * 8);
-    // strips of UPS units so that about one workgroup per CU exists
-    const long total_units = static_cast<long>(p.N) * pl.units_per_row;
-    pl.UPS = static_cast<int>((total_units + kNumCU - 1) / kNumCU);
-    if (pl.UPS < 1) pl.UPS = 1;
-    pl.SPR = cdiv(pl.units_per_row, pl.UPS);
+    // Strips of KSS k-steps (32 columns) so that one workgroup per CU exists: the columns of a sample are dealt out
+    // evenly (60000 columns over 16 strips: 118 k-steps = 9 units and 1 step each, where whole units gave 10 and 5).
+    pl.KS = cdiv(p.Q, 32);
+    int spr = p.N >= kNumCU ? 1 : kNumCU / p.N;
+    if (spr > pl.KS) spr = pl.KS;
+    pl.KSS = cdiv(pl.KS, spr);
+    pl.SPR = cdiv(pl.KS, pl.KSS);
     const long grid = static_cast<long>(p.N) * pl.SPR;
     if (grid > 0x7fffffffL) return pl;
     pl.grid = static_cast<int>(grid);
@@ -769,7 +798,7 @@ hipError_t smallc_bf16_wgrad_stage1_launch(const WgradProblem& p, hipStream_t st
     if (!pl.ok) return hipErrorInvalidValue;
     *nwg = pl.grid;
     return launch_kernel(pl.fast ? smallc_wgrad_bf16_d8_kernel<true> : smallc_wgrad_bf16_d8_kernel<false>, dim3(pl.grid),
-                         dim3(512), 0, st, p, pl.SPR, pl.UPS, pl.units_per_row);
+                         dim3(512), 0, st, p, pl.SPR, pl.KSS, pl.KS);
 }
 
 hipError_t smallc_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st) {
