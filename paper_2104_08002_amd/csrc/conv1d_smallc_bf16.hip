@@ -41,6 +41,15 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast
 // k-slot layout of one MFMA (lane = li + 16*kb, element j of the lane's 8):
 //   channel r = 8*(kb & 1) + j,  tap s = p + NP*(kb >> 1)
 // LDS: plane h = kb & 1 holds channels 8h..8h+7; slot (h*LPS + i) <-> input position G0 + i.
+// Block staging (L16 kernels): blocks of 8 positions per window and the block count NB per position residue
+// (NB = 2 mod 16, NB > blocks staged), both fixed by the tap count bucket and the dilation.
+constexpr int blk_count(int NP, int d) { return (4 * 8 * 16 + (2 * NP - 1) * d + 7) / 8; }
+constexpr int blk_nb(int NP, int d) {
+    int nb = blk_count(NP, d) + 1;
+    while (nb % 16 != 2) ++nb;
+    return nb;
+}
+
 constexpr int kOS = 132;                    // row stride (floats) of an output staging tile: 4 rows apart -> 16 banks apart
 constexpr int kOstSlots = 4 * 16 * kOS / 4;  // 16-byte slots of one staging buffer (4 consumer waves x 16 rows)
 
@@ -55,9 +64,17 @@ constexpr int kOstSlots = 4 * 16 * kOS / 4;  // 16-byte slots of one staging buf
 // whose instruction stream is almost pure MFMA, and the memory traffic of both directions runs under it.
 // LDS (16-byte slots): window buffer b at b*2*LPS (two planes of LPS slots), staging buffer b at
 // 4*LPS + b*kOstSlots; the weight-slice assembly area aliases the staging buffers before the first tile.
-template <int NP, int G, int T, int MAXT, bool FAST>
+// L16 (d = 8 or 16, padding and width multiples of 8): the window is staged in blocks of 8 positions with 16-byte
+// global loads (a quarter of the load instructions of the dword path), and the LDS window is laid out block-transposed:
+//   slot(position) = (position & 7) * NB + (position >> 3),   NB = LPS / 8 = 2 (mod 16)
+// A producer lane that holds block b writes its eight positions to slots k*NB + b: the 16 lanes of a pass hit 16
+// adjacent slots.  A consumer's 16 lanes read 16 adjacent positions from a block boundary on: slots u + 2k (first
+// block) and u + 1 + 2k (second block) modulo 16, all different.  Both are conflict-free, and a step of 8 positions
+// is still a step of one slot, so the operand walk keeps its immediate offsets.
+template <int NP, int G, int T, int MAXT, bool FAST, bool L16>
 __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p, int tiles_per_row, int ntiles, int LPS, int vec_out) {
     static_assert(T == 8, "the output staging tile is 16 rows x 128 columns");
+    static_assert(!L16 || (FAST && (G == 1 || G == 2)), "block staging needs tile and tap shifts that are multiples of 8 positions");
     extern __shared__ u32x4 lds4[];
     constexpr int TQ = 4 * T * 16;
     const int tid = threadIdx.x;
@@ -185,9 +202,62 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
             ++cur_n;
         }
     };
-    Task pre[FAST ? MAXT : 1];
+    // ---- block staging (L16): one task = 8 channels (half h) x 8 adjacent positions, 8 loads of 16 bytes ----------
+    // (compile-time geometry: the LDS offsets of a lane's eight slots become immediates)
+    constexpr int NB = L16 ? blk_nb(NP, 16 / (G > 0 ? G : 1)) : 1;     // the host passes LPS = 8 * NB
+    constexpr int NBLK = L16 ? blk_count(NP, 16 / (G > 0 ? G : 1)) : 1;  // blocks staged per plane; 2 * NBLK <= 256
+    u32x4 pre16[L16 ? 8 : 1];
+    auto prefetch16 = [&](int t) {
+        const TilePos tp = tile_pos(t);
+        const int n = tp.n, G0 = tp.O0 - p.P;  // a multiple of 8
+        const int task = rtid < 2 * NBLK ? rtid : 2 * NBLK - 1;
+        const int h = task >= NBLK ? 1 : 0;
+        int g = G0 + 8 * (task - h * NBLK);
+        g = g < 0 ? 0 : (g > p.Win - 8 ? p.Win - 8 : g);
+        const char* base = reinterpret_cast<const char*>(in + static_cast<long>(n) * p.in_sn);  // uniform
+        const unsigned rowb = static_cast<unsigned>(p.Win) * 2u;                                     // uniform
+        const unsigned offmax = static_cast<unsigned>((p.R - 1) * p.Win + g) * 2u;
+        unsigned off = static_cast<unsigned>(8 * h * p.Win + g) * 2u;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            pre16[j] = *reinterpret_cast<const u32x4*>(base + min(off, offmax));
+            off += rowb;
+        }
+    };
+    auto commit16 = [&](int t, u32x4* wb) {
+        const TilePos tp = tile_pos(t);
+        const int G0 = tp.O0 - p.P;
+        const bool edge = G0 < 0 || G0 + 8 * NBLK > p.Win;  // uniform
+        if (rtid < 2 * NBLK) {
+            const int h = rtid >= NBLK ? 1 : 0;
+            const int blk = rtid - h * NBLK;
+            const int g = G0 + 8 * blk;
+            // a block is inside or outside the row as a whole (row length and padding are multiples of 8)
+            const bool pos_ok = g >= 0 && g + 8 <= p.Win;
+            u32x4* dst = wb + h * LPS + blk;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                u32x4 ev, od;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    unsigned a = pre16[2 * q][i], b = pre16[2 * q + 1][i];
+                    if (edge) {
+                        a = (pos_ok && 8 * h + 2 * q < p.R) ? a : 0u;
+                        b = (pos_ok && 8 * h + 2 * q + 1 < p.R) ? b : 0u;
+                    }
+                    ev[q] = __builtin_amdgcn_perm(b, a, kPermLo);
+                    od[q] = __builtin_amdgcn_perm(b, a, kPermHi);
+                }
+                dst[(2 * i) * NB] = ev;
+                dst[(2 * i + 1) * NB] = od;
+            }
+        }
+    };
+    Task pre[(FAST && !L16) ? MAXT : 1];
     auto prefetch = [&](int t) {  // producers: window of tile t -> registers
-        if constexpr (FAST) {
+        if constexpr (L16) {
+            prefetch16(t);
+        } else if constexpr (FAST) {
             const TilePos tp = tile_pos(t);
             const int n = tp.n, G0 = tp.O0 - p.P - psh;
 #pragma unroll
@@ -198,6 +268,10 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
         }
     };
     auto commit = [&](int t, u32x4* wb) {  // producers: registers (or memory) -> LDS window of tile t
+        if constexpr (L16) {
+            commit16(t, wb);
+            return;
+        }
         const TilePos tp = tile_pos(t);
         const int n = tp.n, G0 = tp.O0 - p.P - psh;
         const bool edge = G0 < 0 || G0 + 2 * LP2 > p.Win;
@@ -351,7 +425,9 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
         f32x4 acc[T];
 #pragma unroll
         for (int j = 0; j < T; ++j) acc[j] = f32x4{bias_li, bias_li, bias_li, bias_li};
-        const u32x4* bbase = wb + (kb & 1) * LPS + ob + li + (kb >> 1) * NP * d + psh;
+        // (L16: slot(position) = (position & 7) * NB + (position >> 3); every offset but the lane's own is a multiple of 8)
+        const u32x4* bbase = L16 ? wb + (kb & 1) * LPS + (li & 7) * NB + (li >> 3) + ((ob + (kb >> 1) * NP * d) >> 3)
+                                 : wb + (kb & 1) * LPS + ob + li + (kb >> 1) * NP * d + psh;
         // The input fragment is the A operand and the weight slice the B operand, so the accumulator tile is
         // [position][filter]: lane (li, kb) holds filter li at the 4 adjacent columns 4 kb .. 4 kb + 3 of tile j,
         // parked with one 16-byte LDS write.
@@ -361,7 +437,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
             // of their MFMAs; tile j is complete after step G*j + NP - 1 and is parked two steps later.
             // The scheduling barriers pin this interleaving.
             constexpr int PF = 3;
-            constexpr int D = 16 / (G > 0 ? G : 1);
+            constexpr int D = L16 ? (16 / (G > 0 ? G : 1)) / 8 : 16 / (G > 0 ? G : 1);  // slots between consecutive operands
             constexpr int NF = G * (T - 1) + NP;
             // rotating: operand m lives in slot m % (PF + 2); one slot more than the look-ahead needs, so that a
             // read never targets the registers of the operand whose MFMAs have only just been issued
@@ -406,6 +482,109 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
         }
     };
 
+    // ---- steady state, block staging ---------------------------------------------------------------
+    // Measured on this kernel: every instruction a producer wave issues, vector or scalar, lengthens the tile by about
+    // 4.4 cycles (it shares its SIMD's issue with the MFMA wave), so the producers' path for tiles that lie inside
+    // their row is stripped to the loads, the 32 byte permutes, the LDS accesses and the stores: everything that
+    // depends on the thread only (row offsets, LDS addresses, output offsets) is worked out once, what depends on the
+    // tile only is scalar, and tiles at a row edge, ragged row ends and the epilogue variants take the general lambdas.
+    if constexpr (L16) {
+        if (consumer) {
+            int k = 0;
+            for (int t = t_begin; t < t_end; ++t, ++k) {
+                compute(win(k & 1), ost(k & 1));
+                __syncthreads();
+            }
+            return;
+        }
+        const int task = rtid < 2 * NBLK ? rtid : 2 * NBLK - 1;  // idle threads repeat the last task: same data, same slots
+        const int h = task >= NBLK ? 1 : 0;
+        const int blk = task - h * NBLK;
+        unsigned voff_ld[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) voff_ld[j] = static_cast<unsigned>(min(8 * h + j, p.R - 1) * p.Win + 8 * blk) * 2u;
+        const int ldsw = h * LPS + blk;
+        const int orow = lane >> 5, ocol = 4 * (lane & 31);
+        unsigned voff_st[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) voff_st[q] = static_cast<unsigned>((2 * q + orow) * p.Wout + ocol) * 4u;
+        const int ldsr = orow * kOS + ocol;
+        const bool plain_out = vec_out && !p.accumulate && !p.epi.relu && !p.epi.out_bf16 && p.M >= 15;
+        const bool last_row_ok = orow < p.M - 14;
+        auto interior = [&](int O0) { return O0 - p.P >= 0 && O0 - p.P + 8 * NBLK <= p.Win; };
+        auto prefetch_plain = [&](int n, int O0) {
+            const char* base = reinterpret_cast<const char*>(in + static_cast<long>(n) * p.in_sn + (O0 - p.P));  // uniform
+#pragma unroll
+            for (int j = 0; j < 8; ++j) pre16[j] = *reinterpret_cast<const u32x4*>(base + voff_ld[j]);
+        };
+        auto commit_plain = [&](u32x4* wb) {
+            u32x4* dst = wb + ldsw;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                u32x4 ev, od;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    ev[q] = __builtin_amdgcn_perm(pre16[2 * q + 1][i], pre16[2 * q][i], kPermLo);
+                    od[q] = __builtin_amdgcn_perm(pre16[2 * q + 1][i], pre16[2 * q][i], kPermHi);
+                }
+                dst[(2 * i) * NB] = ev;
+                dst[(2 * i + 1) * NB] = od;
+            }
+        };
+        auto flush_plain = [&](int n, int O0, int b) {
+            const float* src = ost(b) + ldsr;
+            f32x4 v[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v[q] = *reinterpret_cast<const f32x4*>(src + 2 * q * kOS);
+            char* base = reinterpret_cast<char*>(p.out + static_cast<long>(n) * p.out_sn + O0 + ob);  // uniform
+#pragma unroll
+            for (int q = 0; q < 7; ++q) *reinterpret_cast<f32x4*>(base + voff_st[q]) = v[q];
+            if (last_row_ok) *reinterpret_cast<f32x4*>(base + voff_st[7]) = v[7];
+        };
+        // (sample, first column) of tiles t - 1 .. t + 2, moved along with the loop
+        TilePos tm1{0, 0}, t0 = tile_pos(t_begin), tp1 = tile_pos(t_begin + 1), tp2 = tile_pos(t_begin + 2);
+        auto next_pos = [&](TilePos a) {
+            a.O0 += TQ;
+            if (a.O0 >= row_w) {
+                a.O0 = 0;
+                ++a.n;
+            }
+            return a;
+        };
+        int k = 0;
+        for (int t = t_begin; t < t_end; ++t, ++k) {
+            if (t + 1 < t_end) {
+                if (interior(tp1.O0)) {
+                    commit_plain(win((k + 1) & 1));
+                } else {
+                    commit16(t + 1, win((k + 1) & 1));
+                }
+                if (t + 2 < t_end) {
+                    if (interior(tp2.O0)) {
+                        prefetch_plain(tp2.n, tp2.O0);
+                    } else {
+                        prefetch16(t + 2);
+                    }
+                }
+            }
+            if (k > 0) {
+                if (plain_out && tm1.O0 + TQ <= p.Wout) {
+                    flush_plain(tm1.n, tm1.O0, (k - 1) & 1);
+                } else {
+                    flush(t - 1, (k - 1) & 1);
+                }
+            }
+            __syncthreads();
+            tile_advance();
+            tm1 = t0;
+            t0 = tp1;
+            tp1 = tp2;
+            tp2 = next_pos(tp2);
+        }
+        if (k > 0) flush(t_end - 1, (k - 1) & 1);
+        return;
+    }
+
     // ---- steady state -----------------------------------------------------------------------------
     int k = 0;
     for (int t = t_begin; t < t_end; ++t, ++k) {
@@ -429,7 +608,7 @@ constexpr int kCorrMaxT = 4;
 constexpr int kNPBuckets[] = {3, 5, 9, 13, 17, 26};
 
 struct CorrPlan {
-    int NP, G, LPS, tiles_per_row, ntiles, fast, vec_out;
+    int NP, G, LPS, tiles_per_row, ntiles, fast, vec_out, l16;
     size_t lds_bytes;
     bool ok;
 };
@@ -455,6 +634,7 @@ CorrPlan corr_plan(const CorrProblem& p) {
     const long slots = 4 * LPS + 2 * kOstSlots;
     if (slots * 16 > kLdsBudget) return pl;  // one workgroup per CU
     pl.LPS = static_cast<int>(LPS);
+    pl.l16 = 0;
     pl.tiles_per_row = cdiv(p.Wout, TQ);
     const long nt = static_cast<long>(p.N) * pl.tiles_per_row;
     if (nt > 0x7fffffffL) return pl;
@@ -464,13 +644,25 @@ CorrPlan corr_plan(const CorrProblem& p) {
     pl.fast = (p.Win % 2 == 0) && (p.in_sn % 2 == 0) && (reinterpret_cast<uintptr_t>(p.in) % 4 == 0) && p.Win >= 2;
     pl.vec_out = (p.Wout % 4 == 0) && (reinterpret_cast<uintptr_t>(p.out) % 16 == 0) &&
                  static_cast<long>(p.M) * p.Wout < (1L << 30);
+    // block staging: see the kernel.  NB = 2 (mod 16) blocks per position residue, one plane = 8 * NB slots
+    if (pl.fast && (pl.G == 1 || pl.G == 2) && p.P % 8 == 0 && p.Win % 8 == 0 && p.in_sn % 8 == 0 && p.Win >= 8 &&
+        reinterpret_cast<uintptr_t>(p.in) % 16 == 0) {
+        const long nblk = blk_count(pl.NP, p.d);
+        const long nb = blk_nb(pl.NP, p.d);
+        const long slots16 = 4 * 8 * nb + 2 * kOstSlots;
+        if (2 * nblk <= 256 && slots16 * 16 <= kLdsBudget) {
+            pl.l16 = 1;
+            pl.LPS = static_cast<int>(8 * nb);
+            pl.lds_bytes = static_cast<size_t>(slots16) * 16;
+        }
+    }
     pl.ok = true;
     return pl;
 }
 
-template <int NP, int G, bool FAST>
+template <int NP, int G, bool FAST, bool L16 = false>
 hipError_t corr_launch_f(const CorrProblem& p, const CorrPlan& pl, hipStream_t st) {
-    auto kern = smallc_corr_bf16_kernel<NP, G, kCorrT, kCorrMaxT, FAST>;
+    auto kern = smallc_corr_bf16_kernel<NP, G, kCorrT, kCorrMaxT, FAST, L16>;
     hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), pl.lds_bytes);
     if (e != hipSuccess) return e;
     const int grid = pl.ntiles < kNumCU ? pl.ntiles : kNumCU;
@@ -479,6 +671,9 @@ hipError_t corr_launch_f(const CorrProblem& p, const CorrPlan& pl, hipStream_t s
 
 template <int NP, int G>
 hipError_t corr_launch_t(const CorrProblem& p, const CorrPlan& pl, hipStream_t st) {
+    if constexpr (G == 1 || G == 2) {
+        if (pl.l16) return corr_launch_f<NP, G, true, true>(p, pl, st);
+    }
     return pl.fast ? corr_launch_f<NP, G, true>(p, pl, st) : corr_launch_f<NP, G, false>(p, pl, st);
 }
 

@@ -116,6 +116,12 @@ SMALL = [
     ("str3_bwd",          4, 1056, 200, 200, 12, 2, 11),    # odd padding
     ("str5_fwd",          4, 232, 1056, 200, 17, 2, 16),    # an odd number of stages, the last tile of the last sample
     ("str5_bwd",          4, 1056, 232, 210, 15, 8, 3),
+    # small-channel bf16 forward / backward-data with block staging (d = 8 or 16; width and padding multiples of 8)
+    ("blk_d16_S25",       2, 15, 15, 3000, 25, 16, 192),
+    ("blk_d8_S9",         3, 10, 8,  4000, 9,  8,  32),
+    ("blk_short",         2, 15, 15, 64,   51, 8,  200),   # both row edges inside one window
+    ("blk_P_gt_span",     2, 7,  16, 2048, 5,  8,  40),    # backward-data shift -8: window starts beyond column 0
+    ("blk_one_block",     1, 16, 16, 8,    3,  8,  8),
     ("c40_halo_gt_width", 2, 40, 24, 200,  51, 8,  200),   # many channels, halo (S-1)d = 400 exceeds W
     ("c40_tiny_Q",        3, 40, 24, 420,  51, 8,  0),     # Q = 20: less than one k-step / one position block pair
 ]
