@@ -118,6 +118,16 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
         for (int fb = 0; fb < kFB; ++fb)
 #pragma unroll
             for (int t = 0; t < kT; ++t) acc[fb][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // The bias of the lane's filters, loaded once: a load where a tile completes would wait, with the counter
+        // the vector memory instructions share, for every output store still in flight.
+        float bm[kFB][4];
+#pragma unroll
+        for (int fb = 0; fb < kFB; ++fb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int m = (fg * kFB + fb) * 16 + 4 * kb + i;
+                bm[fb][i] = m < a.M ? epi_bias(a.epi, m) : 0.f;
+            }
 
         int tile = t_begin, cc = 0;
         __syncthreads();  // raw weights of stage 0 are in LDS
@@ -157,11 +167,10 @@ __global__ __launch_bounds__(512, 2) void igemm_corr_bf16_kernel(IgArgs a) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int m = (fg * kFB + fb) * 16 + 4 * kb + i;
-                        const float bm = m < a.M ? epi_bias(a.epi, m) : 0.f;
 #pragma unroll
                         for (int t = 0; t < kT; ++t) {
                             if (m < a.M && o + 16 * t < a.Wout)
-                                epi_store(a.epi, a.out, base + static_cast<long>(m) * a.Wout + o + 16 * t, epi_apply(a.epi, acc[fb][t][i], bm));
+                                epi_store(a.epi, a.out, base + static_cast<long>(m) * a.Wout + o + 16 * t, epi_apply(a.epi, acc[fb][t][i], bm[fb][i]));
                         }
                     }
 #pragma unroll

@@ -35,6 +35,7 @@ namespace rg {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int kLdsBudget = 160 * 1024;
@@ -43,7 +44,9 @@ constexpr int kNumCU = 256;
 constexpr int kMaxWT = 5;         // window tasks per producer thread
 constexpr int kMaxWI = 4;         // weight entries per thread and chunk (prologue, 512 threads)
 constexpr int kMaxRP = 3;         // raw 16-byte pieces per thread and chunk
+constexpr int kMaxDE = 8;         // weight entries per thread of the direct prologue
 constexpr int kQS = 68;           // slots per (plane, tap group, filter block): 4 k-blocks x 17
+constexpr int kBufferRsrcFlags = 0x00020000;  // fourth dword of a raw buffer descriptor (32-bit data format, no swizzle)
 constexpr unsigned kPermLo = 0x05040100u;  // {b.lo16, a.lo16} -> a.lo | b.lo << 16
 constexpr unsigned kPermHi = 0x07060302u;  // {b.hi16, a.hi16} -> a.hi | b.hi << 16
 
@@ -67,6 +70,10 @@ struct RgArgs {
     long su;           // elements between the starts of consecutive runs
     long wbytes;       // size of the weight tensor
     int raw_slots;     // NU * NPc
+    int t_base, t_rem; // tiles per team: t_base, and one more for the first t_rem teams
+    FastDiv dv_nfg, dv_tpr, dv_ncc, dv_lp2, dv_npc, dv_s, dv_ngw;  // nfg, tiles_per_row, ncc, LP / 2, NPc, S, NGW
+    FastDiv dv_pl;     // ncc * NG
+    int direct;        // few weights: every thread loads its entries straight from the tensor (no raw buffers)
     int vec_out;       // output rows and the base pointer are 16-byte aligned
     Epilogue epi;
 };
@@ -97,9 +104,9 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
     const int kb = lane >> 4;
 
     const int lid = xcd_logical_id(blockIdx.x, gridDim.x);
-    const int team = lid / a.nfg, fg = lid - team * a.nfg;
-    const int t_begin = static_cast<int>(static_cast<long>(team) * a.nct / a.nteams);
-    const int t_end = static_cast<int>(static_cast<long>(team + 1) * a.nct / a.nteams);
+    const int team = fast_div(lid, a.dv_nfg), fg = lid - team * a.nfg;
+    const int t_begin = team * a.t_base + min(team, a.t_rem);
+    const int t_end = t_begin + a.t_base + (team < a.t_rem ? 1 : 0);
     const int nstages = (t_end - t_begin) * a.ncc;
     if (nstages <= 0) return;  // the whole workgroup (the plan gives every team at least one tile)
 
@@ -111,21 +118,24 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
     const int LP2 = a.LP >> 1;
     const int NWT = a.NG * LP2;
     int wt_plane8[kMaxWT], wt_pair[kMaxWT], wt_dst[kMaxWT];
+    unsigned wt_off[kMaxWT];  // byte offset of the task's first load from that of (channel r0, position G0)
 #pragma unroll
     for (int k = 0; k < kMaxWT; ++k) {
         const int e = min(rtid + k * 256, NWT - 1);
-        const int g = e / LP2;
+        const int g = fast_div(e, a.dv_lp2);
         wt_plane8[k] = 8 * g;
         wt_pair[k] = e - g * LP2;
         wt_dst[k] = g * a.LPS + 2 * wt_pair[k];
+        wt_off[k] = static_cast<unsigned>(8 * g * a.Win + 2 * wt_pair[k]) * 2u;
     }
     struct Geo {
         int n, G0, r0;  // sample, window origin, first channel of the stage
     };
     auto geo = [&](int st) -> Geo {
-        const int ct = t_begin + st / a.ncc, cc = st - (st / a.ncc) * a.ncc;
+        const int tq = fast_div(st, a.dv_ncc);
+        const int ct = t_begin + tq, cc = st - tq * a.ncc;
         Geo g;
-        g.n = ct / a.tiles_per_row;
+        g.n = fast_div(ct, a.dv_tpr);
         g.G0 = (ct - g.n * a.tiles_per_row) * kTW - a.P - a.delta;
         g.r0 = cc * a.NG * 8;
         return g;
@@ -140,8 +150,21 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
         constexpr int NT = decltype(nt_)::value;
         const char* ib = reinterpret_cast<const char*>(a.in + static_cast<long>(g.n) * a.in_sn);
         const unsigned rowb = static_cast<unsigned>(a.Win) * 2u;
-        // (one path for interior and edge windows: clamping on the vector ALU measured faster than a second path
-        // with scalar row bases)
+        if (interior(g)) {
+            // Nothing to clamp: buffer loads from the sample's [R][Win] block, whose address is a per-thread offset
+            // that never changes plus a scalar offset (stage origin, row) - no vector instruction per load.  (The
+            // range check of the descriptor is not relied upon: every address is inside the block.)
+            const __amdgpu_buffer_rsrc_t rsrc =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(ib), 0, a.R * static_cast<int>(rowb), kBufferRsrcFlags);
+            const int so = g.r0 * static_cast<int>(rowb) + 2 * g.G0;
+#pragma unroll
+            for (int k = 0; k < NT; ++k) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    wr[k][j] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, static_cast<int>(wt_off[k]), so + j * static_cast<int>(rowb), 0);
+            }
+            return;
+        }
 #pragma unroll
         for (int k = 0; k < NT; ++k) {
             int pos = g.G0 + 2 * wt_pair[k];
@@ -157,12 +180,27 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
     };
     auto window_commit = [&](const Geo& g, int b, unsigned (&wr)[kMaxWT][8]) {
         u32x4* win = lds4 + wbase + b * a.win_slots;
-        const bool inner = interior(g);
+        if (interior(g)) {  // nothing to mask
+#pragma unroll
+            for (int k = 0; k < kMaxWT; ++k)
+                if (rtid + k * 256 < NWT) {
+                    u32x4 ev, od;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        ev[q] = __builtin_amdgcn_perm(wr[k][2 * q + 1], wr[k][2 * q], kPermLo);
+                        od[q] = __builtin_amdgcn_perm(wr[k][2 * q + 1], wr[k][2 * q], kPermHi);
+                    }
+                    u32x4* dst = win + wt_dst[k];
+                    dst[0] = ev;
+                    dst[1] = od;
+                }
+            return;
+        }
 #pragma unroll
         for (int k = 0; k < kMaxWT; ++k)
             if (rtid + k * 256 < NWT) {
                 const int pos = g.G0 + 2 * wt_pair[k];
-                const bool ok = inner || (pos >= 0 && pos < a.Win);  // a pair is inside or outside the row as a whole
+                const bool ok = pos >= 0 && pos < a.Win;  // a pair is inside or outside the row as a whole
                 u32x4 ev, od;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -176,10 +214,6 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
             }
     };
     Geo g0 = geo(0), g1 = geo(1 < nstages ? 1 : 0), g2 = g1;
-    if (!consumer) {
-        __builtin_amdgcn_s_setprio(3);
-        window_prefetch(std::integral_constant<int, kMaxWT>{}, g0, wreg[0]);  // in flight during the prologue
-    }
 
     // ---- prologue: the workgroup's weight entries, gathered chunk by chunk (every thread helps) --------------
     // The weights of a chunk (NGW planes of 8 channels) are NU contiguous runs of the [K][C][S] tensor (forward: one run of 8 NGW channels x
@@ -187,55 +221,109 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
     // fetched as 16-byte pieces from 4-byte aligned addresses (two chunks ahead), parked raw in the LDS that
     // will later hold the windows, and the entries (8 channels of one tap per lane) are gathered with 2-byte LDS
     // reads.  Entries of padded taps, channels beyond R and filters beyond M stay zero.
-    {
+    // The prologue runs on 8 waves that share 4 SIMDs and every vector instruction of it costs the workgroup about 8
+    // cycles: whatever does not depend on the chunk is computed once, and the steps an aligned, complete tensor
+    // does not need (masks, the shift of the last pieces) sit behind launch- or chunk-uniform branches.
+    if (a.direct) {
+        // Few weights (at most kMaxDE entries per thread): the 8 channels of an entry are 8 two-byte loads from the
+        // tensor, all requested at once, before anything else; nothing passes through raw buffers, so the first
+        // window can be written as soon as it arrives.  What the workgroup waits for is one memory round trip.
+        const int PL = a.ncc * a.NG;
+        const int NE = FB * 16 * PL * a.S;
+        const int m0 = fg * FB * 16;
+        unsigned dv[kMaxDE][8];
+        int dslot[kMaxDE], dnv[kMaxDE];
+        // channels beyond R or filters beyond M anywhere in the launch?  (else no entry needs a clamp or a mask)
+        const bool wmask = PL * 8 != a.R || a.nfg * FB * 16 != a.M;
+        // buffer loads: one byte offset per entry plus a scalar offset per channel (the range check of the descriptor
+        // is not relied upon: every address is inside the tensor)
+        const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<unsigned short*>(a.wt), 0, static_cast<int>(static_cast<unsigned>(a.wbytes)), kBufferRsrcFlags);
+        const int sr2 = 2 * static_cast<int>(a.w_sr);
+#pragma unroll
+        for (int k = 0; k < kMaxDE; ++k)
+            if (k * 512 < NE) {  // uniform
+                const int e = min(tid + k * 512, NE - 1);
+                const int mg = fast_div(e, a.dv_s), sx = e - mg * a.S;
+                // neighbouring lanes take neighbouring addresses: after the taps, the planes of one filter
+                // (forward, [m][r][s]) or the filters of one plane (backward-data, [r][m][s])
+                int ml, g;
+                if (a.fwd_mode) {
+                    ml = fast_div(mg, a.dv_pl);
+                    g = mg - ml * PL;
+                } else {
+                    g = mg / (FB * 16);
+                    ml = mg - g * (FB * 16);
+                }
+                const unsigned base = static_cast<unsigned>(min(m0 + ml, a.M - 1)) * static_cast<unsigned>(a.w_sm) +
+                                      static_cast<unsigned>(a.fwd_mode ? sx : a.S - 1 - sx);
+                dslot[k] = ((g * JT + (sx >> 2)) * FB + (ml >> 4)) * kQS + 17 * (sx & 3) + (ml & 15);
+                if (!wmask) {
+                    const int vo = static_cast<int>((base + static_cast<unsigned>(8 * g) * static_cast<unsigned>(a.w_sr)) << 1);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        dv[k][j] = static_cast<unsigned short>(__builtin_amdgcn_raw_buffer_load_b16(wrsrc, vo, j * sr2, 0));
+                } else {
+                    dnv[k] = m0 + ml < a.M ? a.R - 8 * g : 0;  // channels of the entry that exist
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        dv[k][j] = a.wt[base + static_cast<unsigned>(min(8 * g + j, a.R - 1)) * static_cast<unsigned>(a.w_sr)];
+                }
+            }
+        if (!consumer) {
+            __builtin_amdgcn_s_setprio(3);
+            window_prefetch(std::integral_constant<int, kMaxWT>{}, g0, wreg[0]);
+        }
         for (int e = tid; e < a.wres_slots; e += 512) lds4[e] = u32x4{0u, 0u, 0u, 0u};
+        __syncthreads();  // the zeroes are in place
+#pragma unroll
+        for (int k = 0; k < kMaxDE; ++k)
+            if (tid + k * 512 < NE) {
+                if (wmask) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) dv[k][j] = j < dnv[k] ? dv[k][j] : 0u;
+                }
+                lds4[dslot[k]] = u32x4{dv[k][0] | (dv[k][1] << 16), dv[k][2] | (dv[k][3] << 16), dv[k][4] | (dv[k][5] << 16), dv[k][6] | (dv[k][7] << 16)};
+            }
+        // (no barrier here: the one that hands stage 0 to the consumers follows)
+    } else {
         const int NWI = FB * 16 * a.NGW * a.S;  // entries of one chunk (NGW planes)
         const int nchunks = a.ncc * a.NG / a.NGW;
         const int NRP = a.NU * a.NPc;
         const int RSH = a.NPc * 8;  // halfwords per raw run
-        const int cs = a.fwd_mode ? a.S : RSH;
-        int rp_u[kMaxRP], rp_q[kMaxRP];
+        const int cs2 = 2 * (a.fwd_mode ? a.S : RSH);  // bytes between the 8 channels of an entry in a raw buffer
+        const int m0 = fg * FB * 16;
+        // element offset of the first run of chunk cc (even: m0 is a multiple of 16 and the chunks start at multiples of 8 channels)
+        auto chunk_base = [&](int cc) -> unsigned {  // the tensor has fewer than 2^31 elements
+            return static_cast<unsigned>(static_cast<long>(m0) * a.w_sm + static_cast<long>(cc * a.NGW * 8) * a.w_sr);
+        };
+        // raw piece k of the thread: piece q of run u, parked at slot u * NPc + q = tid + 512 k of the raw buffer
+        unsigned rp_run[kMaxRP], rp_q16[kMaxRP];
+        int rp_u[kMaxRP];
 #pragma unroll
         for (int k = 0; k < kMaxRP; ++k) {
             const int e = min(tid + k * 512, NRP - 1);
-            rp_u[k] = e / a.NPc;
-            rp_q[k] = e - rp_u[k] * a.NPc;
+            const int u = fast_div(e, a.dv_npc);
+            rp_u[k] = u;
+            rp_q16[k] = 16u * static_cast<unsigned>(e - u * a.NPc);
+            // forward: the runs are filters, the same in every chunk; filters beyond M repeat the last one
+            rp_run[k] = static_cast<unsigned>(a.fwd_mode ? min(u, a.M - 1 - m0) : u) * static_cast<unsigned>(a.su);
         }
-        int wi_idx0[kMaxWI], wi_lds[kMaxWI], wi_g8[kMaxWI], wi_par[kMaxWI], wi_ml[kMaxWI];
-#pragma unroll
-        for (int k = 0; k < kMaxWI; ++k) {
-            const int e = min(tid + k * 512, NWI - 1);
-            const int sx = e % a.S, mg = e / a.S;
-            const int g = mg % a.NGW, ml = mg / a.NGW;
-            if (a.fwd_mode) {
-                wi_idx0[k] = ml * RSH + 8 * g * a.S + sx;
-                const int pm = static_cast<int>((ml * a.w_sm) & 1);
-                wi_par[k] = pm | (pm << 1);
-            } else {
-                wi_idx0[k] = 8 * g * RSH + ml * a.S + (a.S - 1 - sx);
-                wi_par[k] = static_cast<int>(a.w_sr & 1) << 1;  // runs of odd channels start at the other parity
-            }
-            wi_lds[k] = ((g * JT + (sx >> 2)) * FB + (ml >> 4)) * kQS + 17 * (sx & 3) + (ml & 15);
-            wi_g8[k] = 8 * g;
-            wi_ml[k] = ml;
-        }
-        const int m0 = fg * FB * 16;
-        auto chunk_base = [&](int cc) -> long { return static_cast<long>(m0) * a.w_sm + static_cast<long>(cc * a.NGW * 8) * a.w_sr; };
         constexpr int kDepth = 4;  // chunks whose raw pieces are in flight
         u32x4 rreg[kDepth][kMaxRP];
         // byte offset of piece k of chunk cc (4-byte aligned), and the last offset a 16-byte load may start at
         const unsigned last_dw = static_cast<unsigned>(a.wbytes - 2) & ~3u;  // the last dword that holds an element
         const unsigned last_piece = last_dw - 12u;
         auto piece_offset = [&](int cc, int k) -> unsigned {
-            const int r0 = cc * a.NGW * 8;
-            const unsigned eb = static_cast<unsigned>(chunk_base(cc));  // the tensor has fewer than 2^31 elements
-            const int umax = a.fwd_mode ? a.M - 1 - m0 : a.R - 1 - r0;
-            const unsigned eu = eb + static_cast<unsigned>(max(0, min(rp_u[k], umax))) * static_cast<unsigned>(a.su);
-            return ((eu * 2u) & ~3u) + 16u * static_cast<unsigned>(rp_q[k]);
+            unsigned run = rp_run[k];
+            if (!a.fwd_mode) {  // the runs are channels: those beyond R (last chunk) repeat the last one
+                const int r0 = cc * a.NGW * 8;
+                if (r0 + 8 * a.NGW > a.R) run = static_cast<unsigned>(max(0, min(rp_u[k], a.R - 1 - r0))) * static_cast<unsigned>(a.su);
+            }
+            return (((chunk_base(cc) + run) & ~1u) << 1) + rp_q16[k];
         };
-        // Every path issues the same loads (chunks past the end repeat the last one, the last pieces of the tensor
-        // are loaded from a clamped address and shifted when they are parked), so that the compiler can count the
-        // loads in flight instead of waiting for all of them.
+        // The first kDepth requests are issued on every path (chunks past the end repeat the last one), and the last
+        // pieces of the tensor are loaded from a clamped address and shifted when they are parked.
         auto raw_prefetch = [&](int cc_, u32x4 (&rr)[kMaxRP]) {
             const int cc = min(cc_, nchunks - 1);
             const char* wb = reinterpret_cast<const char*>(a.wt);
@@ -244,54 +332,99 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
         };
         auto raw_commit = [&](int cc, const u32x4 (&rr)[kMaxRP]) {
             u32x4* raw = lds4 + a.wres_slots + (cc & 1) * a.raw_slots;
+            // does any piece of this chunk reach into the last 16 bytes of the tensor?  (an upper bound, uniform)
+            const unsigned top = static_cast<unsigned>(a.fwd_mode ? min(a.NU - 1, a.M - 1 - m0) : a.NU - 1) * static_cast<unsigned>(a.su);
+            const bool tail = ((chunk_base(cc) + top) << 1) + 16u * static_cast<unsigned>(a.NPc - 1) > last_piece;
 #pragma unroll
             for (int k = 0; k < kMaxRP; ++k)
                 if (tid + k * 512 < NRP) {
-                    const unsigned B = piece_offset(cc, k);
-                    const unsigned sh = B > last_piece ? (B - last_piece) >> 2 : 0u;  // dwords the clamped load started early
                     u32x4 v = rr[k];
-                    v[0] = sh == 0 ? v[0] : (sh == 1 ? v[1] : (sh == 2 ? v[2] : v[3]));
-                    v[1] = sh == 0 ? v[1] : (sh == 1 ? v[2] : v[3]);
-                    v[2] = sh == 0 ? v[2] : v[3];
-                    raw[rp_u[k] * a.NPc + rp_q[k]] = v;
+                    if (tail) {
+                        const unsigned B = piece_offset(cc, k);
+                        const unsigned sh = B > last_piece ? (B - last_piece) >> 2 : 0u;  // dwords the clamped load started early
+                        v[0] = sh == 0 ? v[0] : (sh == 1 ? v[1] : (sh == 2 ? v[2] : v[3]));
+                        v[1] = sh == 0 ? v[1] : (sh == 1 ? v[2] : v[3]);
+                        v[2] = sh == 0 ? v[2] : v[3];
+                    }
+                    raw[tid + k * 512] = v;
                 }
         };
+        // entry k of the thread (filter ml of the group, plane g of the chunk, tap sx): byte offsets, within a raw
+        // buffer, of its channels 0 (and 2, 4, 6: + j cs2) and 1 (3, 5, 7); 16-byte slot within the chunk's entries.
+        // A run that starts at an odd element was fetched from the dword before it and lies one halfword further on.
+        int wi_be[kMaxWI], wi_bo[kMaxWI], wi_lds[kMaxWI], wi_g8[kMaxWI], wi_ml[kMaxWI];
+        auto entry_tables = [&]() {
+#pragma unroll
+            for (int k = 0; k < kMaxWI; ++k) {
+                const int e = min(tid + k * 512, NWI - 1);
+                const int mg = fast_div(e, a.dv_s), sx = e - mg * a.S;
+                const int ml = fast_div(mg, a.dv_ngw), g = mg - ml * a.NGW;
+                if (a.fwd_mode) {
+                    const int idx0 = ml * RSH + 8 * g * a.S + sx;
+                    const int pm = static_cast<int>((ml * a.w_sm) & 1);
+                    wi_be[k] = 2 * (idx0 + pm);
+                    wi_bo[k] = 2 * (idx0 + pm) + cs2;
+                } else {
+                    const int idx0 = 8 * g * RSH + ml * a.S + (a.S - 1 - sx);
+                    wi_be[k] = 2 * idx0;
+                    wi_bo[k] = 2 * (idx0 + static_cast<int>(a.w_sr & 1)) + cs2;  // runs of odd channels start at the other parity
+                }
+                wi_lds[k] = ((g * JT + (sx >> 2)) * FB + (ml >> 4)) * kQS + 17 * (sx & 3) + (ml & 15);
+                wi_g8[k] = 8 * g;
+                wi_ml[k] = ml;
+            }
+        };
+        // channels beyond R or filters beyond M anywhere in the launch?  (else no entry needs a mask)
+        const bool wmask = a.ncc * a.NG * 8 != a.R || a.nfg * FB * 16 != a.M;
         auto gather = [&](int cc) {
-            const unsigned short* raw = reinterpret_cast<const unsigned short*>(lds4 + a.wres_slots + (cc & 1) * a.raw_slots);
+            const char* raw = reinterpret_cast<const char*>(lds4 + a.wres_slots + (cc & 1) * a.raw_slots);
             u32x4* wgt = lds4 + cc * (a.NGW * JT * FB * kQS);
-            const int pb = static_cast<int>(chunk_base(cc) & 1);
             const int r0 = cc * a.NGW * 8;
             unsigned v[kMaxWI][8];
 #pragma unroll
             for (int k = 0; k < kMaxWI; ++k)
                 if (k * 512 < NWI) {
-                    const int ie = wi_idx0[k] + (pb ^ (wi_par[k] & 1)), io = wi_idx0[k] + (pb ^ (wi_par[k] >> 1));
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) v[k][j] = raw[((j & 1) ? io : ie) + j * cs];
+                    for (int j = 0; j < 8; j += 2) {
+                        v[k][j] = *reinterpret_cast<const unsigned short*>(raw + wi_be[k] + j * cs2);
+                        v[k][j + 1] = *reinterpret_cast<const unsigned short*>(raw + wi_bo[k] + j * cs2);
+                    }
                 }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int k = 0; k < kMaxWI; ++k)
                 if (tid + k * 512 < NWI) {
-                    const int nv = m0 + wi_ml[k] < a.M ? a.R - r0 - wi_g8[k] : 0;  // channels that exist
+                    if (wmask) {
+                        const int nv = m0 + wi_ml[k] < a.M ? a.R - r0 - wi_g8[k] : 0;  // channels that exist
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) v[k][j] = j < nv ? v[k][j] : 0u;
+                        for (int j = 0; j < 8; ++j) v[k][j] = j < nv ? v[k][j] : 0u;
+                    }
                     wgt[wi_lds[k]] = u32x4{v[k][0] | (v[k][1] << 16), v[k][2] | (v[k][3] << 16), v[k][4] | (v[k][5] << 16), v[k][6] | (v[k][7] << 16)};
                 }
         };
-        // chunk cc travels in register set cc % kDepth and raw buffer cc & 1; its loads are issued kDepth chunks
-        // ahead, so that only the first chunks wait for memory
+        // Chunk cc travels in register set cc % kDepth and raw buffer cc & 1; its loads are issued kDepth chunks
+        // ahead, so that only the first chunks wait for memory.  The first loads leave before anything else is
+        // set up: the weights first, then (producer waves) the window of the first stage, and the tables of the
+        // gather and the zeroes are written while they are in flight.
 #pragma unroll
         for (int i = 0; i < kDepth; ++i) raw_prefetch(i, rreg[i]);
+        if (!consumer) {
+            __builtin_amdgcn_s_setprio(3);
+            window_prefetch(std::integral_constant<int, kMaxWT>{}, g0, wreg[0]);
+        }
+        for (int e = tid; e < a.wres_slots; e += 512) lds4[e] = u32x4{0u, 0u, 0u, 0u};
+        entry_tables();
         __syncthreads();  // the zeroes are in place
         for (int c0 = 0; c0 < nchunks; c0 += kDepth) {
 #pragma unroll
             for (int i = 0; i < kDepth; ++i) {
                 const int cc = c0 + i;
-                if (cc < nchunks) raw_commit(cc, rreg[i]);
-                __syncthreads();
-                if (cc < nchunks) gather(cc);
-                raw_prefetch(cc + kDepth, rreg[i]);
+                if (cc < nchunks) {  // uniform
+                    raw_commit(cc, rreg[i]);
+                    __syncthreads();
+                    gather(cc);
+                    if (cc + kDepth < nchunks) raw_prefetch(cc + kDepth, rreg[i]);
+                }
             }
         }
         __syncthreads();
@@ -309,18 +442,53 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
         auto ld = [&](unsigned off) { return as_bf16x8(*reinterpret_cast<const u32x4*>(ldsb + off)); };
         f32x4 acc[FB][kT];
         bf16x8 W[FB][JT];
+        // The bias of the lane's filters, loaded once: a load where a tile completes would wait, with the counter
+        // the vector memory instructions share, for every output store still in flight.
+        float bm[FB];
 #pragma unroll
         for (int fb = 0; fb < FB; ++fb) {
+            const int m = (fg * FB + fb) * 16 + li;
+            bm[fb] = m < a.M ? epi_bias(a.epi, m) : 0.f;
+        }
+        const bool plain = a.epi.bias == nullptr && !a.epi.relu;
+        const long rowblk = 16L * a.Wout;
+        const int mlim = a.M - fg * FB * 16 - li;  // filter block fb of this lane exists if 16 fb < mlim
+        auto store_unit = [&](int fb, int t, const f32x4& v, long idx0, int o) {  // v: after the epilogue
+            if (16 * fb < mlim) {
+                const long idx = idx0 + fb * rowblk + 16 * t;
+                if (a.vec_out && o + 16 * t + 3 < a.Wout) {
+                    epi_store4(a.epi, a.out, idx, v);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (o + 16 * t + i < a.Wout) epi_store(a.epi, a.out, idx + i, v[i]);
+                }
+            }
+        };
+        // aligned rows only; with bfloat16 output the first two registers already hold the 8 bytes
+        auto store_unit_vec = [&](int fb, int t, const f32x4& v, long idx0, int o) {
+            if (16 * fb < mlim && o + 16 * t < a.Wout) {
+                const long idx = idx0 + fb * rowblk + 16 * t;
+                if (a.epi.out_bf16) {
+                    *reinterpret_cast<f32x2*>(reinterpret_cast<__bf16*>(a.out) + idx) = f32x2{v[0], v[1]};
+                } else {
+                    *reinterpret_cast<f32x4*>(a.out + idx) = v;
+                }
+            }
+        };
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
             for (int t = 0; t < kT; ++t) acc[fb][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int jj = 0; jj < JT; ++jj) W[fb][jj] = ld(wlane + 16u * static_cast<unsigned>((jj * FB + fb) * kQS));
-        }
         unsigned wnext = wlane + plane_bytes;  // entries of the plane after the current one
         if (wnext >= wlane + wres_bytes) wnext = wlane;
 
         int tile = t_begin, cc = 0;
-        __syncthreads();  // stage 0 is in LDS
+        __syncthreads();  // the weight entries and stage 0 are in LDS
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+            for (int jj = 0; jj < JT; ++jj) W[fb][jj] = ld(wlane + 16u * static_cast<unsigned>((jj * FB + fb) * kQS));
         for (int st = 0; st < nstages; ++st) {
             const unsigned sb = xlane + 16u * static_cast<unsigned>((st & 1) * a.win_slots);
             for (int g = 0; g < a.NG; ++g) {
@@ -362,28 +530,42 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
                 // the tile is complete.  The MFMA operands are swapped (A = input slots, B = weights), so lane
                 // (li, kb) holds filter li of each block at the 4 adjacent columns 4 kb .. 4 kb + 3 of each position block
                 const int ct = tile;
-                const int n = ct / a.tiles_per_row;
+                const int n = fast_div(ct, a.dv_tpr);
                 const int o = (ct - n * a.tiles_per_row) * kTW + cw * (kT * 16) + 4 * kb;
-                const long base = static_cast<long>(n) * a.out_sn;
+                const long idx0 = static_cast<long>(n) * a.out_sn + static_cast<long>(fg * FB * 16 + li) * a.Wout + o;
+                // Every choice below is uniform for the launch and is taken once for the whole tile, not per row
+                // segment (this code runs between two stages, with the MFMAs idle); each step works in place on
+                // the accumulators.
+                auto finish = [&](f32x4 (&fin)[FB][kT]) {
+                    if (!plain) {
 #pragma unroll
-                for (int fb = 0; fb < FB; ++fb) {
-                    const int m = (fg * FB + fb) * 16 + li;
-                    if (m < a.M) {
-                        const long row = base + static_cast<long>(m) * a.Wout + o;
-                        const float bm = epi_bias(a.epi, m);
+                        for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
-                        for (int t = 0; t < kT; ++t) {
-                            const f32x4 v = epi_apply4(a.epi, acc[fb][t], bm);
-                            if (a.vec_out && o + 16 * t + 3 < a.Wout) {
-                                epi_store4(a.epi, a.out, row + 16 * t, v);
-                            } else {
-#pragma unroll
-                                for (int i = 0; i < 4; ++i)
-                                    if (o + 16 * t + i < a.Wout) epi_store(a.epi, a.out, row + 16 * t + i, v[i]);
-                            }
-                        }
+                            for (int t = 0; t < kT; ++t) fin[fb][t] = epi_apply4(a.epi, fin[fb][t], bm[fb]);
                     }
-                }
+                    if (!a.vec_out) {  // rows that are not 16-byte aligned: element by element, here
+#pragma unroll
+                        for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+                            for (int t = 0; t < kT; ++t) store_unit(fb, t, fin[fb][t], idx0, o);
+                    } else {
+                        if (a.epi.out_bf16) {  // 4 bfloat16 in the first two registers
+#pragma unroll
+                            for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+                                for (int t = 0; t < kT; ++t) {
+                                    const f32x2 h = __builtin_bit_cast(f32x2, __builtin_convertvector(fin[fb][t], epi_bf16x4));
+                                    fin[fb][t][0] = h[0];
+                                    fin[fb][t][1] = h[1];
+                                }
+                        }
+#pragma unroll
+                        for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+                            for (int t = 0; t < kT; ++t) store_unit_vec(fb, t, fin[fb][t], idx0, o);
+                    }
+                };
+                finish(acc);
 #pragma unroll
                 for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
@@ -401,11 +583,12 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
         // count.
         auto run = [&](auto nt_) {
             const int last = nstages - 1;
+            // (a wave can have 63 loads in flight: the second window is requested only now, with the weights in LDS)
             window_prefetch(nt_, g1, wreg[1]);
             window_commit(g0, 0, wreg[0]);
+            __syncthreads();  // the consumers start on stage 0
             g2 = geo(min(2, last));
             window_prefetch(nt_, g2, wreg[0]);
-            __syncthreads();
             // invariant at the top of iteration st: g1 = stage st + 1 (in set 1), g2 = stage st + 2 (in set 0)
             int st = 0;
             for (; st + 4 <= last; st += 2) {  // the steady state: no branch around a load
@@ -464,6 +647,9 @@ hipError_t rg_launch_dk(const RgPlan& pl, hipStream_t st) {
         case 209: return rg_launch<D, 2, 9, KT>(pl, st);
         case 105: return rg_launch<D, 1, 5, KT>(pl, st);
         case 205: return rg_launch<D, 2, 5, KT>(pl, st);
+        // (four filter blocks only with the narrow tile: with 8 position blocks the accumulators alone take 128 registers)
+        case 403: if constexpr (KT == 5) return rg_launch<D, 4, 3, KT>(pl, st); else return hipErrorInvalidValue;
+        case 402: if constexpr (KT == 5) return rg_launch<D, 4, 2, KT>(pl, st); else return hipErrorInvalidValue;
         case 103: return rg_launch<D, 1, 3, KT>(pl, st);
         case 203: return rg_launch<D, 2, 3, KT>(pl, st);
         case 102: return rg_launch<D, 1, 2, KT>(pl, st);

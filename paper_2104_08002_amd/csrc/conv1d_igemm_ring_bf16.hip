@@ -44,7 +44,9 @@ RgPlan rg_plan_kt(const CorrProblem& p, int kT) {
     const long LP = (kTW + halo + a.delta + 1) / 2 * 2;
     const long LPS = LP + 8;
     const int planes = cdiv(p.R, 8);
-    for (int FB = p.M > 16 ? 2 : 1; FB >= 1; --FB) {
+    // Four filter blocks per workgroup with few taps: the window of a tile is then staged once for 64 filters, and
+    // staging, not the MFMAs, is what a stage with few taps waits for.
+    for (int FB = (p.M > 32 && JT <= 3 && kT == 5) ? 4 : (p.M > 16 ? 2 : 1); FB >= 1; FB /= 2) {
         // one filter block per workgroup pays off only with many taps per input operand (measured: C = K = 256,
         // S = 9 ran 1.4 times slower than the staged kernel with its two filter blocks)
         if (FB == 1 && p.M > 16 && JT < 5) break;
@@ -55,21 +57,30 @@ RgPlan rg_plan_kt(const CorrProblem& p, int kT) {
             const long win = NG * LPS;
             if (cdiv(NG * (LP / 2), 256) > kMaxWT) continue;
             // the prologue gathers the weights in chunks of NGW planes: as many as its per-thread task lists hold
+            // (all planes at once where the lists and the LDS allow it: every chunk costs a barrier and a round
+            // trip through LDS).  The two raw buffers of the prologue lie where the two window buffers will be.
             int NGW = 0, NU = 0;
             long NPc = 0;
-            for (int w = NG; w >= 1 && NGW == 0; w /= 2) {
+            size_t bytes = 0;
+            // few weights: the direct prologue (no raw buffers)
+            const long NE = static_cast<long>(FB) * 16 * ncc * NG * p.S;
+            const bool direct = NE <= 512L * rg::kMaxDE && static_cast<size_t>(wres + 2 * win) * 16 <= static_cast<size_t>(kLdsBudget);
+            if (direct) {
+                NGW = NG; NU = 1; NPc = 1; bytes = static_cast<size_t>(wres + 2 * win) * 16;
+            }
+            for (int w = ncc * NG; w >= 1 && NGW == 0; --w) {
+                if ((ncc * NG) % w != 0) continue;  // whole chunks
                 if (cdiv(static_cast<long>(FB) * 16 * w * p.S, 512) > kMaxWI) continue;
-                NU = fwd_mode ? FB * 16 : 8 * w;
+                const int nu = fwd_mode ? FB * 16 : 8 * w;
                 const long L = fwd_mode ? 8L * w * p.S : static_cast<long>(FB) * 16 * p.S;
-                NPc = (2 * L + 2 + 15) / 16;
-                if (cdiv(NU * NPc, 512) > kMaxRP) continue;
-                NGW = w;
+                const long npc = (2 * L + 2 + 15) / 16;
+                if (cdiv(nu * npc, 512) > kMaxRP) continue;
+                const long behind = 2 * win > 2 * nu * npc ? 2 * win : 2 * nu * npc;
+                const size_t need = static_cast<size_t>(wres + behind) * 16;
+                if (need > static_cast<size_t>(kLdsBudget)) continue;
+                NGW = w; NU = nu; NPc = npc; bytes = need;
             }
             if (NGW == 0) continue;
-            // the two raw buffers of the prologue lie where the two window buffers will be
-            const long behind = 2 * win > 2 * NU * NPc ? 2 * win : 2 * NU * NPc;
-            const size_t bytes = static_cast<size_t>(wres + behind) * 16;
-            if (bytes > static_cast<size_t>(kLdsBudget)) continue;
             pl.D = p.d; pl.FB = FB; pl.JT = JT; pl.KT = kT;
             a.NG = NG;
             a.NGW = NGW;
@@ -79,6 +90,7 @@ RgPlan rg_plan_kt(const CorrProblem& p, int kT) {
             a.win_slots = static_cast<int>(win);
             a.wres_slots = static_cast<int>(wres);
             a.fwd_mode = fwd_mode;
+            a.direct = direct ? 1 : 0;
             a.NU = NU;
             a.NPc = static_cast<int>(NPc);
             a.raw_slots = static_cast<int>(NU * NPc);
@@ -92,6 +104,23 @@ RgPlan rg_plan_kt(const CorrProblem& p, int kT) {
             a.nct = static_cast<int>(nct);
             const int fit = kNumCU / a.nfg > 0 ? kNumCU / a.nfg : 1;  // teams that run at the same time
             a.nteams = a.nct < fit ? a.nct : fit;
+            a.t_base = a.nct / a.nteams;
+            a.t_rem = a.nct % a.nteams;
+            {
+                // the divisions of the kernel, and the largest number each of them divides
+                const long max_stages = static_cast<long>(a.t_base + 1) * ncc;
+                const long NWI = static_cast<long>(FB) * 16 * NGW * p.S;
+                bool ok = make_fastdiv(a.dv_nfg, a.nfg, static_cast<long>(a.nteams) * a.nfg);
+                ok = make_fastdiv(a.dv_tpr, a.tiles_per_row, nct) && ok;
+                ok = make_fastdiv(a.dv_ncc, ncc, max_stages + 4) && ok;
+                ok = make_fastdiv(a.dv_lp2, LP / 2, 256L * kMaxWT + static_cast<long>(NG) * (LP / 2)) && ok;
+                ok = make_fastdiv(a.dv_npc, NPc, 512L * kMaxRP + NU * NPc) && ok;
+                ok = make_fastdiv(a.dv_s, p.S, 512L * kMaxWI + NWI) && ok;
+                ok = make_fastdiv(a.dv_ngw, NGW, (512L * kMaxWI + NWI) / p.S + 1) && ok;
+                ok = make_fastdiv(a.dv_pl, ncc * NG, (512L * rg::kMaxDE + NE) / p.S + 1) && ok;
+                ok = make_fastdiv(a.dv_s, p.S, 512L * (kMaxWI > rg::kMaxDE ? kMaxWI : rg::kMaxDE) + NWI + NE) && ok;
+                if (!ok) return pl;
+            }
             pl.grid = a.nteams * a.nfg;
             pl.lds_bytes = bytes;
             pl.ok = true;
@@ -102,13 +131,14 @@ RgPlan rg_plan_kt(const CorrProblem& p, int kT) {
 }
 
 // Tile width: 8 position blocks per wave, or 5 when that spreads the tiles more evenly over the workgroups (a
-// workgroup walks whole tiles; 2.5 tiles per workgroup cost as much as 3).
+// workgroup walks whole tiles; 2.5 tiles per workgroup cost as much as 3), or when only the narrow tile leaves
+// room for four filter blocks.
 RgPlan rg_plan(const CorrProblem& p) {
     RgPlan best = rg_plan_kt(p, 8);
     if (best.ok) {
         const RgPlan alt = rg_plan_kt(p, 5);
         auto makespan = [](const RgPlan& pl) { return static_cast<long>(cdiv(pl.a.nct, pl.a.nteams)) * (2 * pl.KT + 1); };
-        if (alt.ok && alt.FB == best.FB && makespan(alt) * 10 < makespan(best) * 9) best = alt;
+        if (alt.ok && (alt.FB > best.FB || (alt.FB == best.FB && makespan(alt) * 10 < makespan(best) * 9))) best = alt;
     }
     return best;
 }

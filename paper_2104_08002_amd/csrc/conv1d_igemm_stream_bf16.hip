@@ -104,6 +104,14 @@ __global__ __launch_bounds__(512, 2) void igemm_stream_bf16_kernel(SgArgs a) {
         for (int fb = 0; fb < kFB; ++fb)
 #pragma unroll
             for (int t = 0; t < kT; ++t) acc[fb][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // The bias of the lane's filters, loaded once: a load where a tile completes would wait, with the counter
+        // the vector memory instructions share, for every output store still in flight.
+        float bm[kFB];
+#pragma unroll
+        for (int fb = 0; fb < kFB; ++fb) {
+            const int m = (fg * kFB + fb) * 16 + li;
+            bm[fb] = m < a.M ? epi_bias(a.epi, m) : 0.f;
+        }
 
         int tile = t_begin, cc = 0;
         __syncthreads();  // raw weights of stage 0 are in LDS
@@ -149,10 +157,9 @@ __global__ __launch_bounds__(512, 2) void igemm_stream_bf16_kernel(SgArgs a) {
                     const int m = (fg * kFB + fb) * 16 + li;
                     if (m < a.M) {
                         const long row = base + static_cast<long>(m) * a.Wout + o;
-                        const float bm = epi_bias(a.epi, m);
 #pragma unroll
                         for (int t = 0; t < kT; ++t) {
-                            const f32x4 v = epi_apply4(a.epi, acc[fb][t], bm);
+                            const f32x4 v = epi_apply4(a.epi, acc[fb][t], bm[fb]);
                             if (a.vec_out && o + 16 * t + 3 < a.Wout) {
                                 epi_store4(a.epi, a.out, row + 16 * t, v);
                             } else {

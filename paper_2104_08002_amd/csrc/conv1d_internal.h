@@ -237,6 +237,27 @@ __device__ __forceinline__ int xcd_logical_id(int b, int grid) {
 
 inline int cdiv(long a, long b) { return static_cast<int>((a + b - 1) / b); }
 
+// Division of a small non-negative number by a divisor fixed for the launch: one multiply-high instead of the
+// several dozen instructions of a 32-bit division.  With m = ceil(2^32 / d) the quotient umulhi(n, m) is exact
+// while n * (m * d - 2^32) < 2^32; the host checks that for the largest n the kernel will divide.
+struct FastDiv {
+    unsigned d, m;
+};
+inline bool make_fastdiv(FastDiv& f, long d, long nmax) {
+    if (d < 1 || d >= (1L << 31) || nmax < 0 || nmax >= (1L << 31)) return false;
+    f.d = static_cast<unsigned>(d);
+    if (d == 1) {
+        f.m = 0;
+        return true;
+    }
+    const unsigned long m = ((1UL << 32) + d - 1) / d;
+    f.m = static_cast<unsigned>(m);
+    return static_cast<unsigned long>(nmax) * (m * d - (1UL << 32)) < (1UL << 32);
+}
+__device__ __forceinline__ int fast_div(int n, const FastDiv& f) {
+    return f.d == 1 ? n : static_cast<int>(__umulhi(static_cast<unsigned>(n), f.m));
+}
+
 // ---- host helpers: launches ---------------------------------------------------------------------
 // Raise a kernel's dynamic LDS limit to `bytes` on the current GPU.  The runtime call costs microseconds, so the
 // largest size granted so far is remembered per (kernel, GPU) and the call is made only when it has to grow.

@@ -53,6 +53,7 @@ inline void __syncthreads() {}
 inline float __uint_as_float(unsigned u) { float f; std::memcpy(&f, &u, 4); return f; }
 inline unsigned __float_as_uint(float f) { unsigned u; std::memcpy(&u, &f, 4); return u; }
 inline float __shfl_down(float v, int, int) { return v; }
+inline unsigned __umulhi(unsigned a, unsigned b) { return static_cast<unsigned>((static_cast<unsigned long long>(a) * b) >> 32); }
 inline int min(int a, int b) { return a < b ? a : b; }
 inline int max(int a, int b) { return a > b ? a : b; }
 inline unsigned min(unsigned a, unsigned b) { return a < b ? a : b; }
@@ -81,6 +82,26 @@ inline unsigned hostmodel_alignbit(unsigned hi, unsigned lo, unsigned sh) {
     return static_cast<unsigned>(((static_cast<uint64_t>(hi) << 32) | lo) >> (sh & 31));
 }
 #define __builtin_amdgcn_alignbit(a, b, s) hostmodel_alignbit(a, b, s)
+
+// raw buffer loads: the descriptor is the base address, the load an ordinary (guard-checked) read
+struct hostmodel_rsrc {
+    const char* base;
+};
+#define __amdgpu_buffer_rsrc_t hostmodel_rsrc
+inline hostmodel_rsrc hostmodel_make_rsrc(const void* p) { return hostmodel_rsrc{static_cast<const char*>(p)}; }
+#define __builtin_amdgcn_make_buffer_rsrc(p, stride, num, flags) hostmodel_make_rsrc(p)
+inline unsigned hostmodel_buffer_load_b32(hostmodel_rsrc r, int voff, int soff) {
+    unsigned v;
+    std::memcpy(&v, r.base + static_cast<long>(voff) + static_cast<long>(soff), 4);
+    return v;
+}
+#define __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, aux) hostmodel_buffer_load_b32(r, voff, soff)
+inline unsigned short hostmodel_buffer_load_b16(hostmodel_rsrc r, int voff, int soff) {
+    unsigned short v;
+    std::memcpy(&v, r.base + static_cast<long>(static_cast<unsigned>(voff)) + static_cast<long>(soff), 2);
+    return v;
+}
+#define __builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, aux) hostmodel_buffer_load_b16(r, voff, soff)
 
 // launch_kernel() in conv1d_internal.h calls this instead of hipLaunchKernel when HOSTMODEL is defined
 template <typename... Params, typename... Args>
