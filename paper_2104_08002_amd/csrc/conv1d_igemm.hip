@@ -148,14 +148,18 @@ hipError_t igemm_corr_launch(const CorrProblem& p, hipStream_t st) {
     return hipSuccess;
 }
 
+// the register-shift kernel where the others would stage several phase copies of x for a handful of taps
+static bool prefer_shift_wgrad(const WgradProblem& p) { return p.bf16 && shift_bf16_wgrad_supported(p); }
+
 bool igemm_wgrad_supported(const WgradProblem& p) {
-    if (p.bf16 && (toeplitz_bf16_wgrad_supported(p) || blocked_bf16_wgrad_supported(p))) return true;
+    if (p.bf16 && (shift_bf16_wgrad_supported(p) || toeplitz_bf16_wgrad_supported(p) || blocked_bf16_wgrad_supported(p))) return true;
     if (p.C <= kBlock && p.K <= kBlock) return false;
     return smallc_wgrad_supported(wgrad_block(p, 0, 0));
 }
 
 size_t igemm_wgrad_workspace(const WgradProblem& p) {
     if (!igemm_wgrad_supported(p)) return 0;
+    if (prefer_shift_wgrad(p)) return shift_bf16_wgrad_workspace(p);
     if (p.bf16 && toeplitz_bf16_wgrad_supported(p)) return toeplitz_bf16_wgrad_workspace(p);
     if (p.bf16 && blocked_bf16_wgrad_supported(p)) return blocked_bf16_wgrad_workspace(p);
     if (fp32_pairs_in_one_launch(p)) return smallc_wgrad_f32_blocks_workspace(p);
@@ -164,6 +168,7 @@ size_t igemm_wgrad_workspace(const WgradProblem& p) {
 
 hipError_t igemm_wgrad_launch(const WgradProblem& p, hipStream_t st) {
     if (!igemm_wgrad_supported(p)) return hipErrorInvalidValue;
+    if (prefer_shift_wgrad(p)) return shift_bf16_wgrad_launch(p, st);
     if (p.bf16 && toeplitz_bf16_wgrad_supported(p)) return toeplitz_bf16_wgrad_launch(p, st);
     if (p.bf16 && blocked_bf16_wgrad_supported(p)) return blocked_bf16_wgrad_launch(p, st);
     if (fp32_pairs_in_one_launch(p)) return smallc_wgrad_f32_blocks_launch(p, st);

@@ -122,6 +122,12 @@ bool toeplitz_bf16_wgrad_supported(const WgradProblem& p);
 size_t toeplitz_bf16_wgrad_workspace(const WgradProblem& p);
 hipError_t toeplitz_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st);
 
+// bf16 backward-weight for dilations 1, 2 and few taps ((S - 1) d <= 16): x is staged once and the tap shift is
+// applied in registers
+bool shift_bf16_wgrad_supported(const WgradProblem& p);
+size_t shift_bf16_wgrad_workspace(const WgradProblem& p);
+hipError_t shift_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st);
+
 // bf16 forward / backward-data for many channels: implicit GEMM over (channel chunk, tap) with the weights
 // gathered into LDS stage by stage
 bool igemm_bf16_corr_supported(const CorrProblem& p);
@@ -193,6 +199,55 @@ __device__ __forceinline__ void epi_store4(const Epilogue& e, float* out, long i
         *reinterpret_cast<epi_f32x4*>(out + idx) = v;
     }
 }
+
+// ---- staging helpers of the bf16 backward-weight kernels: 16-byte pieces of a row, clamped at its ends ----------
+typedef __attribute__((ext_vector_type(4))) unsigned int stage_u32x4;
+
+__device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+// v holds the 8 elements of a row of `limit` >= 8 columns from column clamp(c, 0, limit - 8) on; returns the
+// elements of columns c .. c+7, zero outside the row.
+__device__ __forceinline__ stage_u32x4 fix128(stage_u32x4 v, int c, int limit) {
+    const int sh = c - clampi(c, 0, limit - 8);
+    if (sh == 0) return v;
+    if (sh >= 8 || sh <= -8) return stage_u32x4{0u, 0u, 0u, 0u};
+    unsigned long lo = v.x | (static_cast<unsigned long>(v.y) << 32), hi = v.z | (static_cast<unsigned long>(v.w) << 32);
+    if (sh > 0) {  // the row ends inside the slot: drop the low elements, zeros come in at the top
+        const int s = 16 * sh;
+        if (s < 64) {
+            lo = (lo >> s) | (hi << (64 - s));
+            hi >>= s;
+        } else {
+            lo = hi >> (s - 64);
+            hi = 0;
+        }
+    } else {  // the row starts inside the slot
+        const int s = -16 * sh;
+        if (s < 64) {
+            hi = (hi << s) | (lo >> (64 - s));
+            lo <<= s;
+        } else {
+            hi = lo << (s - 64);
+            lo = 0;
+        }
+    }
+    return stage_u32x4{static_cast<unsigned>(lo), static_cast<unsigned>(lo >> 32), static_cast<unsigned>(hi), static_cast<unsigned>(hi >> 32)};
+}
+
+// 16-byte load of the columns clamp(c, 0, limit - 8) .. + 7 of the row at `row` (c even, row 4-byte aligned)
+__device__ __forceinline__ stage_u32x4 load128_clamped(const unsigned short* row, int c, int limit) {
+    return *reinterpret_cast<const stage_u32x4*>(row + clampi(c, 0, limit - 8));
+}
+// the element pair at the even column c, zero outside the row (limit even)
+__device__ __forceinline__ unsigned load_pair(const unsigned short* row, int c, int limit) {
+    const unsigned v = *reinterpret_cast<const unsigned*>(row + clampi(c, 0, limit - 2));
+    return (c >= 0 && c < limit) ? v : 0u;
+}
+__device__ __forceinline__ stage_u32x4 shift_one(stage_u32x4 v, unsigned next) {
+    return stage_u32x4{__builtin_amdgcn_alignbit(v.y, v.x, 16), __builtin_amdgcn_alignbit(v.z, v.y, 16), __builtin_amdgcn_alignbit(v.w, v.z, 16),
+                 __builtin_amdgcn_alignbit(next, v.w, 16)};
+}
+
 
 // ---- second stage of the small-channel backward-weight kernels ------------------------------------------------
 // Work of "block" b (b < 4*S) of 512 threads on 64 consecutive elements of the S*256 partial tile: thread

@@ -45,51 +45,6 @@ constexpr int kMaxI = 12;  // most x load items (slot, even phase base) per prod
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-__device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
-
-// v holds the 8 elements of a row of `limit` >= 8 columns from column clamp(c, 0, limit - 8) on; returns the
-// elements of columns c .. c+7, zero outside the row.
-__device__ __forceinline__ u32x4 fix128(u32x4 v, int c, int limit) {
-    const int sh = c - clampi(c, 0, limit - 8);
-    if (sh == 0) return v;
-    if (sh >= 8 || sh <= -8) return u32x4{0u, 0u, 0u, 0u};
-    unsigned long lo = v.x | (static_cast<unsigned long>(v.y) << 32), hi = v.z | (static_cast<unsigned long>(v.w) << 32);
-    if (sh > 0) {  // the row ends inside the slot: drop the low elements, zeros come in at the top
-        const int s = 16 * sh;
-        if (s < 64) {
-            lo = (lo >> s) | (hi << (64 - s));
-            hi >>= s;
-        } else {
-            lo = hi >> (s - 64);
-            hi = 0;
-        }
-    } else {  // the row starts inside the slot
-        const int s = -16 * sh;
-        if (s < 64) {
-            hi = (hi << s) | (lo >> (64 - s));
-            lo <<= s;
-        } else {
-            hi = lo << (s - 64);
-            lo = 0;
-        }
-    }
-    return u32x4{static_cast<unsigned>(lo), static_cast<unsigned>(lo >> 32), static_cast<unsigned>(hi), static_cast<unsigned>(hi >> 32)};
-}
-
-// 16-byte load of the columns clamp(c, 0, limit - 8) .. + 7 of the row at `row` (c even, row 4-byte aligned)
-__device__ __forceinline__ u32x4 load128_clamped(const unsigned short* row, int c, int limit) {
-    return *reinterpret_cast<const u32x4*>(row + clampi(c, 0, limit - 8));
-}
-// the element pair at the even column c, zero outside the row (limit even)
-__device__ __forceinline__ unsigned load_pair(const unsigned short* row, int c, int limit) {
-    const unsigned v = *reinterpret_cast<const unsigned*>(row + clampi(c, 0, limit - 2));
-    return (c >= 0 && c < limit) ? v : 0u;
-}
-__device__ __forceinline__ u32x4 shift_one(u32x4 v, unsigned next) {
-    return u32x4{__builtin_amdgcn_alignbit(v.y, v.x, 16), __builtin_amdgcn_alignbit(v.z, v.y, 16), __builtin_amdgcn_alignbit(v.w, v.z, 16),
-                 __builtin_amdgcn_alignbit(next, v.w, 16)};
-}
-
 // Compile-time geometry of one (dilation, taps per wave) pair.
 template <int D, int NTW>
 struct Tz {

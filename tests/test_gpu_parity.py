@@ -122,6 +122,14 @@ SMALL = [
     ("blk_short",         2, 15, 15, 64,   51, 8,  200),   # both row edges inside one window
     ("blk_P_gt_span",     2, 7,  16, 2048, 5,  8,  40),    # backward-data shift -8: window starts beyond column 0
     ("blk_one_block",     1, 16, 16, 8,    3,  8,  8),
+    # bf16 backward-weight with the tap shift applied in registers: d = 1, 2 and (S - 1) d <= 16
+    ("shift_S5_d1_odd_W", 2, 40, 24, 901,  5,  1,  2),     # odd width: element-wise staging
+    ("shift_S17_d1",      2, 64, 40, 1500, 17, 1,  8),     # three x slots per lane and k-step
+    ("shift_S2_d2",       3, 33, 17, 700,  2,  2,  1),     # odd padding: dy rows staged from odd columns
+    ("shift_S5_d2_P0",    2, 70, 64, 1000, 5,  2,  0),     # two channel groups
+    ("shift_S9_d2_big_P", 1, 64, 64, 300,  9,  2,  37),    # padding beyond the span: x slots left of the row
+    ("shift_tiny_W",      2, 20, 20, 9,    5,  1,  2),     # less than one k-step
+    ("shift_k300",        1, 24, 300, 2000, 3, 1,  1),     # many filter groups
     ("c40_halo_gt_width", 2, 40, 24, 200,  51, 8,  200),   # many channels, halo (S-1)d = 400 exceeds W
     ("c40_tiny_Q",        3, 40, 24, 420,  51, 8,  0),     # Q = 20: less than one k-step / one position block pair
 ]
