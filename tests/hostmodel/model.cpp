@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "../../include/conv1d.h"
+#include "conv1d_internal.h"  // (this file is compiled from a copy that sits beside the kernels' sources)
 
 namespace hostmodel {
 
@@ -169,4 +170,14 @@ extern "C" int hostmodel_run(int pass, int N, int C, int K, int W, int S, int d,
 
 extern "C" const char* hostmodel_kernel_name(int pass, int N, int C, int K, int W, int S, int d, int P, int dtype) {
     return conv1d_kernel_name(pass, N, C, K, W, S, d, P, dtype);
+}
+
+// The multiply-high division of the kernels against the plain one: the first n <= nmax whose quotient differs, -1 if
+// none does, -2 if make_fastdiv refuses the pair (it must refuse every pair for which the quotient could be wrong).
+extern "C" long hostmodel_fastdiv_mismatch(long d, long nmax) {
+    conv1d::FastDiv f;
+    if (!conv1d::make_fastdiv(f, d, nmax)) return -2;
+    for (long n = 0; n <= nmax; ++n)
+        if (conv1d::fast_div(static_cast<int>(n), f) != static_cast<int>(n / d)) return n;
+    return -1;
 }

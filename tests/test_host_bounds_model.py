@@ -143,3 +143,24 @@ def test_the_model_finds_a_planted_off_by_one():
     rc, msg = _run(lib, 0, geom, 1)
     assert rc == 1 and "outside x" in msg, (rc, msg)
     assert _run(_load(hostmodel_build.build()), 0, geom, 1)[0] == 0
+
+
+def test_multiply_high_division_is_exact(model):
+    """The kernels divide small indices by launch constants with one multiply-high; the host accepts a divisor only with
+    the largest dividend it was checked for.  Every accepted (divisor, bound) pair is compared with the plain quotient
+    over its whole range; pairs the host refuses are counted, not trusted."""
+    import ctypes as ct
+
+    model.hostmodel_fastdiv_mismatch.argtypes = [ct.c_long, ct.c_long]
+    model.hostmodel_fastdiv_mismatch.restype = ct.c_long
+    rng = np.random.default_rng(7)
+    divisors = list(range(1, 70)) + [95, 117, 118, 188, 255, 256, 257, 626, 641, 1000, 1023, 4097, 65535, 65537] + \
+        [int(v) for v in rng.integers(2, 200000, 40)]
+    accepted = refused = 0
+    for d in divisors:
+        for nmax in (d - 1, 5 * d + 3, 70000, 1 << 20):
+            r = model.hostmodel_fastdiv_mismatch(d, nmax)
+            assert r in (-1, -2), f"fast_div({r}, {d}) differs from {r} // {d} although the bound {nmax} was accepted"
+            accepted += r == -1
+            refused += r == -2
+    assert accepted > 300 and refused < accepted
