@@ -87,6 +87,9 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
     if (!consumer) __builtin_amdgcn_s_setprio(3);
     const int li = lane & 15;
     const int kb = lane >> 4;
+    // lane (li, kb) accumulates filter li: its sums start from that filter's bias (requested here, at the start, so
+    // that the first tile does not wait for it)
+    const float bias_li = (!p.accumulate && p.epi.bias && li < p.M) ? p.epi.bias[li] : 0.f;
     const unsigned short* __restrict__ in = static_cast<const unsigned short*>(p.in);
     const unsigned short* __restrict__ wt = static_cast<const unsigned short*>(p.wt);
     const int d = (G > 0) ? 16 / (G > 0 ? G : 1) : p.d;
@@ -419,8 +422,6 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
     __syncthreads();  // the slice entries alias the staging buffers: every wave has its copy before anyone parks
 
     // ---- consumer side: one tile's reduction, parked in LDS ------------------------------------------
-    // lane (li, kb) accumulates filter li: its sums start from that filter's bias
-    const float bias_li = (!p.accumulate && p.epi.bias && li < p.M) ? p.epi.bias[li] : 0.f;
     auto compute = [&](const u32x4* wb, float* dst) {
         f32x4 acc[T];
 #pragma unroll
