@@ -214,6 +214,17 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
             }
     };
     Geo g0 = geo(0), g1 = geo(1 < nstages ? 1 : 0), g2 = g1;
+    // The only weight entries no gather writes are those of the taps S .. 4 JT - 1 that pad the last tap groups:
+    // they must be zero (they multiply real input positions), everything else is written (masked where a channel or
+    // a filter does not exist) before it is read.
+    auto zero_padded_taps = [&]() {
+        const int nrows = a.ncc * a.NG * FB * 16;  // (plane, filter block, filter)
+        for (int t = a.S; t < 4 * JT; ++t)
+            for (int idx = tid; idx < nrows; idx += 512) {
+                const int fbg = idx >> 4, g = fbg / FB, fb = fbg - g * FB;
+                lds4[((g * JT + (t >> 2)) * FB + fb) * kQS + 17 * (t & 3) + (idx & 15)] = u32x4{0u, 0u, 0u, 0u};
+            }
+    };
 
     // ---- prologue: the workgroup's weight entries, gathered chunk by chunk (every thread helps) --------------
     // The weights of a chunk (NGW planes of 8 channels) are NU contiguous runs of the [K][C][S] tensor (forward: one run of 8 NGW channels x
@@ -274,8 +285,8 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
             __builtin_amdgcn_s_setprio(3);
             window_prefetch(std::integral_constant<int, kMaxWT>{}, g0, wreg[0]);
         }
-        for (int e = tid; e < a.wres_slots; e += 512) lds4[e] = u32x4{0u, 0u, 0u, 0u};
-        __syncthreads();  // the zeroes are in place
+        zero_padded_taps();
+        // (no barrier: the slots just zeroed are no gathered entry's)
 #pragma unroll
         for (int k = 0; k < kMaxDE; ++k)
             if (tid + k * 512 < NE) {
@@ -328,7 +339,8 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
             const int cc = min(cc_, nchunks - 1);
             const char* wb = reinterpret_cast<const char*>(a.wt);
 #pragma unroll
-            for (int k = 0; k < kMaxRP; ++k) rr[k] = *reinterpret_cast<const u32x4*>(wb + min(piece_offset(cc, k), last_piece));
+            for (int k = 0; k < kMaxRP; ++k)
+                if (k * 512 < NRP) rr[k] = *reinterpret_cast<const u32x4*>(wb + min(piece_offset(cc, k), last_piece));
         };
         auto raw_commit = [&](int cc, const u32x4 (&rr)[kMaxRP]) {
             u32x4* raw = lds4 + a.wres_slots + (cc & 1) * a.raw_slots;
@@ -356,6 +368,7 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
         auto entry_tables = [&]() {
 #pragma unroll
             for (int k = 0; k < kMaxWI; ++k) {
+                if (k * 512 >= NWI) break;  // uniform
                 const int e = min(tid + k * 512, NWI - 1);
                 const int mg = fast_div(e, a.dv_s), sx = e - mg * a.S;
                 const int ml = fast_div(mg, a.dv_ngw), g = mg - ml * a.NGW;
@@ -412,9 +425,9 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
             __builtin_amdgcn_s_setprio(3);
             window_prefetch(std::integral_constant<int, kMaxWT>{}, g0, wreg[0]);
         }
-        for (int e = tid; e < a.wres_slots; e += 512) lds4[e] = u32x4{0u, 0u, 0u, 0u};
+        zero_padded_taps();
         entry_tables();
-        __syncthreads();  // the zeroes are in place
+        // (no barrier: the slots just zeroed are no gathered entry's)
         for (int c0 = 0; c0 < nchunks; c0 += kDepth) {
 #pragma unroll
             for (int i = 0; i < kDepth; ++i) {
