@@ -33,6 +33,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 constexpr int kLdsBudget = 160 * 1024;
 constexpr int kNumCU = 256;
 constexpr int kLU = 8;  // k-steps per unit
+constexpr int kBufferRsrcFlags = 0x00020000;  // fourth dword of a raw buffer descriptor (32-bit data format, no swizzle)
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -77,7 +78,7 @@ __global__ __launch_bounds__(512, 1) void shift_wgrad_bf16_kernel(SwArgs a) {
     using G = Sw<D, SMAX>;
     constexpr int NSL = G::NSL, NXS = G::NXS, NYS = G::NYS;
     constexpr int NXT = 64 * NXS, NYT = FB * 16 * NYS;  // staging tasks (16-byte slots) per unit
-    constexpr int NT = (NXT + NYT + 255) / 256;          // per producer thread
+    constexpr int NT = (NXT + NYT + 255) / 256;          // per producer thread (one more when neither count is a multiple of 256)
     extern __shared__ u32x4 lds4[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -88,10 +89,13 @@ __global__ __launch_bounds__(512, 1) void shift_wgrad_bf16_kernel(SwArgs a) {
     const int li = lane & 15;
     const int kb = lane >> 4;
 
-    // blockIdx -> (strip, filter group, channel group); the strips of one combination are consecutive
+    // workgroup -> (strip, filter group, channel group).  The combinations of one strip read the same x and dy
+    // columns: their logical indices are consecutive, which puts them on one XCD and its L2 (the loop runs at the
+    // rate memory delivers the units, so every byte fetched twice from HBM is time).
     const int ncombos = a.nfg * a.ncg;
-    const int strip = static_cast<int>(blockIdx.x) / ncombos;
-    const int combo = static_cast<int>(blockIdx.x) - strip * ncombos;
+    const int lid = xcd_logical_id(blockIdx.x, gridDim.x);
+    const int strip = lid / ncombos;
+    const int combo = lid - strip * ncombos;
     const int fg = combo / a.ncg, cg = combo - fg * a.ncg;
     const int u_begin = strip * a.u_base + min(strip, a.u_rem);
     const int u_end = u_begin + a.u_base + (strip < a.u_rem ? 1 : 0);
@@ -172,75 +176,104 @@ __global__ __launch_bounds__(512, 1) void shift_wgrad_bf16_kernel(SwArgs a) {
             for (int s = 0; s < SMAX; ++s)
                 *reinterpret_cast<f32x4*>(tile + (((v * FB + fb) * SMAX + s) * 64 + lane) * 4) = acc[s][fb];
     } else {
-        // ---- producers: task e = rtid + 256 i is slot (e % NXS) of x row (e / NXS) or, from NXT on, a dy slot ----
-        int t_rs[NT], t_lds[NT];  // 256 row + slot (row: channel / filter of the group); LDS slot within a stage
+        // ---- producers: a thread's first NTX tasks are x slots (task e = rtid + 256 i: slot e % NXS of row e / NXS of
+        // the channel group), the other NTY are dy slots; which is which is the same for every lane ----
+        constexpr int NTX = (NXT + 255) / 256, NTY = (NYT + 255) / 256;
+        static_assert(NTX + NTY == NT || NTX + NTY == NT + 1, "task split");
+        constexpr int NTT = NTX + NTY;
+        int t_rs[NTT], t_lds[NTT];  // 256 row + slot; LDS slot within a stage
+        unsigned t_vo[NTT];         // byte offset of (row, clamped to the last real one; column 8 slot) in the sample's block
+        bool t_row_ok[NTT];
 #pragma unroll
-        for (int i = 0; i < NT; ++i) {
-            const int e = min(rtid + 256 * i, NXT + NYT - 1);
-            if (e < NXT) {
-                const int r = e / NXS, sl = e - r * NXS;
-                t_rs[i] = 256 * r + sl;
-                t_lds[i] = a.ybuf_slots + r * a.RSX + sl;
-            } else {
-                const int ey = e - NXT;
-                const int r = ey / NYS, sl = ey - r * NYS;
-                t_rs[i] = 256 * r + sl;
-                t_lds[i] = r * a.RSY + sl;
-            }
+        for (int i = 0; i < NTT; ++i) {
+            const bool is_x = i < NTX;
+            const int e = is_x ? min(rtid + 256 * i, NXT - 1) : min(rtid + 256 * (i - NTX), NYT - 1);
+            const int per = is_x ? NXS : NYS;
+            const int r = e / per, sl = e - r * per;
+            t_rs[i] = 256 * r + sl;
+            t_lds[i] = is_x ? a.ybuf_slots + r * a.RSX + sl : r * a.RSY + sl;
+            const int row = is_x ? cg * 64 + r : fg * FB * 16 + r;
+            const int nrows = is_x ? a.C : a.K, len = is_x ? a.W : a.Q;
+            t_row_ok[i] = row < nrows;
+            t_vo[i] = static_cast<unsigned>(min(row, nrows - 1) * len + 8 * sl) * 2u;
         }
+        auto task_valid = [&](int i) { return i < NTX ? rtid + 256 * i < NXT : rtid + 256 * (i - NTX) < NYT; };
         // Two register sets: the loads of unit u + 2 are requested before unit u + 1 is written to LDS (a unit is
         // consumed faster than memory answers).  Set u & 1 (counted from the strip's first unit) holds unit u.
-        // Every load is unconditional, from a column clamped into the row; what lies outside the row is shifted
-        // out and zeroed when the registers are written to LDS (a branch around a load would make the compiler
-        // wait for each load where the paths join).  dy slots that start at an odd column (odd padding) are the
-        // 16 bytes from the even column before plus one more element pair.
-        constexpr int NYTT = (NYT + 255) / 256 + 1;  // tasks of a thread that can be dy slots
-        constexpr int IY0 = NXT / 256;               // the first of them
+        // Every load is unconditional (a branch around a load would make the compiler wait for each load where the
+        // paths join).  Units that lie inside their rows - all but the first and last of a row - take buffer
+        // loads whose address is the thread's constant offset plus a scalar offset per unit, and are written to
+        // LDS as they are; for the others the column is clamped into the row, and what lies outside is shifted out
+        // and zeroed when the registers are written to LDS.  dy slots that start at an odd column (odd padding) are
+        // the 16 bytes from the even column before plus one more element pair.
         struct Regs {
-            u32x4 v[NT];
-            unsigned nxt[NYTT];
+            u32x4 v[NTT];
+            unsigned nxt[NTY];
         };
         Regs reg[2];
         const int podd = Pr & 1;
+        const bool all_rows = cg * 64 + 64 <= a.C && (fg + 1) * FB * 16 <= a.K;
+        struct Cols {
+            int cx, cy;  // first column of the unit's x slots, and of its dy slots (even: one less if Pr is odd)
+            bool lean;
+        };
+        auto cols = [&](const Unit& un) -> Cols {
+            Cols c;
+            c.cx = 8 * (4 * un.t0 - 1 - P8);
+            c.cy = Pr - 8 + 32 * un.t0 - podd;
+            c.lean = a.fast && c.cx >= 0 && c.cx + 8 * NXS <= a.W && c.cy >= 0 && c.cy + 8 * NYS + 2 <= a.Q;
+            return c;
+        };
         auto fetch = [&](int u, Regs& rg) {
             const Unit un = unit(u);
+            const Cols c = cols(un);
             const unsigned short* xb = a.x + static_cast<long>(un.n) * a.x_sn;
             const unsigned short* yb = a.dy + static_cast<long>(un.n) * a.dy_sn;
-            const int cx = 8 * (4 * un.t0 - 1 - P8), cy = Pr - 8 + 32 * un.t0;
+            if (c.lean) {
+                // (the range check of the descriptors is not relied upon: every address is inside the sample's block)
+                const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned short*>(xb), 0, 2 * a.C * a.W, kBufferRsrcFlags);
+                const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned short*>(yb), 0, 2 * a.K * a.Q, kBufferRsrcFlags);
 #pragma unroll
-            for (int i = 0; i < NT; ++i) {
-                const bool is_x = rtid + 256 * i < NXT;
-                const unsigned short* row = is_x ? xb + static_cast<long>(min(cg * 64 + (t_rs[i] >> 8), a.C - 1)) * a.W
-                                                 : yb + static_cast<long>(min(fg * FB * 16 + (t_rs[i] >> 8), a.K - 1)) * a.Q;
+                for (int i = 0; i < NTT; ++i) {
+                    if (i < NTX) {
+                        rg.v[i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rx, static_cast<int>(t_vo[i]), 2 * c.cx, 0));
+                    } else {
+                        rg.v[i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ry, static_cast<int>(t_vo[i]), 2 * c.cy, 0));
+                        if (podd) rg.nxt[i - NTX] = __builtin_amdgcn_raw_buffer_load_b32(ry, static_cast<int>(t_vo[i]), 2 * c.cy + 16, 0);
+                    }
+                }
+                return;
+            }
+#pragma unroll
+            for (int i = 0; i < NTT; ++i) {
+                const bool is_x = i < NTX;
+                const int sl = t_rs[i] & 255;
+                const unsigned short* row = (is_x ? xb : yb) + ((t_vo[i] >> 1) - 8 * sl);
                 const int limit = is_x ? a.W : a.Q;
-                const int c = is_x ? cx + 8 * (t_rs[i] & 255) : cy + 8 * (t_rs[i] & 255) - podd;  // even
+                const int col = (is_x ? c.cx : c.cy) + 8 * sl;  // even
                 if (a.fast) {
-                    rg.v[i] = load128_clamped(row, c, limit);
-                    if (i >= IY0 && i - IY0 < NYTT) rg.nxt[i - IY0 < NYTT ? i - IY0 : 0] = podd ? load_pair(row, c + 8, limit) : 0u;
+                    rg.v[i] = load128_clamped(row, col, limit);
+                    if (!is_x) rg.nxt[is_x ? 0 : i - NTX] = podd ? load_pair(row, col + 8, limit) : 0u;
                 } else {
-                    rg.v[i] = load_slot(row, is_x ? c : c + podd, limit);  // element by element
+                    rg.v[i] = load_slot(row, is_x ? col : col + podd, limit);  // element by element
                 }
             }
         };
         auto commit = [&](int u, int b, const Regs& rg) {
             const Unit un = unit(u);
-            const int cx = 8 * (4 * un.t0 - 1 - P8), cy = Pr - 8 + 32 * un.t0;
+            const Cols c = cols(un);
             u32x4* st = lds4 + b * a.stage_slots;
 #pragma unroll
-            for (int i = 0; i < NT; ++i)
-                if (rtid + 256 * i < NXT + NYT) {
-                    const bool is_x = rtid + 256 * i < NXT;
-                    const bool row_ok = is_x ? cg * 64 + (t_rs[i] >> 8) < a.C : fg * FB * 16 + (t_rs[i] >> 8) < a.K;
+            for (int i = 0; i < NTT; ++i)
+                if (task_valid(i)) {
+                    const bool is_x = i < NTX;
                     u32x4 v = rg.v[i];
                     if (a.fast) {
-                        const int limit = is_x ? a.W : a.Q;
-                        const int c = is_x ? cx + 8 * (t_rs[i] & 255) : cy + 8 * (t_rs[i] & 255) - podd;
-                        v = fix128(v, c, limit);
-                        if (i >= IY0 && i - IY0 < NYTT) {
-                            if (!is_x && podd) v = shift_one(v, rg.nxt[i - IY0 < NYTT ? i - IY0 : 0]);
-                        }
+                        if (!c.lean) v = fix128(v, (is_x ? c.cx : c.cy) + 8 * (t_rs[i] & 255), is_x ? a.W : a.Q);
+                        if (!is_x && podd) v = shift_one(v, rg.nxt[is_x ? 0 : i - NTX]);
                     }
-                    st[t_lds[i]] = row_ok ? v : u32x4{0u, 0u, 0u, 0u};
+                    if (!all_rows) v = t_row_ok[i] ? v : u32x4{0u, 0u, 0u, 0u};
+                    st[t_lds[i]] = v;
                 }
         };
         const int nu = u_end - u_begin;

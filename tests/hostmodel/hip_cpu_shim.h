@@ -96,6 +96,13 @@ inline unsigned hostmodel_buffer_load_b32(hostmodel_rsrc r, int voff, int soff) 
     return v;
 }
 #define __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, aux) hostmodel_buffer_load_b32(r, voff, soff)
+typedef __attribute__((ext_vector_type(4))) unsigned int hostmodel_u32x4;
+inline hostmodel_u32x4 hostmodel_buffer_load_b128(hostmodel_rsrc r, int voff, int soff) {
+    hostmodel_u32x4 v;
+    std::memcpy(&v, r.base + static_cast<long>(static_cast<unsigned>(voff)) + static_cast<long>(soff), 16);
+    return v;
+}
+#define __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, aux) hostmodel_buffer_load_b128(r, voff, soff)
 inline unsigned short hostmodel_buffer_load_b16(hostmodel_rsrc r, int voff, int soff) {
     unsigned short v;
     std::memcpy(&v, r.base + static_cast<long>(static_cast<unsigned>(voff)) + static_cast<long>(soff), 2);
