@@ -106,8 +106,32 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
     // Contiguous strip of tiles per workgroup.  Workgroups are dealt round-robin to the 8 XCDs, so the
     // logical index puts neighbouring strips (which share halos) on the same XCD and its L2.
     const int lid = xcd_logical_id(blockIdx.x, gridDim.x);
-    const int t_begin = static_cast<int>(static_cast<long>(lid) * ntiles / gridDim.x);
-    const int t_end = static_cast<int>(static_cast<long>(lid + 1) * ntiles / gridDim.x);
+    int t_begin = static_cast<int>(static_cast<long>(lid) * ntiles / gridDim.x);
+    int t_wend = static_cast<int>(static_cast<long>(lid + 1) * ntiles / gridDim.x);  // end of the whole tiles
+    // Half tiles.  With ntiles = base * grid + rem the strips above hold base or base + 1 tiles and the launch lasts
+    // base + 1 tile times.  Where the plain output path applies (block staging, aligned float rows, no epilogue
+    // beyond the bias) and 2 rem <= grid, every workgroup takes base whole tiles instead, and the rem tiles left over
+    // are cut into halves of TQ / 2 columns, one for each of the first 2 rem workgroups: it is that workgroup's last
+    // item (index t_wend), staged like any tile that starts at its first column, computed by the four consumer
+    // waves on 64 columns each.  The launch then lasts base + 1/2 tile times.
+    int xn = 0, xO0 = 0;  // (sample, first column) of the workgroup's half tile
+    bool has_half = false;
+    if constexpr (L16) {
+        const int grid = static_cast<int>(gridDim.x);
+        const int base = ntiles / grid, rem = ntiles - base * grid;
+        const bool plain = vec_out && !p.accumulate && !p.epi.relu && !p.epi.out_bf16 && p.M >= 15;
+        if (plain && base >= 1 && rem > 0 && 2 * rem <= grid) {
+            t_begin = lid * base;
+            t_wend = t_begin + base;
+            if (lid < 2 * rem) {
+                const int X = grid * base + (lid >> 1);
+                xn = X / tiles_per_row;
+                xO0 = (X - xn * tiles_per_row) * TQ + (lid & 1) * (TQ / 2);
+                has_half = xO0 < p.Wout;
+            }
+        }
+    }
+    const int t_end = t_wend + (has_half ? 1 : 0);
 
     // ---- producer side: window staging -----------------------------------------------------------
     // One staging task = 8 channels (half h) x 2 adjacent positions: 8 dwords in, two 16-byte
@@ -186,6 +210,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
         int n, O0;
     };
     auto tile_pos = [&](int t) -> TilePos {
+        if (has_half && t >= t_wend) return TilePos{xn, xO0};
         TilePos tp{cur_n, cur_O0 + (t - cur_t) * TQ};
         while (tp.O0 >= row_w) {
             tp.O0 -= row_w;
@@ -422,13 +447,15 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
     __syncthreads();  // the slice entries alias the staging buffers: every wave has its copy before anyone parks
 
     // ---- consumer side: one tile's reduction, parked in LDS ------------------------------------------
-    auto compute = [&](const u32x4* wb, float* dst) {
-        f32x4 acc[T];
+    // (TT position blocks per wave from column obx of the tile on: T and ob for a whole tile, T / 2 and ob / 2 for a half tile)
+    auto compute_tt = [&](auto tt_, int obx, const u32x4* wb, float* dst) {
+        constexpr int TT = decltype(tt_)::value;
+        f32x4 acc[TT];
 #pragma unroll
-        for (int j = 0; j < T; ++j) acc[j] = f32x4{bias_li, bias_li, bias_li, bias_li};
+        for (int j = 0; j < TT; ++j) acc[j] = f32x4{bias_li, bias_li, bias_li, bias_li};
         // (L16: slot(position) = (position & 7) * NB + (position >> 3); every offset but the lane's own is a multiple of 8)
-        const u32x4* bbase = L16 ? wb + (kb & 1) * LPS + (li & 7) * NB + (li >> 3) + ((ob + (kb >> 1) * NP * d) >> 3)
-                                 : wb + (kb & 1) * LPS + ob + li + (kb >> 1) * NP * d + psh;
+        const u32x4* bbase = L16 ? wb + (kb & 1) * LPS + (li & 7) * NB + (li >> 3) + ((obx + (kb >> 1) * NP * d) >> 3)
+                                 : wb + (kb & 1) * LPS + obx + li + (kb >> 1) * NP * d + psh;
         // The input fragment is the A operand and the weight slice the B operand, so the accumulator tile is
         // [position][filter]: lane (li, kb) holds filter li at the 4 adjacent columns 4 kb .. 4 kb + 3 of tile j,
         // parked with one 16-byte LDS write.
@@ -439,7 +466,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
             // The scheduling barriers pin this interleaving.
             constexpr int PF = 3;
             constexpr int D = L16 ? (16 / (G > 0 ? G : 1)) / 8 : 16 / (G > 0 ? G : 1);  // slots between consecutive operands
-            constexpr int NF = G * (T - 1) + NP;
+            constexpr int NF = G * (TT - 1) + NP;
             // rotating: operand m lives in slot m % (PF + 2); one slot more than the look-ahead needs, so that a
             // read never targets the registers of the operand whose MFMAs have only just been issued
             bf16x8 fr[PF + 2];
@@ -449,39 +476,42 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
             for (int m = 0; m < NF; ++m) {
                 if (m + PF < NF) fr[(m + PF) % (PF + 2)] = as_bf16x8(bbase[(m + PF) * D]);
 #pragma unroll
-                for (int j = 0; j < T; ++j)
+                for (int j = 0; j < TT; ++j)
                     if (G * j + NP - 1 == m - 2) park(j);
 #pragma unroll
-                for (int j = 0; j < T; ++j) {
+                for (int j = 0; j < TT; ++j) {
                     const int pi = m - G * j;
                     if (pi >= 0 && pi < NP) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fr[m % (PF + 2)], wreg[pi < 0 ? 0 : (pi >= NP ? 0 : pi)], acc[j], 0, 0, 0);
                 }
                 // issue order within the step: one MFMA, one LDS operation, one MFMA, ... so that the operand
                 // read and the parking writes go out in the shadow of the MFMAs instead of in front of them
 #pragma unroll
-                for (int j = 0; j < T; ++j) {
+                for (int j = 0; j < TT; ++j) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                     __builtin_amdgcn_sched_group_barrier(0x080, 1, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
-            for (int j = 0; j < T; ++j)
+            for (int j = 0; j < TT; ++j)
                 if (G * j + NP - 1 > NF - 3) park(j);
         } else {
             // dilations without operand sharing between tiles: every (tile, slice) pair reads its own operand
 #pragma unroll
             for (int pi = 0; pi < NP; ++pi) {
 #pragma unroll
-                for (int j = 0; j < T; ++j) {
+                for (int j = 0; j < TT; ++j) {
                     const bf16x8 f = as_bf16x8(bbase[16 * j + pi * d]);
                     acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f, wreg[pi], acc[j], 0, 0, 0);
                 }
             }
 #pragma unroll
-            for (int j = 0; j < T; ++j) park(j);
+            for (int j = 0; j < TT; ++j) park(j);
         }
     };
+    auto compute = [&](const u32x4* wb, float* dst) { compute_tt(std::integral_constant<int, T>{}, ob, wb, dst); };
+    auto compute_half = [&](const u32x4* wb, float* dst) { compute_tt(std::integral_constant<int, T / 2>{}, ob / 2, wb, dst); };
+
 
     // ---- steady state, block staging ---------------------------------------------------------------
     // Measured on this kernel: every instruction a producer wave issues, vector or scalar, lengthens the tile by about
@@ -493,7 +523,11 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
         if (consumer) {
             int k = 0;
             for (int t = t_begin; t < t_end; ++t, ++k) {
-                compute(win(k & 1), ost(k & 1));
+                if (t < t_wend) {
+                    compute(win(k & 1), ost(k & 1));
+                } else {
+                    compute_half(win(k & 1), ost(k & 1));
+                }
                 __syncthreads();
             }
             return;
@@ -542,6 +576,19 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
             for (int q = 0; q < 7; ++q) *reinterpret_cast<f32x4*>(base + voff_st[q]) = v[q];
             if (last_row_ok) *reinterpret_cast<f32x4*>(base + voff_st[7]) = v[7];
         };
+        // the workgroup's half tile: 16 rows x 64 columns per wave, 4 rows per store instruction
+        auto flush_half = [&](int b) {
+            const int hrow = lane >> 4, hcol = 4 * (lane & 15);
+            const float* src = ost(b) + hrow * kOS + hcol;
+            f32x4 v[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const f32x4*>(src + 4 * q * kOS);
+            const int col = xO0 + ob / 2 + hcol;
+            float* base = p.out + static_cast<long>(xn) * p.out_sn + col;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (col < p.Wout && 4 * q + hrow < p.M) *reinterpret_cast<f32x4*>(base + static_cast<long>(4 * q + hrow) * p.Wout) = v[q];
+        };
         // (sample, first column) of tiles t - 1 .. t + 2, moved along with the loop
         TilePos tm1{0, 0}, t0 = tile_pos(t_begin), tp1 = tile_pos(t_begin + 1), tp2 = tile_pos(t_begin + 2);
         auto next_pos = [&](TilePos a) {
@@ -580,9 +627,15 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
             tm1 = t0;
             t0 = tp1;
             tp1 = tp2;
-            tp2 = next_pos(tp2);
+            tp2 = (has_half && t + 3 >= t_wend) ? TilePos{xn, xO0} : next_pos(tp2);
         }
-        if (k > 0) flush(t_end - 1, (k - 1) & 1);
+        if (k > 0) {
+            if (has_half) {
+                flush_half((k - 1) & 1);
+            } else {
+                flush(t_end - 1, (k - 1) & 1);
+            }
+        }
         return;
     }
 
