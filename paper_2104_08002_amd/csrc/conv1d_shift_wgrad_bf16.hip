@@ -1,5 +1,5 @@
 // Backward-weight pass (Section 3.3, Algorithm 4) for bfloat16 inputs, few taps and small dilations
-// (d = 1, 2 with (S - 1) d <= 16): the tap shift is applied in registers.
+// (d = 1, 2 with (S - 1) d <= 16, d = 4 with (S - 1) d <= 32): the tap shift is applied in registers.
 //
 //   dw[k][c][s] = sum_n sum_q dy[n][k][q] * x[n][c][q + s*d - P]
 //
@@ -13,7 +13,7 @@
 // v_alignbit_b32 per operand.  A wave reads 2 - 3 x slots and FB dy slots from LDS per k-step for SMAX * FB MFMAs.
 //
 // Work split.  A workgroup owns 64 channels (consumer wave v: channels 16 v .. 16 v + 15), FB blocks of 16
-// filters, all taps, and a strip of the positions (units of LU k-steps of 32 positions); it keeps all its sums
+// filters, all taps, and a strip of the positions (units of 8 (or 4) k-steps of 32 positions); it keeps all its sums
 // in registers and writes one partial tile to the workspace; a second kernel adds the strips in a fixed order
 // (no floating-point atomics).  Workgroup = 8 waves: waves 0-3 consume, waves 4-7 ("producers") load the next
 // unit from global memory and write it into the other half of the double-buffered LDS.  One workgroup barrier
@@ -32,7 +32,9 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int kLdsBudget = 160 * 1024;
 constexpr int kNumCU = 256;
-constexpr int kLU = 8;  // k-steps per unit
+// k-steps per unit: 8, or 4 with four filter blocks (the producers' two register sets hold one slot per task: 9 x and 8
+// dy tasks per thread at 8 k-steps no longer fit, 5 + 4 at 4 k-steps do, and the unit is as long in MFMAs either way)
+constexpr int lu_of(int FB) { return FB == 4 ? 4 : 8; }
 constexpr int kBufferRsrcFlags = 0x00020000;  // fourth dword of a raw buffer descriptor (32-bit data format, no swizzle)
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -57,11 +59,12 @@ struct SwArgs {
 };
 
 // Compile-time geometry: dilation D, taps computed SMAX (taps s >= S are computed and dropped), filter blocks FB.
-template <int D, int SMAX>
+template <int D, int SMAX, int FB>
 struct Sw {
+    static constexpr int LU = lu_of(FB);
     static constexpr int NSL = 1 + ((SMAX - 1) * D + 7) / 8;  // x slots a lane reads per k-step
-    static constexpr int NXS = 4 * kLU + NSL - 1;             // x slots per row of a unit
-    static constexpr int NYS = 4 * kLU;                       // dy slots per row of a unit
+    static constexpr int NXS = 4 * LU + NSL - 1;              // x slots per row of a unit
+    static constexpr int NYS = 4 * LU;                        // dy slots per row of a unit
 };
 
 // the 8 elements of columns c .. c + 7 of a row of `limit` columns, zero outside the row: element by element, for
@@ -75,8 +78,8 @@ __device__ __forceinline__ u32x4 load_slot(const unsigned short* row, int c, int
 
 template <int D, int SMAX, int FB>
 __global__ __launch_bounds__(512, 1) void shift_wgrad_bf16_kernel(SwArgs a) {
-    using G = Sw<D, SMAX>;
-    constexpr int NSL = G::NSL, NXS = G::NXS, NYS = G::NYS;
+    using G = Sw<D, SMAX, FB>;
+    constexpr int NSL = G::NSL, NXS = G::NXS, NYS = G::NYS, LU = G::LU;
     constexpr int NXT = 64 * NXS, NYT = FB * 16 * NYS;  // staging tasks (16-byte slots) per unit
     constexpr int NT = (NXT + NYT + 255) / 256;          // per producer thread (one more when neither count is a multiple of 256)
     extern __shared__ u32x4 lds4[];
@@ -110,8 +113,8 @@ __global__ __launch_bounds__(512, 1) void shift_wgrad_bf16_kernel(SwArgs a) {
     auto unit = [&](int u) -> Unit {
         Unit un;
         un.n = fast_div(u, a.dv_upr);
-        un.t0 = (u - un.n * a.UPR) * kLU;
-        un.ks = min(kLU, a.KSR - un.t0);
+        un.t0 = (u - un.n * a.UPR) * LU;
+        un.ks = min(LU, a.KSR - un.t0);
         return un;
     };
 
@@ -344,6 +347,9 @@ hipError_t sw_launch(const SwPlan& pl, hipStream_t st) {
 template <int D, int SMAX>
 hipError_t sw_launch_fb(const SwPlan& pl, hipStream_t st) {
     switch (pl.FB) {
+        case 4:
+            if constexpr (SMAX <= 9) return sw_launch<D, SMAX, 4>(pl, st);
+            return hipErrorInvalidValue;
         case 2: return sw_launch<D, SMAX, 2>(pl, st);
         case 1: return sw_launch<D, SMAX, 1>(pl, st);
         default: return hipErrorInvalidValue;
@@ -357,9 +363,9 @@ namespace {
 using sw::SwArgs;
 using sw::SwPlan;
 
-template <int D, int SMAX>
-void sw_geometry(SwPlan& pl) {
-    using G = sw::Sw<D, SMAX>;
+template <int D, int SMAX, int FB>
+void sw_geometry_fb(SwPlan& pl) {
+    using G = sw::Sw<D, SMAX, FB>;
     SwArgs& a = pl.a;
     a.RSX = G::NXS | 1;
     a.RSY = G::NYS | 1;
@@ -369,20 +375,29 @@ void sw_geometry(SwPlan& pl) {
     pl.lds_bytes = static_cast<size_t>(2 * a.stage_slots + 8) * 16;
 }
 
+template <int D, int SMAX>
+void sw_geometry(SwPlan& pl) {
+    switch (pl.FB) {
+        case 4: sw_geometry_fb<D, SMAX, 4>(pl); break;
+        case 2: sw_geometry_fb<D, SMAX, 2>(pl); break;
+        default: sw_geometry_fb<D, SMAX, 1>(pl); break;
+    }
+}
+
 SwPlan sw_plan(const WgradProblem& p) {
     SwPlan pl{};
     pl.ok = false;
     if (!p.bf16) return pl;
-    // (dilation 4 would work the same way, but there the ring kernel needs only two phase copies and measured
-    // faster: 24.6 us against 26.9 us on C = K = 64, S = 5)
-    if (p.d != 1 && p.d != 2) return pl;
-    if (static_cast<long>(p.S - 1) * p.d > 16 || p.S < 2) return pl;
+    // (dilation 4: the caller prefers the ring kernel, which needs only two phase copies there, where that applies)
+    if (p.d != 1 && p.d != 2 && p.d != 4) return pl;
+    const int max_shift = p.d == 4 ? 32 : 16;  // 3 x slots per lane and k-step; 5 at dilation 4 (shifts of whole dwords)
+    if (static_cast<long>(p.S - 1) * p.d > max_shift || p.S < 2) return pl;
     if (p.dw_sc != p.S || p.dw_sk != static_cast<long>(p.C) * p.S) return pl;  // writes the whole dw tensor
     if (static_cast<long>(p.C) * p.W >= (1L << 30) || static_cast<long>(p.K) * p.Q >= (1L << 30)) return pl;
     if (static_cast<long>(p.K) * p.C * p.S >= (1L << 31)) return pl;
     if (p.P < 0 || p.W < 1 || p.Q < 1) return pl;
     const int SMAX = p.S <= 5 ? 5 : (p.S <= 9 ? 9 : 17);
-    if (static_cast<long>(SMAX - 1) * p.d > 16) return pl;
+    if (static_cast<long>(SMAX - 1) * p.d > max_shift) return pl;
     SwArgs& a = pl.a;
     a.x = static_cast<const unsigned short*>(p.x);
     a.dy = static_cast<const unsigned short*>(p.dy);
@@ -396,18 +411,20 @@ SwPlan sw_plan(const WgradProblem& p) {
     const int Pr = p.P & 7;
     const int NJ = cdiv(p.Q - Pr + 8, 8);
     a.KSR = cdiv(NJ, 4);
-    a.UPR = cdiv(a.KSR, sw::kLU);
+    // filter blocks per workgroup: as many as the accumulators allow (every x slot staged then feeds more MFMAs),
+    // fewer when that leaves compute units idle (a strip should still have some 32 k-steps: every workgroup pays a
+    // start-up and writes a partial tile)
+    const int fbmax = SMAX <= 9 ? 4 : 2;
+    int FB = 1;
+    while (FB * 2 <= fbmax && FB * 16 < p.K) FB *= 2;
+    const long row_units8 = cdiv(a.KSR, 8);
+    while (FB > 1 && static_cast<long>(cdiv(cdiv(p.K, 16), FB)) * a.ncg * cdiv(p.N * row_units8, 4) < sw::kNumCU) FB /= 2;
+    pl.FB = FB;
+    a.UPR = cdiv(a.KSR, sw::lu_of(FB));
     const long nunits = static_cast<long>(p.N) * a.UPR;
     if (nunits >= (1L << 30)) return pl;
     a.nunits = static_cast<int>(nunits);
     if (!make_fastdiv(a.dv_upr, a.UPR, nunits)) return pl;
-    // filter blocks per workgroup: two, one when that leaves compute units idle
-    // (a strip should still have a few units: every workgroup pays a start-up and writes a partial tile)
-    const int fbmax = 2;  // (four blocks: the producers' two register sets of 17 slots no longer fit)
-    int FB = 1;
-    while (FB * 2 <= fbmax && FB * 16 < p.K) FB *= 2;
-    while (FB > 1 && static_cast<long>(cdiv(cdiv(p.K, 16), FB)) * a.ncg * cdiv(nunits, 4) < sw::kNumCU) FB /= 2;
-    pl.FB = FB;
     pl.D = p.d;
     pl.SMAX = SMAX;
     a.nfg = cdiv(cdiv(p.K, 16), FB);
@@ -428,6 +445,8 @@ SwPlan sw_plan(const WgradProblem& p) {
         case 117: sw_geometry<1, 17>(pl); break;
         case 205: sw_geometry<2, 5>(pl); break;
         case 209: sw_geometry<2, 9>(pl); break;
+        case 405: sw_geometry<4, 5>(pl); break;
+        case 409: sw_geometry<4, 9>(pl); break;
         default: return pl;
     }
     if (pl.lds_bytes > static_cast<size_t>(sw::kLdsBudget)) return pl;
@@ -454,6 +473,8 @@ hipError_t shift_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st) {
         case 117: e = sw::sw_launch_fb<1, 17>(pl, st); break;
         case 205: e = sw::sw_launch_fb<2, 5>(pl, st); break;
         case 209: e = sw::sw_launch_fb<2, 9>(pl, st); break;
+        case 405: e = sw::sw_launch_fb<4, 5>(pl, st); break;
+        case 409: e = sw::sw_launch_fb<4, 9>(pl, st); break;
         default: e = hipErrorInvalidValue; break;
     }
     if (e != hipSuccess) return e;
