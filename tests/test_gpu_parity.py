@@ -130,6 +130,8 @@ SMALL = [
     ("shift_S9_d2_big_P", 1, 64, 64, 300,  9,  2,  37),    # padding beyond the span: x slots left of the row
     ("shift_tiny_W",      2, 20, 20, 9,    5,  1,  2),     # less than one k-step
     ("shift_k300",        1, 24, 300, 2000, 3, 1,  1),     # many filter groups
+    ("shift_d4_c96",      2, 96, 96, 900,  5,  4,  7),     # dilation 4, many channel blocks, odd padding; four filter blocks
+    ("shift_d4_S9_c300",  1, 300, 40, 1000, 9, 4,  16),    # five x slots per lane; ragged channel and filter groups
     ("c40_halo_gt_width", 2, 40, 24, 200,  51, 8,  200),   # many channels, halo (S-1)d = 400 exceeds W
     ("c40_tiny_Q",        3, 40, 24, 420,  51, 8,  0),     # Q = 20: less than one k-step / one position block pair
 ]
