@@ -20,7 +20,7 @@ _ERR_TABLE = os.path.join(_ROOT, "gpurun_out", "parity_errors.jsonl")
 
 
 def record(case: str, variant: str, errs: dict) -> None:
-    """Append one line per compared case to gpurun_out/parity_errors.jsonl (the per-case error table)."""
+    """Append one line per compared case to the per-case error table (a JSON-lines file in the run's output folder)."""
     try:
         os.makedirs(os.path.dirname(_ERR_TABLE), exist_ok=True)
         with open(_ERR_TABLE, "a") as f:
