@@ -147,6 +147,35 @@ def test_small_geometries(binding, oracle, case, dtype, variant):
     _run_full(binding, oracle, wl, variant)
 
 
+# ---- seeded random geometries in the many-channel, few-tap corner (bf16): the resident-weight kernel's two prologue
+# ---- paths and filter-block counts, the register-shift backward-weight kernel's slot counts, masks and edge units ----
+def _random_few_tap_cases(count=36, seed=20210408):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        d = int(rng.choice([1, 2, 4, 8, 16]))
+        S = int(rng.integers(2, 13)) if d <= 4 else int(rng.integers(5, 13))
+        C = int(rng.choice([17, 24, 32, 40, 64, 72, 96, 130]))
+        K = int(rng.choice([17, 24, 33, 48, 64, 80, 100, 144]))
+        W = int(rng.integers(40, 2600))
+        P = int(rng.integers(0, (S - 1) * d + 3))
+        N = int(rng.integers(1, 4))
+        if W + 2 * P - (S - 1) * d < 1:
+            continue
+        cases.append((f"rnd{len(cases)}_c{C}_k{K}_S{S}_d{d}", N, C, K, W, S, d, P))
+    return cases
+
+
+RANDOM_FEW_TAP = _random_few_tap_cases()
+
+
+@pytest.mark.parametrize("case", RANDOM_FEW_TAP, ids=[c[0] for c in RANDOM_FEW_TAP])
+def test_random_many_channel_few_taps(binding, oracle, case):
+    name, N, C, K, W, S, d, P = case
+    wl = _mk(f"{name}_bf16", N, C, K, W, S, d, P, "bf16", seed=inputs.BASE_SEED + 3000 + len(name) + W)
+    _run_full(binding, oracle, wl, "auto")
+
+
 # ---- base pointers that are only element-aligned: every kernel's unaligned path --------------------
 UNALIGNED = [
     # name             N  C   K   W     S   d  P
