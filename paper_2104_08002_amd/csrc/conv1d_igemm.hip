@@ -148,13 +148,9 @@ hipError_t igemm_corr_launch(const CorrProblem& p, hipStream_t st) {
     return hipSuccess;
 }
 
-// the register-shift kernel where the others would stage several phase copies of x for a handful of taps
-// (at dilation 4 the ring kernel needs only two copies and measured faster where it applies: 24.6 us against 26.9 us
-// on C = K = 64, S = 5)
-static bool prefer_shift_wgrad(const WgradProblem& p) {
-    if (!p.bf16 || !shift_bf16_wgrad_supported(p)) return false;
-    return p.d < 4 || !toeplitz_bf16_wgrad_supported(p);
-}
+// the register-shift kernel wherever it applies: the others stage several phase copies of x for these shapes (measured
+// on C = K = 64: 23.4 against 24.7 us at S = 5, d = 4; 35.2 against 37.4 us at S = 17, d = 2; 24 against 50 us at S = 5, d = 1)
+static bool prefer_shift_wgrad(const WgradProblem& p) { return p.bf16 && shift_bf16_wgrad_supported(p); }
 
 bool igemm_wgrad_supported(const WgradProblem& p) {
     if (p.bf16 && (shift_bf16_wgrad_supported(p) || toeplitz_bf16_wgrad_supported(p) || blocked_bf16_wgrad_supported(p))) return true;

@@ -122,7 +122,7 @@ bool toeplitz_bf16_wgrad_supported(const WgradProblem& p);
 size_t toeplitz_bf16_wgrad_workspace(const WgradProblem& p);
 hipError_t toeplitz_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st);
 
-// bf16 backward-weight for dilations 1, 2 and few taps ((S - 1) d <= 16): x is staged once and the tap shift is
+// bf16 backward-weight for dilations 1, 2, 4 and few taps ((S - 1) d <= 16, 32 at even dilations): x is staged once and the tap shift is
 // applied in registers
 bool shift_bf16_wgrad_supported(const WgradProblem& p);
 size_t shift_bf16_wgrad_workspace(const WgradProblem& p);

@@ -1,5 +1,5 @@
 // Backward-weight pass (Section 3.3, Algorithm 4) for bfloat16 inputs, few taps and small dilations
-// (d = 1, 2 with (S - 1) d <= 16, d = 4 with (S - 1) d <= 32): the tap shift is applied in registers.
+// (d = 1 with (S - 1) d <= 16, d = 2, 4 with (S - 1) d <= 32): the tap shift is applied in registers.
 //
 //   dw[k][c][s] = sum_n sum_q dy[n][k][q] * x[n][c][q + s*d - P]
 //
@@ -388,9 +388,8 @@ SwPlan sw_plan(const WgradProblem& p) {
     SwPlan pl{};
     pl.ok = false;
     if (!p.bf16) return pl;
-    // (dilation 4: the caller prefers the ring kernel, which needs only two phase copies there, where that applies)
     if (p.d != 1 && p.d != 2 && p.d != 4) return pl;
-    const int max_shift = p.d == 4 ? 32 : 16;  // 3 x slots per lane and k-step; 5 at dilation 4 (shifts of whole dwords)
+    const int max_shift = p.d >= 2 ? 32 : 16;  // 3 x slots per lane and k-step; 5 at even dilations (shifts of whole dwords)
     if (static_cast<long>(p.S - 1) * p.d > max_shift || p.S < 2) return pl;
     if (p.dw_sc != p.S || p.dw_sk != static_cast<long>(p.C) * p.S) return pl;  // writes the whole dw tensor
     if (static_cast<long>(p.C) * p.W >= (1L << 30) || static_cast<long>(p.K) * p.Q >= (1L << 30)) return pl;
@@ -445,6 +444,7 @@ SwPlan sw_plan(const WgradProblem& p) {
         case 117: sw_geometry<1, 17>(pl); break;
         case 205: sw_geometry<2, 5>(pl); break;
         case 209: sw_geometry<2, 9>(pl); break;
+        case 217: sw_geometry<2, 17>(pl); break;
         case 405: sw_geometry<4, 5>(pl); break;
         case 409: sw_geometry<4, 9>(pl); break;
         default: return pl;
@@ -473,6 +473,7 @@ hipError_t shift_bf16_wgrad_launch(const WgradProblem& p, hipStream_t st) {
         case 117: e = sw::sw_launch_fb<1, 17>(pl, st); break;
         case 205: e = sw::sw_launch_fb<2, 5>(pl, st); break;
         case 209: e = sw::sw_launch_fb<2, 9>(pl, st); break;
+        case 217: e = sw::sw_launch_fb<2, 17>(pl, st); break;
         case 405: e = sw::sw_launch_fb<4, 5>(pl, st); break;
         case 409: e = sw::sw_launch_fb<4, 9>(pl, st); break;
         default: e = hipErrorInvalidValue; break;
