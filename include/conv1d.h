@@ -159,8 +159,9 @@ size_t conv1d_bwd_weight_workspace_bytes(int N, int C, int K, int W, int S, int 
  * workspace: device, 256-byte aligned, at least workspace_bytes >=
  * conv1d_bwd_weight_workspace_bytes(...); contents on entry are ignored and
  * on exit unspecified.  Two calls in flight must not share a workspace.
- * Sizes: about one S*16*16 float tile per workgroup, e.g. 12.5 MB for
- * N=16, C=K=15, W=60000, S=51, d=8 and 27 MB for N=8, C=K=64, W=20000, S=51. */
+ * Sizes: one partial tile of the workgroup's share of dw per workgroup, e.g.
+ * 13.4 MB for N=16, C=K=15, W=60000, S=51, d=8; 27.3 MB for N=8, C=K=64,
+ * W=20000, S=51; 37.7 MB for N=32, C=K=256, W=8192, S=9, d=4. */
 int conv1d_bwd_weight(const void* x, const void* dy, float* dw,
                       void* workspace, size_t workspace_bytes,
                       int N, int C, int K, int W, int S, int dilation, int padding,
