@@ -123,6 +123,24 @@ def test_seeded_random_geometries(model):
     assert ran >= 2400
 
 
+def test_seeded_random_few_tap_small_dilation(model):
+    """The corner of the register-shift backward-weight kernel and the light prologue paths of the resident-weight
+    kernel: bfloat16, 2-17 taps at dilations 1, 2, 4, any padding up to a little beyond the span."""
+    rng = np.random.default_rng(20210409)
+    ran = 0
+    for i in range(150):
+        N, C, K, W, S, d, P = _random_geometry(rng)
+        d = int(rng.choice([1, 2, 4]))
+        S = int(rng.integers(2, 18))
+        if (S - 1) * d > 32:
+            S = 32 // d + 1
+        P = int(rng.integers(0, (S - 1) * d + 9))
+        if W + 2 * P - (S - 1) * d < 1:
+            W = (S - 1) * d + 5
+        ran += _check(model, (N, C, K, W, S, d, P), 1, passes=(0, 1, 2), placements=(i % 2,))
+    assert ran >= 450
+
+
 def test_the_model_finds_a_planted_off_by_one():
     """The one GPU memory fault in this library's history: the streamed-weight kernel asked for a stage behind its
     counters and took its sample index one past the batch.  With that repair removed from the model's copy of the
