@@ -336,7 +336,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
 #pragma unroll
                 for (int q = 0; q < 8; ++q)
                     if (col_ok && 2 * q + orow < p.M)
-                        *reinterpret_cast<f32x4*>(p.out + base + static_cast<long>(2 * q) * p.Wout + lane_off) = v[q];
+                        __builtin_nontemporal_store(v[q], reinterpret_cast<f32x4*>(p.out + base + static_cast<long>(2 * q) * p.Wout + lane_off));
             } else if (p.accumulate) {
 #pragma unroll
                 for (int q = 0; q < 8; ++q)
@@ -573,8 +573,10 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
             for (int q = 0; q < 8; ++q) v[q] = *reinterpret_cast<const f32x4*>(src + 2 * q * kOS);
             char* base = reinterpret_cast<char*>(p.out + static_cast<long>(n) * p.out_sn + O0 + ob);  // uniform
 #pragma unroll
-            for (int q = 0; q < 7; ++q) *reinterpret_cast<f32x4*>(base + voff_st[q]) = v[q];
-            if (last_row_ok) *reinterpret_cast<f32x4*>(base + voff_st[7]) = v[7];
+            // (non-temporal stores: the outputs are not read again by this launch, and measured 1.3 us per launch
+            // faster than plain stores, with cached and with uncached tensors)
+            for (int q = 0; q < 7; ++q) __builtin_nontemporal_store(v[q], reinterpret_cast<f32x4*>(base + voff_st[q]));
+            if (last_row_ok) __builtin_nontemporal_store(v[7], reinterpret_cast<f32x4*>(base + voff_st[7]));
         };
         // the workgroup's half tile: 16 rows x 64 columns per wave, 4 rows per store instruction
         auto flush_half = [&](int b) {
@@ -587,7 +589,8 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
             float* base = p.out + static_cast<long>(xn) * p.out_sn + col;
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-                if (col < p.Wout && 4 * q + hrow < p.M) *reinterpret_cast<f32x4*>(base + static_cast<long>(4 * q + hrow) * p.Wout) = v[q];
+                if (col < p.Wout && 4 * q + hrow < p.M)
+                    __builtin_nontemporal_store(v[q], reinterpret_cast<f32x4*>(base + static_cast<long>(4 * q + hrow) * p.Wout));
         };
         // (sample, first column) of tiles t - 1 .. t + 2, moved along with the loop
         TilePos tm1{0, 0}, t0 = tile_pos(t_begin), tp1 = tile_pos(t_begin + 1), tp2 = tile_pos(t_begin + 2);
