@@ -46,6 +46,23 @@ __global__ __launch_bounds__(256) void mfma_f32_32x32x2_kernel(float* out, int i
     out[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// the 16 x 16 x 4 shape the FP32 kernels of the library use (4 accumulator registers per tile instead of 16)
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+template <int NACC>
+__global__ __launch_bounds__(256) void mfma_f32_16x16x4_kernel(float* out, int iters) {
+    const float a = static_cast<float>(threadIdx.x & 7), b = 1.0f;
+    f32x4 acc[NACC];
+    for (int j = 0; j < NACC; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < NACC; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[j], 0, 0, 0);
+    }
+    float s = 0.f;
+    for (int j = 0; j < NACC; ++j)
+        for (int i = 0; i < 4; ++i) s += acc[j][i];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 __global__ __launch_bounds__(256) void copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst, size_t n) {
     size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
     const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
@@ -108,12 +125,14 @@ int num_cus() {
 extern "C" {
 
 // Sustained dense MFMA rate of the whole GPU in TFLOP/s with 2 waves per SIMD and no memory traffic.
-// shape 0: v_mfma_f32_32x32x16_bf16, 1: v_mfma_f32_32x32x2_f32 (the 16 x 16 shapes have the same nominal rate).
+// shape 0: v_mfma_f32_32x32x16_bf16, 1: v_mfma_f32_32x32x2_f32, 2: v_mfma_f32_16x16x4_f32 (same nominal rate as 1).
+// Shapes 3-5 run ONE wave per SIMD, as the consumer waves of the library's kernels do: 3: 16x16x4 with 4 independent
+// accumulators, 4: 16x16x4 with 8, 5: 32x32x2 with 4.
 // Returns 0 and writes *tflops, or -1 on a HIP error / unknown shape.
 int conv1d_ubench_mfma_tflops(int shape, double* tflops) {
     const int ncu = num_cus();
     if (ncu <= 0 || !tflops) return -1;
-    const int blocks = ncu * 2, iters = 20000;  // 2 blocks of 4 waves per CU
+    const int blocks = shape >= 3 ? ncu : ncu * 2, iters = 20000;  // 1 or 2 blocks of 4 waves per CU
     float* out = nullptr;
     if (hipMalloc(&out, static_cast<size_t>(blocks) * 256 * sizeof(float)) != hipSuccess) return -1;
     Timer t;
@@ -127,6 +146,19 @@ int conv1d_ubench_mfma_tflops(int shape, double* tflops) {
                 flop = waves * iters * 4 * 2.0 * 32 * 32 * 16;
                 break;
             case 1:
+                ms = t.best_ms([&] { hipLaunchKernelGGL(mfma_f32_32x32x2_kernel<4>, dim3(blocks), dim3(256), 0, nullptr, out, iters / 4); }, 3);
+                flop = waves * (iters / 4) * 4 * 2.0 * 32 * 32 * 2;
+                break;
+            case 2:
+            case 3:
+                ms = t.best_ms([&] { hipLaunchKernelGGL(mfma_f32_16x16x4_kernel<4>, dim3(blocks), dim3(256), 0, nullptr, out, iters); }, 3);
+                flop = waves * iters * 4 * 2.0 * 16 * 16 * 4;
+                break;
+            case 4:
+                ms = t.best_ms([&] { hipLaunchKernelGGL(mfma_f32_16x16x4_kernel<8>, dim3(blocks), dim3(256), 0, nullptr, out, iters / 2); }, 3);
+                flop = waves * (iters / 2) * 8 * 2.0 * 16 * 16 * 4;
+                break;
+            case 5:
                 ms = t.best_ms([&] { hipLaunchKernelGGL(mfma_f32_32x32x2_kernel<4>, dim3(blocks), dim3(256), 0, nullptr, out, iters / 4); }, 3);
                 flop = waves * (iters / 4) * 4 * 2.0 * 32 * 32 * 2;
                 break;
