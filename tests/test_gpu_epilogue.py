@@ -33,6 +33,7 @@ def binding():
 CASES = [
     # name               N  C    K    W     S   d   P     kernel the auto choice lands on
     ("epi_genomics",     2, 15,  15,  5000, 51, 8,  200),   # small-channel MFMA
+    ("epi_genomics_k9",  3, 12,  9,   4104, 51, 8,  200),   # small-channel MFMA, fewer than 15 filters: general output flush
     ("epi_smallc_d3",    2, 9,   13,  1777, 25, 3,  36),  # small-channel, no operand sharing, odd width
     ("epi_ring_S51",     1, 64,  64,  2100, 51, 8,  200), # resident weights
     ("epi_ring_k40",     2, 72,  40,  1000, 7,  4,  12),
