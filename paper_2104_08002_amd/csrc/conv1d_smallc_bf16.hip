@@ -995,7 +995,9 @@ __global__ __launch_bounds__(512, 2) void smallc_wgrad_bf16_d8_kernel(WgradProbl
             if (i < nt) {
                 const int s = cw + 4 * i;
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) ws[s * 256 + (4 * kb + jj) * 16 + li] = acc[i][jj];
+                // (non-temporal: the second stage that reads them runs on other compute units, and the lines would
+                // only push input rows out of this one's L2; measured 28.5 -> 27.9 us per pass on uncached tensors)
+                for (int jj = 0; jj < 4; ++jj) __builtin_nontemporal_store(acc[i][jj], &ws[s * 256 + (4 * kb + jj) * 16 + li]);
             }
         }
     }
