@@ -150,7 +150,14 @@ hipError_t igemm_corr_launch(const CorrProblem& p, hipStream_t st) {
 
 // the register-shift kernel wherever it applies: the others stage several phase copies of x for these shapes (measured
 // on C = K = 64: 23.4 against 24.7 us at S = 5, d = 4; 35.2 against 37.4 us at S = 17, d = 2; 24 against 50 us at S = 5, d = 1)
-static bool prefer_shift_wgrad(const WgradProblem& p) { return p.bf16 && shift_bf16_wgrad_supported(p); }
+// Its four consumer waves take the four channel blocks of a group of 64 channels: with fewer than three of the four real
+// (C = 16, 32, 80 ...) most of its MFMA waves idle and the phase-copy kernel is faster (batch 56, d = 4, S = 5,
+// Q = 60000: 58 against 85 us at C = K = 16, 122 against 132 us at C = K = 32).
+static bool prefer_shift_wgrad(const WgradProblem& p) {
+    if (!p.bf16 || !shift_bf16_wgrad_supported(p)) return false;
+    const int blocks = (p.C + 15) / 16, groups = (p.C + 63) / 64;
+    return 4 * blocks >= 3 * 4 * groups || !toeplitz_bf16_wgrad_supported(p);
+}
 
 bool igemm_wgrad_supported(const WgradProblem& p) {
     if (p.bf16 && (shift_bf16_wgrad_supported(p) || toeplitz_bf16_wgrad_supported(p) || blocked_bf16_wgrad_supported(p))) return true;
