@@ -479,10 +479,11 @@ __global__ __launch_bounds__(512, 2) void igemm_ring_bf16_kernel(RgArgs a) {
             }
         };
         // aligned rows only; with bfloat16 output the first two registers already hold the 8 bytes
-        // Non-temporal stores from 17 taps on: measured on C = K = 64 they save 1.1 - 1.5 us per launch there (35.0 -> 33.9 us
-        // at S = 17, 63.9 -> 62.7 us at S = 51) and cost 0.9 - 1.2 us with 5 or 9 taps, where a tile is stored almost as fast
-        // as the store path accepts it.
-        constexpr bool kNtOut = JT >= 5;
+        // Non-temporal stores from 37 taps on: measured on C = K = 64 they save 1.2 us per launch there (63.9 -> 62.7 us at
+        // S = 51).  With fewer taps a tile is stored almost as fast as the store path accepts it, and non-temporal stores cost
+        // 0.9 - 1.2 us at 5 and 9 taps and up to 4 us of 28 at 21 taps when the output is small enough to stay cached
+        // (batch 56, C = K = 32, Q = 5000), against a gain of 1.1 us at 17 and 33 taps on the C = K = 64 sweep.
+        constexpr bool kNtOut = JT >= 13;
         auto store_unit_vec = [&](int fb, int t, const f32x4& v, long idx0, int o) {
             if (16 * fb < mlim && o + 16 * t < a.Wout) {
                 const long idx = idx0 + fb * rowblk + 16 * t;
