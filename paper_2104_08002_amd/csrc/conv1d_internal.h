@@ -200,6 +200,15 @@ __device__ __forceinline__ void epi_store4(const Epilogue& e, float* out, long i
     }
 }
 
+// the same with non-temporal stores, for kernels whose output lines would only push their own input out of L2
+__device__ __forceinline__ void epi_store4_nt(const Epilogue& e, float* out, long idx, epi_f32x4 v) {
+    if (e.out_bf16) {
+        __builtin_nontemporal_store(__builtin_convertvector(v, epi_bf16x4), reinterpret_cast<epi_bf16x4*>(reinterpret_cast<__bf16*>(out) + idx));
+    } else {
+        __builtin_nontemporal_store(v, reinterpret_cast<epi_f32x4*>(out + idx));
+    }
+}
+
 // ---- staging helpers of the bf16 backward-weight kernels: 16-byte pieces of a row, clamped at its ends ----------
 typedef __attribute__((ext_vector_type(4))) unsigned int stage_u32x4;
 

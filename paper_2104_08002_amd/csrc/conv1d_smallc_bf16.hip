@@ -348,7 +348,7 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_bf16_kernel(CorrProblem p,
 #pragma unroll
                 for (int q = 0; q < 8; ++q)
                     if (col_ok && 2 * q + orow < p.M)
-                        epi_store4(p.epi, p.out, base + static_cast<long>(2 * q) * p.Wout + lane_off, epi_apply4(p.epi, v[q], 0.f));
+                        epi_store4_nt(p.epi, p.out, base + static_cast<long>(2 * q) * p.Wout + lane_off, epi_apply4(p.epi, v[q], 0.f));
             }
         } else {
             for (int idx = lane; idx < 16 * T * 16; idx += 64) {
