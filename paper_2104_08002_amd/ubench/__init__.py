@@ -15,7 +15,8 @@ SRC = os.path.join(_HERE, "peaks.hip")
 LIB = os.path.join(_HERE, "libconv1d_ubench.so")
 
 MFMA_SHAPES = {0: "bf16_32x32x16", 1: "fp32_32x32x2", 2: "fp32_16x16x4", 3: "fp32_16x16x4_1wave_4acc",
-               4: "fp32_16x16x4_1wave_8acc", 5: "fp32_32x32x2_1wave_4acc"}
+               4: "fp32_16x16x4_1wave_8acc", 5: "fp32_32x32x2_1wave_4acc", 6: "bf16_16x16x32",
+               7: "bf16_16x16x32_1wave_8acc", 8: "bf16_16x16x32_1wave_13acc"}
 COPY_SIZES_MB = (64, 256, 1024)
 
 

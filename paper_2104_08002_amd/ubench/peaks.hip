@@ -46,6 +46,29 @@ __global__ __launch_bounds__(256) void mfma_f32_32x32x2_kernel(float* out, int i
     out[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// the 16 x 16 x 32 shape the bf16 kernels of the library use (4 accumulator registers per tile instead of 16)
+template <int NACC>
+__global__ __launch_bounds__(256) void mfma_bf16_16x16x32_kernel(float* out, int iters) {
+    bf16x8 a, b;
+    for (int i = 0; i < 8; ++i) {
+        a[i] = static_cast<__bf16>(static_cast<float>((threadIdx.x + i) & 7));
+        b[i] = static_cast<__bf16>(static_cast<float>(i));
+    }
+    typedef __attribute__((ext_vector_type(4))) float acc4;
+    acc4 acc[NACC];
+    for (int j = 0; j < NACC; ++j) acc[j] = acc4{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        // (inline assembly with the accumulator tied to the destination: left to itself the compiler moves these small
+        // accumulators between register files on every trip of the loop, and the loop then measures those moves)
+        for (int j = 0; j < NACC; ++j) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc[j]) : "v"(a), "v"(b));
+    }
+    float s = 0.f;
+    for (int j = 0; j < NACC; ++j)
+        for (int i = 0; i < 4; ++i) s += acc[j][i];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 // the 16 x 16 x 4 shape the FP32 kernels of the library use (4 accumulator registers per tile instead of 16)
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 template <int NACC>
@@ -55,7 +78,7 @@ __global__ __launch_bounds__(256) void mfma_f32_16x16x4_kernel(float* out, int i
     for (int j = 0; j < NACC; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int j = 0; j < NACC; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[j], 0, 0, 0);
+        for (int j = 0; j < NACC; ++j) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc[j]) : "v"(a), "v"(b));
     }
     float s = 0.f;
     for (int j = 0; j < NACC; ++j)
@@ -127,12 +150,13 @@ extern "C" {
 // Sustained dense MFMA rate of the whole GPU in TFLOP/s with 2 waves per SIMD and no memory traffic.
 // shape 0: v_mfma_f32_32x32x16_bf16, 1: v_mfma_f32_32x32x2_f32, 2: v_mfma_f32_16x16x4_f32 (same nominal rate as 1).
 // Shapes 3-5 run ONE wave per SIMD, as the consumer waves of the library's kernels do: 3: 16x16x4 with 4 independent
-// accumulators, 4: 16x16x4 with 8, 5: 32x32x2 with 4.
+// accumulators, 4: 16x16x4 with 8, 5: 32x32x2 with 4.  6: v_mfma_f32_16x16x32_bf16 with 2 waves per SIMD and 4 accumulators,
+// 7: the same with one wave per SIMD and 8 accumulators, 8: one wave per SIMD and 13 accumulators.
 // Returns 0 and writes *tflops, or -1 on a HIP error / unknown shape.
 int conv1d_ubench_mfma_tflops(int shape, double* tflops) {
     const int ncu = num_cus();
     if (ncu <= 0 || !tflops) return -1;
-    const int blocks = shape >= 3 ? ncu : ncu * 2, iters = 20000;  // 1 or 2 blocks of 4 waves per CU
+    const int blocks = (shape >= 3 && shape != 6) ? ncu : ncu * 2, iters = 20000;  // 1 or 2 blocks of 4 waves per CU
     float* out = nullptr;
     if (hipMalloc(&out, static_cast<size_t>(blocks) * 256 * sizeof(float)) != hipSuccess) return -1;
     Timer t;
@@ -161,6 +185,18 @@ int conv1d_ubench_mfma_tflops(int shape, double* tflops) {
             case 5:
                 ms = t.best_ms([&] { hipLaunchKernelGGL(mfma_f32_32x32x2_kernel<4>, dim3(blocks), dim3(256), 0, nullptr, out, iters / 4); }, 3);
                 flop = waves * (iters / 4) * 4 * 2.0 * 32 * 32 * 2;
+                break;
+            case 6:
+                ms = t.best_ms([&] { hipLaunchKernelGGL(mfma_bf16_16x16x32_kernel<4>, dim3(blocks), dim3(256), 0, nullptr, out, iters); }, 3);
+                flop = waves * iters * 4 * 2.0 * 16 * 16 * 32;
+                break;
+            case 7:
+                ms = t.best_ms([&] { hipLaunchKernelGGL(mfma_bf16_16x16x32_kernel<8>, dim3(blocks), dim3(256), 0, nullptr, out, iters); }, 3);
+                flop = waves * iters * 8 * 2.0 * 16 * 16 * 32;
+                break;
+            case 8:
+                ms = t.best_ms([&] { hipLaunchKernelGGL(mfma_bf16_16x16x32_kernel<13>, dim3(blocks), dim3(256), 0, nullptr, out, iters); }, 3);
+                flop = waves * iters * 13 * 2.0 * 16 * 16 * 32;
                 break;
             default: break;
         }
