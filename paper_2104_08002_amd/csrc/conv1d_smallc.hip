@@ -186,15 +186,33 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
         } else if (!consumer && t_begin < t_end) {
             prefetch_set(preA, t_begin);
         }
-        for (int e = tid; e < ncb * nsteps * 64; e += 512) {
-            const int cb = (e >> 6) / nsteps, step = (e >> 6) - cb * nsteps, l = e & 63;
-            const int m = l & 15, r = 16 * cb + 4 * (step % RC) + (l >> 4), s = step / RC;
-            float v = 0.f;
-            if (m < Mb && r < p.R) {
-                const long idx = m * p.w_sm + r * p.w_sr + p.w_s0 + s * p.w_ss;
-                v = raw_in_lds ? raw[idx] : wt[idx];
+        // Entry (channel block cb, step, lane): wave w takes the steps w, w + 8, ... of the sequence over all channel
+        // blocks.  The step counter is wave-uniform and counted, not divided (this loop is most of the time a workgroup
+        // spends before its first MFMA); element offsets fit 32 bits (checked by the host).
+        {
+            const int m = lane & 15, kbl = lane >> 4;
+            const int wsr = static_cast<int>(p.w_sr), wss = static_cast<int>(p.w_ss);
+            const int mbase = m * static_cast<int>(p.w_sm) + static_cast<int>(p.w_s0);
+            int step = wave, cb = 0;
+            while (step >= nsteps) {
+                step -= nsteps;
+                ++cb;
             }
-            wfrag[e] = v;
+            while (cb < ncb) {
+                const int cc = step % RC, s = step / RC;  // (RC is a compile-time constant)
+                const int r = 16 * cb + 4 * cc + kbl;
+                float v = 0.f;
+                if (m < Mb && r < p.R) {
+                    const int idx = mbase + r * wsr + s * wss;
+                    v = raw_in_lds ? raw[idx] : wt[idx];
+                }
+                wfrag[(cb * nsteps + step) * 64 + lane] = v;
+                step += 8;
+                while (step >= nsteps) {
+                    step -= nsteps;
+                    ++cb;
+                }
+            }
         }
         __syncthreads();  // raw copy is dead, wfrag is complete
     }
@@ -356,6 +374,10 @@ CorrF32Plan corr_f32_plan(const CorrProblem& p, bool blocks = false) {
     pl.ok = false;
     if (p.bf16 || (p.M > 16 && !blocks) || cdiv(p.M, 16) > 65535) return pl;
     if (static_cast<long>(p.R) * p.Win >= (1L << 30)) return pl;  // 32-bit element offsets within one sample
+    {  // ... and within the weights this launch reads
+        const auto mag = [](long v) { return v < 0 ? -v : v; };
+        if (16 * mag(p.w_sm) + p.R * mag(p.w_sr) + p.S * mag(p.w_ss) + mag(p.w_s0) >= (1L << 31)) return pl;
+    }
     constexpr int TQ = 4 * kCorrT * 16;
     // more than 16 channels: blocks of 16, reduced one after the other inside the kernel
     pl.ncb = cdiv(p.R, 16);
