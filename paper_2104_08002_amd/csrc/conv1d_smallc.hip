@@ -259,12 +259,13 @@ __global__ __launch_bounds__(512, 2) void smallc_corr_f32_kernel(CorrProblem p, 
 #pragma unroll
                 for (int j = 0; j < T; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(b[cc][j], a[cc], acc[j], 0, 0, 0);
         };
-        // the LDS reads of the next tap are spread between the MFMAs of the current one
+        // the LDS reads of the next tap are spread between the MFMAs of the current one, an MFMA first (read first
+        // measured 234.6 against 230.4 us on the 51-tap genomics layer: the tap's first MFMA then waits behind a read)
         auto interleave = [&]() {
 #pragma unroll
             for (int i = 0; i < RC * T; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
             __builtin_amdgcn_sched_group_barrier(0x100, RC, 0);
         };
